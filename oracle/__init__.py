@@ -1,0 +1,194 @@
+"""CPU f64 oracle for property-annotated matrix-chain products.
+
+TEST INFRASTRUCTURE ONLY: the tests, the smoke check and the benchmark's CPU
+baseline are the only callers.  Nothing here is shared with, or imported by,
+the GPU library, and the GPU library never falls back to it.
+
+Thin ctypes layer over oracle.c; every function documents the passage of the
+paper (MOM: Matrix Operations in MLIR) that it states.  Properties are the
+integers 0 general, 1 lowerTri, 2 upperTri, 3 Identity (Sec. 2).
+"""
+import ctypes
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+from .build import build as _build
+
+GENERAL, LOWER_TRI, UPPER_TRI, IDENTITY = 0, 1, 2, 3
+
+_lib = ctypes.CDLL(_build())
+
+_i64p = ctypes.POINTER(ctypes.c_int64)
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_f64p = ctypes.POINTER(ctypes.c_double)
+_fpp = ctypes.POINTER(ctypes.c_void_p)
+
+_lib.oracle_count_mults.restype = ctypes.c_uint64
+_lib.oracle_count_mults.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                    ctypes.c_int32, ctypes.c_int32]
+_lib.oracle_plan_bruteforce.restype = ctypes.c_int
+_lib.oracle_plan_bruteforce.argtypes = [ctypes.c_int32, _i64p, _i32p, ctypes.c_int32,
+                                        ctypes.POINTER(ctypes.c_uint64), _i32p, _i32p, _i32p,
+                                        ctypes.POINTER(ctypes.c_int64)]
+_lib.oracle_tree_cost.restype = ctypes.c_int
+_lib.oracle_tree_cost.argtypes = [ctypes.c_int32, _i64p, _i32p, _i32p,
+                                  ctypes.POINTER(ctypes.c_uint64), _i32p]
+_lib.oracle_eval_dense.restype = ctypes.c_int
+_lib.oracle_eval_dense.argtypes = [ctypes.c_int32, _i64p, _i32p, _fpp, _f64p]
+_lib.oracle_eval_rows.restype = ctypes.c_int
+_lib.oracle_eval_rows.argtypes = [ctypes.c_int32, _i64p, _i32p, _fpp, ctypes.c_int32, _i64p, _f64p]
+_lib.oracle_eval_plan.restype = ctypes.c_int
+_lib.oracle_eval_plan.argtypes = [ctypes.c_int32, _i64p, _i32p, _fpp, _i32p, _f64p, _i32p]
+_lib.oracle_max_threads.restype = ctypes.c_int
+
+
+def _dims(dims) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(dims, dtype=np.int64))
+
+
+def _props(props) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(props, dtype=np.int32))
+
+
+def _factor_ptrs(dims: np.ndarray, props: np.ndarray, factors: Sequence[Optional[np.ndarray]]):
+    """Host f32 row-major buffers -> array of pointers (Identity entries may be None)."""
+    keep = []
+    ptrs = (ctypes.c_void_p * len(props))()
+    for t, p in enumerate(props):
+        f = factors[t]
+        if f is None:
+            if p != IDENTITY:
+                raise ValueError("factor %d has no buffer but is not an Identity" % t)
+            ptrs[t] = None
+            continue
+        a = np.ascontiguousarray(np.asarray(f, dtype=np.float32))
+        if a.shape != (dims[t], dims[t + 1]):
+            raise ValueError("factor %d has shape %s, expected %s" % (t, a.shape, (dims[t], dims[t + 1])))
+        keep.append(a)
+        ptrs[t] = a.ctypes.data
+    return ptrs, keep
+
+
+def max_threads() -> int:
+    return int(_lib.oracle_max_threads())
+
+
+def count_mults(m: int, k: int, n: int, pX: int, pY: int) -> int:
+    """Scalar products of X(m x k)*Y(k x n) with no structurally-zero operand, counted one
+    by one in a triple loop (the planner's cost unit, Sec. 2 Transformations)."""
+    return int(_lib.oracle_count_mults(m, k, n, pX, pY))
+
+
+def plan_bruteforce(dims, props, elide: bool = True) -> dict:
+    """Minimum-multiplication parenthesisation by enumerating every binary tree
+    (Sec. 2: variadic Mul -> binary products with an optimal parenthesisation; matrix-chain
+    reordering generalised to properties; identity simplification).
+
+    Returns cost, n_eff, splits (preorder, original factor indices), result_prop, num_trees.
+    Ties go to the lexicographically smallest preorder split list."""
+    d, p = _dims(dims), _props(props)
+    n = len(p)
+    assert len(d) == n + 1
+    cost = ctypes.c_uint64()
+    neff = ctypes.c_int32()
+    rprop = ctypes.c_int32()
+    ntrees = ctypes.c_int64()
+    splits = np.zeros(max(n, 1), dtype=np.int32)
+    rc = _lib.oracle_plan_bruteforce(n, d.ctypes.data_as(_i64p), p.ctypes.data_as(_i32p), int(elide),
+                                     ctypes.byref(cost), ctypes.byref(neff),
+                                     splits.ctypes.data_as(_i32p), ctypes.byref(rprop),
+                                     ctypes.byref(ntrees))
+    if rc != 0:
+        raise OverflowError("cost does not fit in 64 bits")
+    k = max(neff.value - 1, 0)
+    return {"cost": int(cost.value), "n_eff": int(neff.value), "splits": [int(x) for x in splits[:k]],
+            "result_prop": int(rprop.value), "num_trees": int(ntrees.value)}
+
+
+def tree_cost(dims, props, splits) -> Tuple[int, int]:
+    """(cost in scalar multiplications, result property) of one given tree."""
+    d, p = _dims(dims), _props(props)
+    s = np.ascontiguousarray(np.asarray(list(splits) + [0], dtype=np.int32))
+    cost = ctypes.c_uint64()
+    rprop = ctypes.c_int32()
+    rc = _lib.oracle_tree_cost(len(p), d.ctypes.data_as(_i64p), p.ctypes.data_as(_i32p),
+                               s.ctypes.data_as(_i32p), ctypes.byref(cost), ctypes.byref(rprop))
+    if rc == 1:
+        raise OverflowError("cost does not fit in 64 bits")
+    if rc == 2:
+        raise ValueError("malformed split list")
+    return int(cost.value), int(rprop.value)
+
+
+def survivors(props) -> List[int]:
+    """Original indices of the factors left after identity simplification (A*I -> A)."""
+    return [i for i, p in enumerate(props) if p != IDENTITY]
+
+
+def plan_string(props, splits) -> str:
+    """Parenthesised form of a preorder split list, original indices, e.g. '(0 (2 (3 4)))'."""
+    surv = survivors(props)
+    if not surv:
+        return "I"
+    it = iter(splits)
+
+    def rec(lo: int, hi: int) -> str:
+        if lo == hi:
+            return str(surv[lo])
+        s = surv.index(next(it))
+        return "(" + rec(lo, s) + " " + rec(s + 1, hi) + ")"
+
+    return rec(0, len(surv) - 1)
+
+
+def left_to_right_splits(props) -> List[int]:
+    """Preorder splits of (((A0 A1) A2) ...), the paper's 'initial parenthesization' (Sec. 4)."""
+    surv = survivors(props)
+    return [surv[i] for i in range(len(surv) - 2, -1, -1)]
+
+
+def eval_dense(dims, props, factors) -> np.ndarray:
+    """The chain product by its plain definition: dense f64 triple loops, left to right,
+    Identity materialised as eye, no property logic (Sec. 2, bufferization and Types)."""
+    d, p = _dims(dims), _props(props)
+    ptrs, keep = _factor_ptrs(d, p, factors)
+    out = np.zeros((d[0], d[-1]), dtype=np.float64)
+    rc = _lib.oracle_eval_dense(len(p), d.ctypes.data_as(_i64p), p.ctypes.data_as(_i32p),
+                                ctypes.cast(ptrs, _fpp), out.ctypes.data_as(_f64p))
+    if rc != 0:
+        raise ValueError("oracle_eval_dense failed: %d" % rc)
+    del keep
+    return out
+
+
+def eval_rows(dims, props, factors, rows) -> np.ndarray:
+    """Selected rows of the dense chain product: A_0[r,:] pushed through the other factors."""
+    d, p = _dims(dims), _props(props)
+    ptrs, keep = _factor_ptrs(d, p, factors)
+    r = np.ascontiguousarray(np.asarray(rows, dtype=np.int64))
+    out = np.zeros((len(r), d[-1]), dtype=np.float64)
+    rc = _lib.oracle_eval_rows(len(p), d.ctypes.data_as(_i64p), p.ctypes.data_as(_i32p),
+                               ctypes.cast(ptrs, _fpp), len(r), r.ctypes.data_as(_i64p),
+                               out.ctypes.data_as(_f64p))
+    if rc != 0:
+        raise ValueError("oracle_eval_rows failed: %d" % rc)
+    del keep
+    return out
+
+
+def eval_plan(dims, props, factors, splits) -> Tuple[np.ndarray, int]:
+    """Evaluate along a given tree with loops restricted by the operand properties, f64.
+    Returns (dense result, result property)."""
+    d, p = _dims(dims), _props(props)
+    ptrs, keep = _factor_ptrs(d, p, factors)
+    s = np.ascontiguousarray(np.asarray(list(splits) + [0], dtype=np.int32))
+    out = np.zeros((d[0], d[-1]), dtype=np.float64)
+    rprop = ctypes.c_int32()
+    rc = _lib.oracle_eval_plan(len(p), d.ctypes.data_as(_i64p), p.ctypes.data_as(_i32p),
+                               ctypes.cast(ptrs, _fpp), s.ctypes.data_as(_i32p),
+                               out.ctypes.data_as(_f64p), ctypes.byref(rprop))
+    if rc != 0:
+        raise ValueError("malformed split list")
+    del keep
+    return out, int(rprop.value)

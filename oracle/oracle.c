@@ -1,0 +1,452 @@
+/*
+ * CPU oracle for property-annotated matrix-chain products (MOM / Linnea dialect).
+ *
+ * THIS FILE IS TEST INFRASTRUCTURE.  It is the slow, plain statement of what the
+ * chain evaluator must compute, used only by the test-suite, the smoke check and
+ * the CPU-baseline leg of the benchmark.  It shares no code, header, table or
+ * helper with the GPU library and nothing in the product path may call it.
+ *
+ * What it states (paper sections in brackets):
+ *   - a chain  A_0 * A_1 * ... * A_{n-1}  of f32 matrices, each carrying one
+ *     property: general, lowerTri, upperTri or Identity           [Sec. 2, "Matrix
+ *     Attribute" and "Types: Matrix, Term and Identity"]
+ *   - memory of a triangular matrix is a plain dense row-major buffer whose
+ *     other half holds zeros; the diagonal is stored             [Sec. 2, bufferization]
+ *   - Identity is square with ones on the diagonal, A*I = A, I*I = I  [Sec. 2, Types]
+ *   - the variadic product is rewritten into binary products whose
+ *     parenthesisation minimises the number of scalar multiplications, taking
+ *     the properties of operands and intermediates into account
+ *                                      [Sec. 2, "Operations" and "Transformations"]
+ *
+ * All floating point work is done in double precision.
+ *
+ * Pins (tests/test_oracle_*.py): the paper's 5x5 lowerTri*lowerTri example with
+ * fill value 1 (closed form i-j+1), the Sec. 4 chain 800x1100x900x1200x100 and its
+ * two parenthesisations, numpy.matmul in f64 on general chains, counted
+ * multiplications against the closed-form costs, identity rules bit-exactly,
+ * structure invariants, agreement of every parenthesisation on tiny inputs.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { P_GENERAL = 0, P_LOWER = 1, P_UPPER = 2, P_IDENTITY = 3 };
+
+/* ------------------------------------------------------------------------ */
+/* Structure of a property: is position (i,j) allowed to be non-zero?       */
+/* lowerTri: zeros above the diagonal; upperTri: zeros below it; the        */
+/* diagonal itself is stored data.  [Sec. 2, bufferization remark]          */
+static int structurally_nonzero(int prop, int64_t i, int64_t j)
+{
+    switch (prop) {
+    case P_LOWER:    return j <= i;
+    case P_UPPER:    return j >= i;
+    case P_IDENTITY: return j == i;
+    default:         return 1;
+    }
+}
+
+/* Number of scalar products X[i][t]*Y[t][j] in which neither operand is a
+ * structural zero, counted one by one.  This is the planner's cost unit
+ * ("number of scalar multiplications", Sec. 2 Transformations) written as
+ * its definition; the closed forms below are checked against it.           */
+uint64_t oracle_count_mults(int64_t m, int64_t k, int64_t n, int32_t pX, int32_t pY)
+{
+    uint64_t c = 0;
+    for (int64_t i = 0; i < m; ++i)
+        for (int64_t t = 0; t < k; ++t)
+            for (int64_t j = 0; j < n; ++j)
+                if (structurally_nonzero(pX, i, t) && structurally_nonzero(pY, t, j))
+                    ++c;
+    return c;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Property of a product of two operands.  Identity is neutral; equal       */
+/* triangles keep their triangle; everything else is general.               */
+static int product_property(int pX, int pY)
+{
+    if (pX == P_IDENTITY) return pY;
+    if (pY == P_IDENTITY) return pX;
+    if (pX == pY && (pX == P_LOWER || pX == P_UPPER)) return pX;
+    return P_GENERAL;
+}
+
+typedef unsigned __int128 u128;
+
+/* Closed-form count of the non-structurally-zero scalar products of
+ * X (m x k, pX) times Y (k x n, pY).  A product with an Identity operand is
+ * no computation at all (A*I -> A).                                        */
+static u128 product_cost(int64_t m, int64_t k, int64_t n, int pX, int pY)
+{
+    u128 M = (u128)m, K = (u128)k, N = (u128)n;
+    int triX = (pX == P_LOWER || pX == P_UPPER);
+    int triY = (pY == P_LOWER || pY == P_UPPER);
+    if (pX == P_IDENTITY || pY == P_IDENTITY) return 0;
+    if (!triX && !triY) return M * K * N;
+    if (triX && !triY)  return N * (M * (M + 1) / 2);          /* m == k */
+    if (!triX && triY)  return M * (N * (N + 1) / 2);          /* k == n */
+    if (pX == pY)       return N * (N + 1) * (N + 2) / 6;      /* tri*tri, same side */
+    return N * (N + 1) * (2 * N + 1) / 6;                      /* L*U or U*L */
+}
+
+/* ------------------------------------------------------------------------ */
+/* Brute-force search over every parenthesisation.                          */
+/*                                                                          */
+/* A binary tree over factors lo..hi is written as its preorder list of     */
+/* splits: the root's split s (left = lo..s, right = s+1..hi), then the     */
+/* left subtree's list, then the right subtree's.  Positions index the      */
+/* chain handed to the enumerator.                                          */
+
+typedef struct { int64_t rows, cols; int prop; u128 cost; } subresult_t;
+
+/* Cost a complete tree bottom-up; *pos walks the preorder split list. */
+static subresult_t cost_tree(const int64_t *dims, const int32_t *props,
+                             int lo, int hi, const int32_t *splits, int *pos)
+{
+    subresult_t r;
+    if (lo == hi) {
+        r.rows = dims[lo]; r.cols = dims[lo + 1]; r.prop = props[lo]; r.cost = 0;
+        return r;
+    }
+    int s = splits[(*pos)++];
+    subresult_t a = cost_tree(dims, props, lo, s, splits, pos);
+    subresult_t b = cost_tree(dims, props, s + 1, hi, splits, pos);
+    r.rows = a.rows; r.cols = b.cols;
+    r.prop = product_property(a.prop, b.prop);
+    r.cost = a.cost + b.cost + product_cost(a.rows, a.cols, b.cols, a.prop, b.prop);
+    return r;
+}
+
+/* All trees over lo..hi, each as (hi-lo) ints, concatenated; returns count. */
+static int64_t all_trees(int lo, int hi, int32_t **out)
+{
+    int len = hi - lo;                       /* number of splits in one tree */
+    if (len == 0) { *out = NULL; return 1; } /* one (empty) tree */
+    int64_t cap = 16, cnt = 0;
+    int32_t *buf = (int32_t *)malloc(sizeof(int32_t) * cap * len);
+    for (int s = lo; s < hi; ++s) {
+        int32_t *L, *R;
+        int64_t nl = all_trees(lo, s, &L), nr = all_trees(s + 1, hi, &R);
+        int ll = s - lo, rl = hi - s - 1;
+        for (int64_t a = 0; a < nl; ++a)
+            for (int64_t b = 0; b < nr; ++b) {
+                if (cnt == cap) { cap *= 2; buf = (int32_t *)realloc(buf, sizeof(int32_t) * cap * len); }
+                int32_t *t = buf + cnt * len;
+                t[0] = s;
+                if (ll) memcpy(t + 1, L + a * ll, sizeof(int32_t) * ll);
+                if (rl) memcpy(t + 1 + ll, R + b * rl, sizeof(int32_t) * rl);
+                ++cnt;
+            }
+        free(L); free(R);
+    }
+    *out = buf;
+    return cnt;
+}
+
+static int lex_less(const int32_t *a, const int32_t *b, int len)
+{
+    for (int i = 0; i < len; ++i) { if (a[i] != b[i]) return a[i] < b[i]; }
+    return 0;
+}
+
+/*
+ * Minimum-multiplication parenthesisation by exhaustive enumeration.
+ *
+ * elide != 0: Identity factors are dropped first (A*I -> A, I*I = I) and the
+ *             trees range over the survivors.
+ * elide == 0: every factor stays in the chain and a product with an Identity
+ *             operand costs nothing (used to cross-check the elision rule).
+ *
+ * Outputs: *cost (minimum), *n_eff (factors the trees range over),
+ * out_splits[n_eff-1] = preorder splits of the minimiser, expressed as ORIGINAL
+ * factor indices (the index of the last factor of each left subtree); among
+ * equal-cost trees the lexicographically smallest preorder list wins.
+ * *result_prop = property of the whole product, *num_trees = trees enumerated.
+ * Returns 0, or 1 when a cost does not fit in 64 bits.
+ */
+int oracle_plan_bruteforce(int32_t n, const int64_t *dims, const int32_t *props, int32_t elide,
+                           uint64_t *cost, int32_t *n_eff, int32_t *out_splits,
+                           int32_t *result_prop, int64_t *num_trees)
+{
+    int64_t *d = (int64_t *)malloc(sizeof(int64_t) * (n + 1));
+    int32_t *p = (int32_t *)malloc(sizeof(int32_t) * n);
+    int32_t *orig = (int32_t *)malloc(sizeof(int32_t) * n);
+    int m = 0;
+    for (int i = 0; i < n; ++i) {
+        if (elide && props[i] == P_IDENTITY) continue;
+        d[m] = dims[i]; p[m] = props[i]; orig[m] = i; ++m;
+    }
+    d[m] = dims[n];
+    *n_eff = m;
+    *num_trees = 0;
+    if (m == 0) {                     /* every factor was an Identity: I*I = I */
+        *cost = 0; *result_prop = P_IDENTITY;
+        free(d); free(p); free(orig); return 0;
+    }
+    int len = m - 1;
+    int32_t *trees;
+    int64_t cnt = all_trees(0, m - 1, &trees);
+    u128 best = 0; int64_t best_idx = -1; int prop = p[0];
+    for (int64_t t = 0; t < cnt; ++t) {
+        int pos = 0;
+        subresult_t r = cost_tree(d, p, 0, m - 1, trees ? trees + t * len : NULL, &pos);
+        prop = r.prop;
+        if (best_idx < 0 || r.cost < best ||
+            (r.cost == best && lex_less(trees + t * len, trees + best_idx * len, len))) {
+            best = r.cost; best_idx = t;
+        }
+    }
+    for (int i = 0; i < len; ++i) out_splits[i] = orig[trees[best_idx * len + i]];
+    *result_prop = prop;
+    *num_trees = cnt;
+    int overflow = (best >> 64) != 0;
+    *cost = (uint64_t)best;
+    free(trees); free(d); free(p); free(orig);
+    return overflow;
+}
+
+/*
+ * Cost of one given tree.  `splits` is a preorder list over the chain with
+ * Identity factors removed, in ORIGINAL factor indices.  Returns 0, 1 on
+ * 64-bit overflow, 2 when a split is not a surviving factor inside its range.
+ */
+int oracle_tree_cost(int32_t n, const int64_t *dims, const int32_t *props,
+                     const int32_t *splits, uint64_t *cost, int32_t *result_prop)
+{
+    int64_t *d = (int64_t *)malloc(sizeof(int64_t) * (n + 1));
+    int32_t *p = (int32_t *)malloc(sizeof(int32_t) * n);
+    int32_t *where = (int32_t *)malloc(sizeof(int32_t) * n);   /* original -> elided position */
+    int m = 0, rc = 0;
+    for (int i = 0; i < n; ++i) {
+        where[i] = -1;
+        if (props[i] == P_IDENTITY) continue;
+        d[m] = dims[i]; p[m] = props[i]; where[i] = m; ++m;
+    }
+    d[m] = dims[n];
+    if (m == 0) { *cost = 0; *result_prop = P_IDENTITY; goto done; }
+    {
+        int32_t *s = (int32_t *)malloc(sizeof(int32_t) * (m > 1 ? m - 1 : 1));
+        for (int i = 0; i + 1 < m; ++i) {
+            if (splits[i] < 0 || splits[i] >= n || where[splits[i]] < 0) { rc = 2; }
+            else s[i] = where[splits[i]];
+        }
+        if (rc == 0) {
+            /* validate ranges while walking */
+            int stack_lo[64], stack_hi[64], sp = 0, pos = 0;
+            stack_lo[0] = 0; stack_hi[0] = m - 1; sp = 1;
+            while (sp > 0 && rc == 0) {
+                int lo = stack_lo[sp - 1], hi = stack_hi[sp - 1]; --sp;
+                if (lo == hi) continue;
+                int k = s[pos++];
+                if (k < lo || k >= hi) { rc = 2; break; }
+                /* preorder: left first, so push right then left */
+                stack_lo[sp] = k + 1; stack_hi[sp] = hi; ++sp;
+                stack_lo[sp] = lo;    stack_hi[sp] = k;  ++sp;
+            }
+        }
+        if (rc == 0) {
+            int pos = 0;
+            subresult_t r = cost_tree(d, p, 0, m - 1, s, &pos);
+            *result_prop = r.prop;
+            if (r.cost >> 64) rc = 1;
+            *cost = (uint64_t)r.cost;
+        }
+        free(s);
+    }
+done:
+    free(d); free(p); free(where);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Values.                                                                   */
+
+/* Entry (i,j) of factor t, promoted to double.  An Identity factor has no   */
+/* buffer: it is the matrix with ones on the diagonal [Sec. 2, Types].       */
+static double factor_entry(const float *const *factors, const int64_t *dims, const int32_t *props,
+                           int t, int64_t i, int64_t j)
+{
+    if (props[t] == P_IDENTITY) return i == j ? 1.0 : 0.0;
+    return (double)factors[t][i * dims[t + 1] + j];
+}
+
+/*
+ * The plain definition: every factor materialised as the dense matrix it is
+ * (zeros of triangular factors are whatever the buffers hold - the input
+ * generator enforces them), Identity as eye, and the chain multiplied left to
+ * right with the textbook triple loop  C[i][j] = sum_k A[i][k] * B[k][j].
+ * No property logic.  out: dims[0] x dims[n] doubles, row-major.
+ */
+int oracle_eval_dense(int32_t n, const int64_t *dims, const int32_t *props,
+                      const float *const *factors, double *out)
+{
+    if (n <= 0) return 1;
+    int64_t rows = dims[0], cols = dims[1];
+    double *acc = (double *)malloc(sizeof(double) * rows * cols);
+    for (int64_t i = 0; i < rows; ++i)
+        for (int64_t j = 0; j < cols; ++j)
+            acc[i * cols + j] = factor_entry(factors, dims, props, 0, i, j);
+    for (int t = 1; t < n; ++t) {
+        int64_t k = dims[t], nc = dims[t + 1];
+        double *b = (double *)malloc(sizeof(double) * k * nc);
+        for (int64_t i = 0; i < k; ++i)
+            for (int64_t j = 0; j < nc; ++j)
+                b[i * nc + j] = factor_entry(factors, dims, props, t, i, j);
+        double *c = (double *)calloc((size_t)(rows * nc), sizeof(double));
+        #pragma omp parallel for schedule(static)
+        for (int64_t i = 0; i < rows; ++i)
+            for (int64_t kk = 0; kk < k; ++kk) {
+                double a = acc[i * k + kk];
+                for (int64_t j = 0; j < nc; ++j)
+                    c[i * nc + j] += a * b[kk * nc + j];
+            }
+        free(acc); free(b);
+        acc = c; cols = nc;
+    }
+    memcpy(out, acc, sizeof(double) * rows * cols);
+    free(acc);
+    return 0;
+}
+
+/*
+ * Selected rows of the chain product, for sizes where the whole product is
+ * out of reach on a CPU: row r of A_0*A_1*...*A_{n-1} is the row vector
+ * A_0[r,:] pushed through the remaining factors one after the other,
+ * w[j] = sum_k v[k] * A_t[k][j].  Same plain definition, no property logic.
+ * out: nrows x dims[n] doubles.
+ */
+int oracle_eval_rows(int32_t n, const int64_t *dims, const int32_t *props,
+                     const float *const *factors, int32_t nrows, const int64_t *row_idx, double *out)
+{
+    if (n <= 0) return 1;
+    int64_t widest = 0;
+    for (int t = 0; t <= n; ++t) if (dims[t] > widest) widest = dims[t];
+    #pragma omp parallel for schedule(dynamic, 1)
+    for (int r = 0; r < nrows; ++r) {
+        double *v = (double *)malloc(sizeof(double) * widest);
+        double *w = (double *)malloc(sizeof(double) * widest);
+        for (int64_t j = 0; j < dims[1]; ++j)
+            v[j] = factor_entry(factors, dims, props, 0, row_idx[r], j);
+        for (int t = 1; t < n; ++t) {
+            int64_t k = dims[t], nc = dims[t + 1];
+            for (int64_t j = 0; j < nc; ++j) w[j] = 0.0;
+            for (int64_t kk = 0; kk < k; ++kk) {
+                double a = v[kk];
+                for (int64_t j = 0; j < nc; ++j)
+                    w[j] += a * factor_entry(factors, dims, props, t, kk, j);
+            }
+            double *tmp = v; v = w; w = tmp;
+        }
+        memcpy(out + (int64_t)r * dims[n], v, sizeof(double) * dims[n]);
+        free(v); free(w);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Evaluation along a given tree with loops restricted by the properties:   */
+/* exactly the scalar products the cost model counts are executed.          */
+
+typedef struct { double *a; int64_t rows, cols; int prop; } dmat_t;
+
+static void k_range(int prop, int64_t i, int64_t k, int64_t *lo, int64_t *hi)   /* t with X[i][t] != 0 */
+{
+    *lo = 0; *hi = k;
+    if (prop == P_LOWER) *hi = i + 1;
+    if (prop == P_UPPER) *lo = i;
+}
+
+static void j_range(int prop, int64_t t, int64_t n, int64_t *lo, int64_t *hi)   /* j with Y[t][j] != 0 */
+{
+    *lo = 0; *hi = n;
+    if (prop == P_LOWER) *hi = t + 1;
+    if (prop == P_UPPER) *lo = t;
+}
+
+static dmat_t eval_tree(const int64_t *d, const int32_t *p, const float *const *f,
+                        int lo, int hi, const int32_t *splits, int *pos)
+{
+    dmat_t r;
+    if (lo == hi) {                                /* leaf: promote, reading only the structure */
+        r.rows = d[lo]; r.cols = d[lo + 1]; r.prop = p[lo];
+        r.a = (double *)calloc((size_t)(r.rows * r.cols), sizeof(double));
+        for (int64_t i = 0; i < r.rows; ++i)
+            for (int64_t j = 0; j < r.cols; ++j)
+                if (structurally_nonzero(r.prop, i, j))
+                    r.a[i * r.cols + j] = (double)f[lo][i * r.cols + j];
+        return r;
+    }
+    int s = splits[(*pos)++];
+    dmat_t X = eval_tree(d, p, f, lo, s, splits, pos);
+    dmat_t Y = eval_tree(d, p, f, s + 1, hi, splits, pos);
+    r.rows = X.rows; r.cols = Y.cols; r.prop = product_property(X.prop, Y.prop);
+    r.a = (double *)calloc((size_t)(r.rows * r.cols), sizeof(double));
+    int64_t K = X.cols, N = Y.cols;
+    #pragma omp parallel for schedule(dynamic, 8)
+    for (int64_t i = 0; i < X.rows; ++i) {
+        int64_t t0, t1;
+        k_range(X.prop, i, K, &t0, &t1);
+        for (int64_t t = t0; t < t1; ++t) {
+            double a = X.a[i * K + t];
+            int64_t j0, j1;
+            j_range(Y.prop, t, N, &j0, &j1);
+            for (int64_t j = j0; j < j1; ++j)
+                r.a[i * N + j] += a * Y.a[t * N + j];
+        }
+    }
+    free(X.a); free(Y.a);
+    return r;
+}
+
+/*
+ * Evaluate the chain along the tree `splits` (preorder, ORIGINAL factor
+ * indices, over the chain with Identity factors removed).  out receives the
+ * dense dims[0] x dims[n] result (zeros outside the triangle of a triangular
+ * result; the identity matrix when every factor is an Identity).
+ * Returns 0, or 2 for a malformed split list.
+ */
+int oracle_eval_plan(int32_t n, const int64_t *dims, const int32_t *props,
+                     const float *const *factors, const int32_t *splits,
+                     double *out, int32_t *result_prop)
+{
+    uint64_t cost; int32_t rp;
+    int rc = oracle_tree_cost(n, dims, props, splits, &cost, &rp);
+    if (rc == 2) return 2;
+    *result_prop = rp;
+    int64_t *d = (int64_t *)malloc(sizeof(int64_t) * (n + 1));
+    int32_t *p = (int32_t *)malloc(sizeof(int32_t) * n);
+    const float **f = (const float **)malloc(sizeof(float *) * n);
+    int32_t *where = (int32_t *)malloc(sizeof(int32_t) * n);
+    int m = 0;
+    for (int i = 0; i < n; ++i) {
+        where[i] = -1;
+        if (props[i] == P_IDENTITY) continue;
+        d[m] = dims[i]; p[m] = props[i]; f[m] = factors[i]; where[i] = m; ++m;
+    }
+    d[m] = dims[n];
+    if (m == 0) {
+        int64_t r = dims[0];
+        for (int64_t i = 0; i < r; ++i)
+            for (int64_t j = 0; j < r; ++j) out[i * r + j] = (i == j) ? 1.0 : 0.0;
+    } else {
+        int32_t *s = (int32_t *)malloc(sizeof(int32_t) * m);
+        for (int i = 0; i + 1 < m; ++i) s[i] = where[splits[i]];
+        int pos = 0;
+        dmat_t r = eval_tree(d, p, f, 0, m - 1, s, &pos);
+        memcpy(out, r.a, sizeof(double) * r.rows * r.cols);
+        free(r.a); free(s);
+    }
+    free(d); free(p); free((void *)f); free(where);
+    return 0;
+}
+
+int oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

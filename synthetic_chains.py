@@ -1,0 +1,79 @@
+"""Seeded synthetic inputs for property-annotated matrix chains.
+
+Shared by the tests, the benchmark, the smoke check and the CPU oracle's callers.
+This module holds no arithmetic of the method: it only draws uniform[-1, 1) f32
+entries from a seed and writes the zeros (or the unit diagonal) that a factor's
+property prescribes, which is how the paper's Fill operation initialises an
+algebraic object "according to its properties" (Sec. 2, Table 1).
+
+Properties: 0 general, 1 lowerTri (zeros above the diagonal), 2 upperTri (zeros below
+the diagonal), 3 Identity (no buffer at all).  The diagonal of a triangular factor is
+ordinary data.
+"""
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import torch
+
+GENERAL, LOWER_TRI, UPPER_TRI, IDENTITY = 0, 1, 2, 3
+
+
+@dataclass(frozen=True)
+class ChainConfig:
+    """One workload: factor t is dims[t] x dims[t+1] with property props[t]."""
+    name: str
+    number: int                 # 1-based workload number, also the seed family
+    dims: Sequence[int]
+    props: Sequence[int]
+    batch: int = 0              # 0 = a single chain; >0 = that many independent chains
+
+
+CONFIGS = {
+    # tiny chain: lowerTri 64x64, general 64x32, general 32x128
+    "tiny": ChainConfig("tiny", 1, (64, 64, 32, 128), (LOWER_TRI, GENERAL, GENERAL)),
+    # one triangular-times-general product, n = 4096
+    "trmm4096": ChainConfig("trmm4096", 2, (4096, 4096, 4096), (LOWER_TRI, GENERAL)),
+    # order-sensitive chain of five general factors
+    "general5": ChainConfig("general5", 3, (8192, 512, 8192, 64, 4096, 2048), (GENERAL,) * 5),
+    # L1 * I * L2 * U * G
+    "mixed5": ChainConfig("mixed5", 4, (8192, 8192, 8192, 8192, 8192, 1024),
+                          (LOWER_TRI, IDENTITY, LOWER_TRI, UPPER_TRI, GENERAL)),
+    # 4096 independent chains L * G * U of 32x32 factors
+    "batched32": ChainConfig("batched32", 5, (32, 32, 32, 32), (LOWER_TRI, GENERAL, UPPER_TRI),
+                             batch=4096),
+}
+
+
+def factor_seed(config_number: int, factor_index: int) -> int:
+    return 1000 * config_number + factor_index
+
+
+def make_factor(rows: int, cols: int, prop: int, seed: int, batch: int = 0) -> Optional[torch.Tensor]:
+    """Uniform[-1, 1) f32 matrix (or [batch, rows, cols] stack) on the CPU with the zeros of
+    `prop` written; None for an Identity factor, which has no buffer."""
+    if prop == IDENTITY:
+        return None
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    shape = (batch, rows, cols) if batch > 0 else (rows, cols)
+    a = torch.rand(shape, generator=g, dtype=torch.float32) * 2.0 - 1.0
+    if prop == LOWER_TRI:
+        a = torch.tril(a)
+    elif prop == UPPER_TRI:
+        a = torch.triu(a)
+    elif prop != GENERAL:
+        raise ValueError("unknown property %r" % (prop,))
+    return a.contiguous()
+
+
+def make_chain(dims: Sequence[int], props: Sequence[int], seed_family: int,
+               batch: int = 0) -> List[Optional[torch.Tensor]]:
+    """All factors of one chain; factor t is drawn from seed 1000*seed_family + t."""
+    assert len(dims) == len(props) + 1
+    return [make_factor(dims[t], dims[t + 1], props[t], factor_seed(seed_family, t), batch)
+            for t in range(len(props))]
+
+
+def make_config(name: str) -> List[Optional[torch.Tensor]]:
+    c = CONFIGS[name]
+    return make_chain(c.dims, c.props, c.number, c.batch)
