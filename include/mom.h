@@ -1,0 +1,154 @@
+/*
+ * mom.h - C ABI of the MI355X (gfx950) evaluator for property-annotated matrix chains.
+ *
+ * The library evaluates the paper's variadic Mul (MOM: Matrix Operations in MLIR, Sec. 2,
+ * "Operations"): a product A_0 * A_1 * ... * A_{n-1} of f32 matrices, each a Linnea Matrix
+ * type with static dimensions and one property (Sec. 2, "Matrix Attribute", "Types").  As the
+ * paper's transformations prescribe (Sec. 2, "Transformations"), Identity factors are
+ * simplified away (A*I -> A, I*I = I), the properties of intermediate results are inferred,
+ * and the chain is rewritten into binary products whose parenthesisation minimises the number
+ * of scalar multiplications, counted with the structural zeros of the operands left out.
+ * Each binary product then runs as one HIP kernel that skips the tiles a property makes zero;
+ * this realises the non-rectangular iteration space that Sec. 5 leaves as future work.
+ *
+ * Conventions
+ *   - All matrices are dense, row-major f32 (the paper's memref materialisation, Sec. 2).
+ *     Factor t has dims[t] rows and dims[t+1] columns.
+ *   - lowerTri: entries above the diagonal are zero; upperTri: entries below it are zero; the
+ *     diagonal is stored data.  The library never READS the zero half of a triangular factor:
+ *     only the triangle defines the value.  Identity factors have no buffer.
+ *   - lowerTri, upperTri and Identity factors must be square.
+ *   - Plans live in host memory, belong to the library until mom_plan_destroy, are immutable
+ *     and may be evaluated concurrently on different streams with different workspaces.
+ *   - The library never allocates, frees or synchronises device memory.  Inputs, output and
+ *     workspace are the caller's; inputs are read-only and must not overlap the output or the
+ *     workspace.  Evaluation calls only enqueue kernels on the given stream and return.
+ *   - Every call reports failure through mom_status_t; nothing is enqueued on failure.
+ *   - "host" / "device" below say where a pointer must point.
+ */
+#ifndef MOM_H
+#define MOM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Matrix properties (Sec. 2, "Matrix Attribute"; Identity is the paper's Identity type). */
+typedef enum {
+    MOM_GENERAL   = 0,
+    MOM_LOWER_TRI = 1,
+    MOM_UPPER_TRI = 2,
+    MOM_IDENTITY  = 3
+} mom_prop_t;
+
+typedef enum {
+    MOM_OK = 0,
+    MOM_ERR_NULL,              /* a required pointer is NULL */
+    MOM_ERR_BAD_N,             /* n <= 0 or above MOM_MAX_FACTORS, batch < 0 */
+    MOM_ERR_BAD_DIM,           /* a dimension is <= 0 or above 2^31-1 */
+    MOM_ERR_BAD_PROP,          /* a property is not one of mom_prop_t */
+    MOM_ERR_NOT_SQUARE,        /* a lowerTri / upperTri / Identity factor is not square */
+    MOM_ERR_OVERFLOW,          /* a multiplication count does not fit in 64 bits */
+    MOM_ERR_BAD_SPLITS,        /* forced parenthesisation is not a tree over the chain */
+    MOM_ERR_WORKSPACE,         /* workspace NULL or smaller than mom_plan_workspace_bytes */
+    MOM_ERR_BUFFER_TOO_SMALL,  /* caller's host buffer cannot hold the answer */
+    MOM_ERR_BAD_STRIDE,        /* a row or batch stride is smaller than the matrix needs */
+    MOM_ERR_UNSUPPORTED,       /* the batched kernel does not cover this plan's shapes */
+    MOM_ERR_HIP                /* the HIP runtime rejected a launch */
+} mom_status_t;
+
+#define MOM_MAX_FACTORS 1024
+
+/* mom_chain_eval flag: also write zeros into the other half of a triangular RESULT, which
+ * restores the fully materialised buffer of the paper's bufferization (Sec. 2).  Without it
+ * only the triangle of a triangular result is written and the rest of d_out is untouched. */
+#define MOM_OUT_ZERO_FILL_TRIANGLE 1u
+
+typedef struct mom_plan mom_plan_t;   /* opaque */
+
+/*
+ * Plan a chain (Sec. 2, "Transformations": identity simplification, property propagation,
+ * matrix-chain reordering generalised to properties).
+ *   dims  [host] n+1 dimensions, props [host] n values of mom_prop_t.
+ *   *out receives a new plan (NULL on error); release it with mom_plan_destroy.
+ * Cost of X(m x k)*Y(k x n) = number of scalar products with no structurally-zero operand:
+ *   general*general m*k*n; tri*general n*m(m+1)/2; general*tri m*n(n+1)/2;
+ *   L*L, U*U n(n+1)(n+2)/6 (result keeps the triangle); L*U, U*L n(n+1)(2n+1)/6 (general).
+ * Among equal-cost trees the one with the smallest root split wins, recursively.
+ */
+mom_status_t mom_chain_plan(const int64_t *dims, const int32_t *props, int32_t n, mom_plan_t **out);
+
+/*
+ * Plan with a forced parenthesisation, e.g. the "initial parenthesization" of Sec. 4.
+ *   preorder_splits [host]: one entry per binary product (survivors-1 entries; survivors =
+ *   factors that are not Identity), in preorder: a node's split, then its left subtree's
+ *   entries, then its right subtree's.  A split is the ORIGINAL index of the last factor of
+ *   the node's left operand and must be a surviving factor inside the node's range.
+ */
+mom_status_t mom_plan_from_splits(const int64_t *dims, const int32_t *props, int32_t n,
+                                  const int32_t *preorder_splits, mom_plan_t **out);
+
+void mom_plan_destroy(mom_plan_t *plan);                       /* NULL is allowed */
+
+/* Scalar multiplications of the plan's tree (0 for a NULL plan). */
+uint64_t mom_plan_cost_mults(const mom_plan_t *plan);
+
+/* Number of binary products the evaluation launches: survivors-1, or 0. */
+int32_t mom_plan_num_products(const mom_plan_t *plan);
+
+/* Shape and inferred property of the result (the concrete type that replaces the paper's
+ * Term type).  All-Identity chains report MOM_IDENTITY.  Any out pointer may be NULL. */
+mom_status_t mom_plan_result(const mom_plan_t *plan, int64_t *rows, int64_t *cols, int32_t *prop);
+
+/* Parenthesised form with original factor indices, e.g. "(0 (2 (3 4)))"; a single survivor
+ * prints as its index, an all-Identity chain as "I".  buf [host], cap bytes incl. the NUL. */
+mom_status_t mom_plan_string(const mom_plan_t *plan, char *buf, size_t cap);
+
+/* Preorder splits (original indices) of the plan; cap entries available in out [host]. */
+mom_status_t mom_plan_splits(const mom_plan_t *plan, int32_t *out, int32_t cap);
+
+/* Bytes of device workspace mom_chain_eval needs for temporaries (may be 0). */
+size_t mom_plan_workspace_bytes(const mom_plan_t *plan);
+
+/*
+ * Enqueue the evaluation of the plan on `stream` (a hipStream_t passed as void*; NULL = the
+ * default stream).  Asynchronous; one kernel per binary product plus, where needed, a
+ * split-K reduction or a zero-fill pass.
+ *   d_factors [host] array of n DEVICE pointers, entry t -> dims[t] x dims[t+1] f32;
+ *             entries of Identity factors are ignored and may be NULL.
+ *   lds       [host] n row strides in elements (>= dims[t+1]), or NULL for packed rows.
+ *   d_out     [device] rows x cols result, row stride ld_out elements (0 = packed).
+ *   d_workspace [device] at least mom_plan_workspace_bytes bytes, 256-byte aligned; may be
+ *             NULL when that is 0.  Contents are scratch.
+ *   flags     0 or MOM_OUT_ZERO_FILL_TRIANGLE.
+ * A chain whose factors are all Identity writes the identity matrix; a chain with a single
+ * surviving factor copies it (its triangle only, for a triangular factor).
+ */
+mom_status_t mom_chain_eval(const mom_plan_t *plan, const float *const *d_factors, const int64_t *lds,
+                            float *d_out, int64_t ld_out, void *d_workspace, size_t workspace_bytes,
+                            uint32_t flags, void *stream);
+
+/*
+ * Evaluate `batch` independent chains that share one plan in ONE kernel launch; each chain is
+ * handled by one 64-lane wavefront and intermediates never leave the compute unit.
+ *   d_factor_bases [host] n DEVICE pointers; chain b's factor t starts at
+ *             d_factor_bases[t] + b * batch_strides[t] and is packed row-major.
+ *   batch_strides [host] n strides in elements, or NULL for dims[t]*dims[t+1].
+ *   d_out [device], chain b's result at d_out + b * out_batch_stride (0 = rows*cols), packed.
+ * Covers plans whose dimensions are all <= 32 and that have at most 8 surviving factors
+ * (MOM_ERR_UNSUPPORTED otherwise).  Triangular results are written in full (zeros included).
+ */
+mom_status_t mom_chain_eval_batched(const mom_plan_t *plan, const float *const *d_factor_bases,
+                                    const int64_t *batch_strides, float *d_out,
+                                    int64_t out_batch_stride, int32_t batch, void *stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char *mom_status_string(mom_status_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOM_H */

@@ -1,0 +1,142 @@
+// Evaluator: walks a plan's binary products and enqueues one product kernel per step on the
+// caller's stream (MOM paper, Sec. 2 "Operations": a variadic Mul rewritten into binary
+// multiplications).  No allocation, no synchronisation, no device memory owned here.
+#include "../../include/mom.h"
+#include "plan_internal.h"
+#include "product_kernel.h"
+#include "schedule.h"
+#include "batched_kernel.h"
+
+#include <hip/hip_runtime.h>
+
+namespace {
+
+using namespace mom;
+
+// 128x128x16 tiles, 4 wavefronts of 64x64: the workhorse.  64x64x16 tiles, 4 wavefronts of
+// 32x32: products with a short side.
+typedef TileConfig<128, 128, 16, 2, 2, 2> Tile128;
+typedef TileConfig<64, 64, 16, 2, 2, 2> Tile64;
+
+template <class T>
+hipError_t launch_product(const ProductParams &p, int grid_x, int grid_y, hipStream_t stream)
+{
+    static bool configured[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64 && !configured[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&product_kernel<T>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        configured[dev] = true;
+    }
+    hipLaunchKernelGGL(product_kernel<T>, dim3(grid_x, grid_y), dim3(T::NT), T::LDS_BYTES, stream, p);
+    return hipGetLastError();
+}
+
+inline bool aligned16(const void *ptr, int64_t ld) { return (reinterpret_cast<uintptr_t>(ptr) & 15) == 0 && (ld & 3) == 0; }
+
+inline int elementwise_grid(int64_t total) { return (int)std::min<int64_t>((total + 255) / 256, 4096); }
+
+struct Resolved { const float *ptr; int64_t ld; };
+
+}  // namespace
+
+extern "C" mom_status_t mom_chain_eval(const mom_plan_t *plan, const float *const *d_factors, const int64_t *lds,
+                                       float *d_out, int64_t ld_out, void *d_workspace, size_t workspace_bytes,
+                                       uint32_t flags, void *stream_)
+{
+    if (!plan || !d_out) return MOM_ERR_NULL;
+    if (!d_factors && !plan->survivors.empty()) return MOM_ERR_NULL;
+    for (int32_t f : plan->survivors)
+        if (!d_factors[f]) return MOM_ERR_NULL;
+    if (lds)
+        for (int32_t f : plan->survivors)
+            if (lds[f] < plan->dims[f + 1]) return MOM_ERR_BAD_STRIDE;
+    if (ld_out == 0) ld_out = plan->cols;
+    if (ld_out < plan->cols) return MOM_ERR_BAD_STRIDE;
+    if (plan->workspace_bytes > 0 &&
+        (!d_workspace || workspace_bytes < plan->workspace_bytes || (reinterpret_cast<uintptr_t>(d_workspace) & 255)))
+        return MOM_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    char *const ws = static_cast<char *>(d_workspace);
+    const bool zero_fill = (flags & MOM_OUT_ZERO_FILL_TRIANGLE) != 0;
+    const int M = (int)plan->rows, N = (int)plan->cols;
+
+    if (plan->survivors.empty()) {                         // I * I * ... = I
+        hipLaunchKernelGGL(write_identity_kernel, dim3(elementwise_grid((int64_t)M * M)), dim3(256), 0, stream,
+                           d_out, ld_out, M);
+        return hipGetLastError() == hipSuccess ? MOM_OK : MOM_ERR_HIP;
+    }
+    auto factor = [&](int32_t f) { return Resolved{d_factors[f], lds ? lds[f] : plan->dims[f + 1]}; };
+
+    if (plan->steps.empty()) {                             // one survivor: A * I -> A
+        const int32_t f = plan->survivors[0];
+        const Resolved a = factor(f);
+        hipLaunchKernelGGL(copy_structure_kernel, dim3(elementwise_grid((int64_t)M * N)), dim3(256), 0, stream,
+                           a.ptr, a.ld, d_out, ld_out, M, N, plan->props[f]);
+        if (hipGetLastError() != hipSuccess) return MOM_ERR_HIP;
+    }
+
+    for (const ProductStep &st : plan->steps) {
+        auto resolve = [&](const Operand &o, int64_t cols) {
+            if (o.where == Where::Factor) return factor(o.index);
+            if (o.where == Where::Temp)
+                return Resolved{reinterpret_cast<const float *>(ws + plan->temps[o.index].offset), cols};
+            return Resolved{d_out, ld_out};
+        };
+        const Resolved a = resolve(st.a, st.k), b = resolve(st.b, st.n), c = resolve(st.c, st.n);
+        const Launch L = choose_launch(st);
+        ProductParams p{};
+        p.A = a.ptr; p.B = b.ptr; p.C = const_cast<float *>(c.ptr);
+        p.lda = a.ld; p.ldb = b.ld; p.ldc = c.ld;
+        p.M = (int)st.m; p.N = (int)st.n; p.K = (int)st.k;
+        p.pa = st.pa; p.pb = st.pb; p.pc = st.pc;
+        p.tiles_m = L.tiles_m; p.tiles_n = L.tiles_n; p.num_tiles = L.num_tiles;
+        p.order = L.order; p.paired = L.paired;
+        p.a_vec = aligned16(a.ptr, a.ld); p.b_vec = aligned16(b.ptr, b.ld);
+        p.split_k = L.split_k;
+        p.slice_stride = 0;
+        if (L.split_k > 1) {                               // partial sums go to the scratch region
+            p.C = reinterpret_cast<float *>(ws + plan->scratch_offset);
+            p.ldc = st.n;
+            p.slice_stride = st.m * st.n;
+        }
+        hipError_t e = L.shape == kTile128 ? launch_product<Tile128>(p, L.grid, L.split_k, stream)
+                                           : launch_product<Tile64>(p, L.grid, L.split_k, stream);
+        if (e != hipSuccess) return MOM_ERR_HIP;
+        if (L.split_k > 1) {
+            hipLaunchKernelGGL(reduce_slices_kernel, dim3(elementwise_grid(st.m * st.n)), dim3(256), 0, stream,
+                               p.C, p.slice_stride, L.split_k, const_cast<float *>(c.ptr), c.ld, p.M, p.N);
+            if (hipGetLastError() != hipSuccess) return MOM_ERR_HIP;
+        }
+    }
+
+    if (zero_fill && (plan->result_prop == kLower || plan->result_prop == kUpper)) {
+        hipLaunchKernelGGL(zero_other_half_kernel, dim3(elementwise_grid((int64_t)M * M)), dim3(256), 0, stream,
+                           d_out, ld_out, M, plan->result_prop);
+        if (hipGetLastError() != hipSuccess) return MOM_ERR_HIP;
+    }
+    return MOM_OK;
+}
+
+extern "C" mom_status_t mom_chain_eval_batched(const mom_plan_t *plan, const float *const *d_factor_bases,
+                                               const int64_t *batch_strides, float *d_out,
+                                               int64_t out_batch_stride, int32_t batch, void *stream_)
+{
+    if (!plan || !d_out) return MOM_ERR_NULL;
+    if (batch < 0) return MOM_ERR_BAD_N;
+    if (!d_factor_bases && !plan->survivors.empty()) return MOM_ERR_NULL;
+    for (int32_t f : plan->survivors)
+        if (!d_factor_bases[f]) return MOM_ERR_NULL;
+    if (plan->max_dim > kBatchedMaxDim || (int)plan->survivors.size() > kBatchedMaxFactors) return MOM_ERR_UNSUPPORTED;
+    if (batch_strides)
+        for (int32_t f : plan->survivors)
+            if (batch_strides[f] < plan->dims[f] * plan->dims[f + 1]) return MOM_ERR_BAD_STRIDE;
+    if (out_batch_stride == 0) out_batch_stride = plan->rows * plan->cols;
+    if (out_batch_stride < plan->rows * plan->cols) return MOM_ERR_BAD_STRIDE;
+    if (batch == 0) return MOM_OK;
+    return launch_batched(plan, d_factor_bases, batch_strides, d_out, out_batch_stride, batch,
+                          static_cast<hipStream_t>(stream_)) == hipSuccess ? MOM_OK : MOM_ERR_HIP;
+}

@@ -1,0 +1,369 @@
+// Host-side planner: identity simplification, property propagation and the
+// property-aware matrix-chain dynamic program (MOM paper, Sec. 2 "Transformations"),
+// followed by the schedule: the binary products in evaluation order and the placement
+// of temporaries in the caller's workspace.  Integer work only; no HIP calls.
+#include "../../include/mom.h"
+#include "plan_internal.h"
+#include "schedule.h"
+
+#include <algorithm>
+#include <limits>
+#include <new>
+
+namespace {
+
+using mom::kGeneral;
+using mom::kIdentity;
+using mom::kLower;
+using mom::kUpper;
+typedef unsigned __int128 u128;
+
+constexpr u128 kU64Max = (u128)std::numeric_limits<uint64_t>::max();
+
+inline bool is_tri(int p) { return p == kLower || p == kUpper; }
+
+// Property of X*Y (Sec. 2: properties of intermediate results are inferred).  With Identity
+// below the triangles below general, this is the join of the two operand properties:
+// equal triangles keep their triangle, anything else fills the matrix.
+inline int join(int px, int py)
+{
+    if (px == kIdentity) return py;
+    if (py == kIdentity) return px;
+    if (px == py) return px;
+    return kGeneral;
+}
+
+// Scalar multiplications of X(m x k)*Y(k x n) in which neither operand is a structural zero.
+u128 product_mults(int64_t m, int64_t k, int64_t n, int px, int py)
+{
+    const u128 M = (u128)m, K = (u128)k, N = (u128)n;
+    if (!is_tri(px) && !is_tri(py)) return M * K * N;
+    if (is_tri(px) && !is_tri(py)) return N * (M * (M + 1) / 2);       // row i of X has i+1 (or m-i) entries
+    if (!is_tri(px) && is_tri(py)) return M * (N * (N + 1) / 2);
+    if (px == py) return N * (N + 1) * (N + 2) / 6;                     // sum over i>=j of (i-j+1)
+    return N * (N + 1) * (2 * N + 1) / 6;                               // sum over i,j of min(i,j)+1
+}
+
+mom_status_t validate(const int64_t *dims, const int32_t *props, int32_t n)
+{
+    if (!dims || !props) return MOM_ERR_NULL;
+    if (n <= 0 || n > MOM_MAX_FACTORS) return MOM_ERR_BAD_N;
+    for (int i = 0; i <= n; ++i)
+        if (dims[i] <= 0 || dims[i] > (int64_t)std::numeric_limits<int32_t>::max()) return MOM_ERR_BAD_DIM;
+    for (int i = 0; i < n; ++i) {
+        if (props[i] < kGeneral || props[i] > kIdentity) return MOM_ERR_BAD_PROP;
+        if (props[i] != kGeneral && dims[i] != dims[i + 1]) return MOM_ERR_NOT_SQUARE;
+    }
+    return MOM_OK;
+}
+
+// First-fit allocator over the workspace, 256-byte granules; temporaries are released as
+// soon as the product that consumes them has been scheduled, so their space is reused.
+class Arena {
+public:
+    size_t alloc(size_t bytes)
+    {
+        bytes = (bytes + 255) & ~(size_t)255;
+        for (size_t i = 0; i < free_.size(); ++i) {
+            if (free_[i].second >= bytes) {
+                size_t off = free_[i].first;
+                free_[i].first += bytes;
+                free_[i].second -= bytes;
+                if (free_[i].second == 0) free_.erase(free_.begin() + i);
+                return off;
+            }
+        }
+        const size_t off = top_;      // release() never leaves a free block touching top_
+        top_ = off + bytes;
+        peak_ = std::max(peak_, top_);
+        return off;
+    }
+    void release(size_t off, size_t bytes)
+    {
+        bytes = (bytes + 255) & ~(size_t)255;
+        free_.emplace_back(off, bytes);
+        std::sort(free_.begin(), free_.end());
+        for (size_t i = 0; i + 1 < free_.size();) {       // merge neighbours
+            if (free_[i].first + free_[i].second == free_[i + 1].first) {
+                free_[i].second += free_[i + 1].second;
+                free_.erase(free_.begin() + i + 1);
+            } else {
+                ++i;
+            }
+        }
+        if (!free_.empty() && free_.back().first + free_.back().second == top_) {
+            top_ = free_.back().first;
+            free_.pop_back();
+        }
+    }
+    size_t peak() const { return peak_; }
+
+private:
+    std::vector<std::pair<size_t, size_t>> free_;
+    size_t top_ = 0, peak_ = 0;
+};
+
+struct Builder {
+    mom_plan *plan;
+    const std::vector<int64_t> &d;     // dims of the survivors chain
+    const std::vector<int32_t> &p;     // props of the survivors chain
+    const std::vector<int32_t> &split_pos;   // preorder, positions in the survivors chain
+    Arena arena;
+    size_t cursor = 0;
+    int depth = 0, max_depth = 0;
+    u128 total = 0;
+    bool ok = true;
+
+    struct Value { mom::Operand op; int64_t rows, cols; int prop; };
+
+    Value walk(int lo, int hi, bool is_root)
+    {
+        if (lo == hi) {
+            ++depth; max_depth = std::max(max_depth, depth);
+            return Value{{mom::Where::Factor, plan->survivors[lo]}, d[lo], d[lo + 1], p[lo]};
+        }
+        if (cursor >= split_pos.size()) { ok = false; return Value{}; }
+        const int s = split_pos[cursor++];
+        if (s < lo || s >= hi) { ok = false; return Value{}; }
+        Value a = walk(lo, s, false);
+        if (!ok) return Value{};
+        Value b = walk(s + 1, hi, false);
+        if (!ok) return Value{};
+        mom::ProductStep st;
+        st.a = a.op; st.b = b.op;
+        st.m = a.rows; st.k = a.cols; st.n = b.cols;
+        st.pa = a.prop; st.pb = b.prop; st.pc = join(a.prop, b.prop);
+        const u128 c = product_mults(st.m, st.k, st.n, st.pa, st.pb);
+        total += c;
+        st.mults = c > kU64Max ? std::numeric_limits<uint64_t>::max() : (uint64_t)c;
+        if (is_root) {
+            st.c = {mom::Where::Out, 0};
+        } else {
+            const size_t bytes = (size_t)st.m * (size_t)st.n * sizeof(float);
+            const size_t off = arena.alloc(bytes);
+            plan->temps.push_back({off, bytes});
+            st.c = {mom::Where::Temp, (int)plan->temps.size() - 1};
+        }
+        plan->steps.push_back(st);
+        for (const mom::Operand &o : {a.op, b.op})
+            if (o.where == mom::Where::Temp) arena.release(plan->temps[o.index].offset, plan->temps[o.index].bytes);
+        --depth;    // two operands popped, one result pushed
+        return Value{st.c, st.m, st.n, st.pc};
+    }
+};
+
+void render(const mom_plan *plan, const std::vector<int32_t> &split_pos, size_t &cursor, int lo, int hi,
+            std::string &out)
+{
+    if (lo == hi) { out += std::to_string(plan->survivors[lo]); return; }
+    const int s = split_pos[cursor++];
+    out += '(';
+    render(plan, split_pos, cursor, lo, s, out);
+    out += ' ';
+    render(plan, split_pos, cursor, s + 1, hi, out);
+    out += ')';
+}
+
+// Build everything that follows from a chosen tree (given as positions in the survivors chain).
+mom_status_t finish(mom_plan *plan, const std::vector<int64_t> &d, const std::vector<int32_t> &p,
+                    const std::vector<int32_t> &split_pos)
+{
+    const int m = (int)plan->survivors.size();
+    plan->rows = plan->dims.front();
+    plan->cols = plan->dims.back();
+    plan->max_dim = *std::max_element(plan->dims.begin(), plan->dims.end());
+    if (m == 0) {                       // I*I = I
+        plan->result_prop = kIdentity;
+        plan->cost = 0;
+        plan->text = "I";
+        return MOM_OK;
+    }
+    if ((int)split_pos.size() != m - 1) return MOM_ERR_BAD_SPLITS;
+    Builder b{plan, d, p, split_pos};
+    Builder::Value root = b.walk(0, m - 1, true);
+    if (!b.ok || b.cursor != split_pos.size()) return MOM_ERR_BAD_SPLITS;
+    if (b.total > kU64Max) return MOM_ERR_OVERFLOW;
+    plan->cost = (uint64_t)b.total;
+    plan->result_prop = root.prop;
+    plan->stack_depth = b.max_depth;
+    plan->temp_bytes = b.arena.peak();
+    plan->splits.clear();
+    for (int s : split_pos) plan->splits.push_back(plan->survivors[s]);
+    size_t cursor = 0;
+    render(plan, split_pos, cursor, 0, m - 1, plan->text);
+    // split-K partial sums live behind the temporaries; products run one after the other on
+    // one stream, so a single region sized for the hungriest product serves all of them
+    size_t scratch = 0;
+    for (const mom::ProductStep &st : plan->steps) scratch = std::max(scratch, mom::choose_launch(st).scratch_bytes);
+    plan->scratch_offset = (plan->temp_bytes + 255) & ~(size_t)255;
+    plan->scratch_bytes = scratch;
+    plan->workspace_bytes = scratch ? plan->scratch_offset + scratch : plan->temp_bytes;
+    return MOM_OK;
+}
+
+mom_status_t start(const int64_t *dims, const int32_t *props, int32_t n, mom_plan **holder,
+                   std::vector<int64_t> &d, std::vector<int32_t> &p)
+{
+    mom_plan *plan = new (std::nothrow) mom_plan();
+    if (!plan) return MOM_ERR_NULL;
+    plan->n = n;
+    plan->dims.assign(dims, dims + n + 1);
+    plan->props.assign(props, props + n);
+    // identity simplification: A*I -> A, I*A -> A, I*I = I
+    for (int i = 0; i < n; ++i) {
+        if (props[i] == kIdentity) continue;
+        plan->survivors.push_back(i);
+        d.push_back(dims[i]);
+        p.push_back(props[i]);
+    }
+    d.push_back(dims[n]);
+    *holder = plan;
+    return MOM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+mom_status_t mom_chain_plan(const int64_t *dims, const int32_t *props, int32_t n, mom_plan_t **out)
+{
+    if (!out) return MOM_ERR_NULL;
+    *out = nullptr;
+    mom_status_t st = validate(dims, props, n);
+    if (st != MOM_OK) return st;
+    mom_plan *plan = nullptr;
+    std::vector<int64_t> d;
+    std::vector<int32_t> p;
+    st = start(dims, props, n, &plan, d, p);
+    if (st != MOM_OK) return st;
+    const int m = (int)p.size();
+    std::vector<int32_t> split_pos;
+    if (m > 1) {
+        // best[i][j]: fewest multiplications for survivors i..j; prop[i][j]: their product's
+        // property (independent of the parenthesisation); cut[i][j]: chosen split.
+        std::vector<u128> best((size_t)m * m, 0);
+        std::vector<int32_t> cut((size_t)m * m, -1);
+        std::vector<int8_t> prop((size_t)m * m, 0);
+        auto at = [m](int i, int j) { return (size_t)i * m + j; };
+        for (int i = 0; i < m; ++i) {
+            prop[at(i, i)] = (int8_t)p[i];
+            for (int j = i + 1; j < m; ++j) prop[at(i, j)] = (int8_t)join(prop[at(i, j - 1)], p[j]);
+        }
+        for (int len = 2; len <= m; ++len) {
+            for (int i = 0; i + len <= m; ++i) {
+                const int j = i + len - 1;
+                u128 lowest = 0;
+                int where = -1;
+                for (int k = i; k < j; ++k) {       // ascending; only a strictly smaller cost
+                    const u128 c = best[at(i, k)] + best[at(k + 1, j)] +
+                                   product_mults(d[i], d[k + 1], d[j + 1], prop[at(i, k)], prop[at(k + 1, j)]);
+                    if (where < 0 || c < lowest) { lowest = c; where = k; }   // replaces: smallest split wins ties
+                }
+                best[at(i, j)] = lowest;
+                cut[at(i, j)] = where;
+            }
+        }
+        if (best[at(0, m - 1)] > kU64Max) { delete plan; return MOM_ERR_OVERFLOW; }
+        // preorder read-out of the chosen tree
+        std::vector<std::pair<int, int>> todo{{0, m - 1}};
+        while (!todo.empty()) {
+            auto [lo, hi] = todo.back();
+            todo.pop_back();
+            if (lo == hi) continue;
+            const int s = cut[at(lo, hi)];
+            split_pos.push_back(s);
+            todo.emplace_back(s + 1, hi);
+            todo.emplace_back(lo, s);
+        }
+    }
+    st = finish(plan, d, p, split_pos);
+    if (st != MOM_OK) { delete plan; return st; }
+    *out = plan;
+    return MOM_OK;
+}
+
+mom_status_t mom_plan_from_splits(const int64_t *dims, const int32_t *props, int32_t n,
+                                  const int32_t *preorder_splits, mom_plan_t **out)
+{
+    if (!out) return MOM_ERR_NULL;
+    *out = nullptr;
+    mom_status_t st = validate(dims, props, n);
+    if (st != MOM_OK) return st;
+    mom_plan *plan = nullptr;
+    std::vector<int64_t> d;
+    std::vector<int32_t> p;
+    st = start(dims, props, n, &plan, d, p);
+    if (st != MOM_OK) return st;
+    const int m = (int)p.size();
+    std::vector<int32_t> split_pos;
+    if (m > 1) {
+        if (!preorder_splits) { delete plan; return MOM_ERR_NULL; }
+        std::vector<int32_t> position(n, -1);
+        for (int i = 0; i < m; ++i) position[plan->survivors[i]] = i;
+        for (int i = 0; i < m - 1; ++i) {
+            const int32_t s = preorder_splits[i];
+            if (s < 0 || s >= n || position[s] < 0) { delete plan; return MOM_ERR_BAD_SPLITS; }
+            split_pos.push_back(position[s]);
+        }
+    }
+    st = finish(plan, d, p, split_pos);
+    if (st != MOM_OK) { delete plan; return st; }
+    *out = plan;
+    return MOM_OK;
+}
+
+void mom_plan_destroy(mom_plan_t *plan) { delete plan; }
+
+uint64_t mom_plan_cost_mults(const mom_plan_t *plan) { return plan ? plan->cost : 0; }
+
+int32_t mom_plan_num_products(const mom_plan_t *plan) { return plan ? (int32_t)plan->steps.size() : 0; }
+
+mom_status_t mom_plan_result(const mom_plan_t *plan, int64_t *rows, int64_t *cols, int32_t *prop)
+{
+    if (!plan) return MOM_ERR_NULL;
+    if (rows) *rows = plan->rows;
+    if (cols) *cols = plan->cols;
+    if (prop) *prop = plan->result_prop;
+    return MOM_OK;
+}
+
+mom_status_t mom_plan_string(const mom_plan_t *plan, char *buf, size_t cap)
+{
+    if (!plan || !buf) return MOM_ERR_NULL;
+    if (cap < plan->text.size() + 1) return MOM_ERR_BUFFER_TOO_SMALL;
+    std::copy(plan->text.begin(), plan->text.end(), buf);
+    buf[plan->text.size()] = '\0';
+    return MOM_OK;
+}
+
+mom_status_t mom_plan_splits(const mom_plan_t *plan, int32_t *out, int32_t cap)
+{
+    if (!plan || (!out && !plan->splits.empty())) return MOM_ERR_NULL;
+    if (cap < (int32_t)plan->splits.size()) return MOM_ERR_BUFFER_TOO_SMALL;
+    std::copy(plan->splits.begin(), plan->splits.end(), out);
+    return MOM_OK;
+}
+
+size_t mom_plan_workspace_bytes(const mom_plan_t *plan) { return plan ? plan->workspace_bytes : 0; }
+
+const char *mom_status_string(mom_status_t status)
+{
+    switch (status) {
+    case MOM_OK: return "ok";
+    case MOM_ERR_NULL: return "a required pointer is NULL";
+    case MOM_ERR_BAD_N: return "number of factors (or batch) out of range";
+    case MOM_ERR_BAD_DIM: return "a dimension is not in 1..2^31-1";
+    case MOM_ERR_BAD_PROP: return "unknown matrix property";
+    case MOM_ERR_NOT_SQUARE: return "a triangular or Identity factor is not square";
+    case MOM_ERR_OVERFLOW: return "multiplication count does not fit in 64 bits";
+    case MOM_ERR_BAD_SPLITS: return "forced parenthesisation is not a tree over the chain";
+    case MOM_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case MOM_ERR_BUFFER_TOO_SMALL: return "host buffer too small";
+    case MOM_ERR_BAD_STRIDE: return "stride smaller than the matrix needs";
+    case MOM_ERR_UNSUPPORTED: return "plan not covered by the batched kernel";
+    case MOM_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

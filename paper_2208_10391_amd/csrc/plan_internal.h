@@ -1,0 +1,55 @@
+// Internal layout of a plan: shared by the planner (host only) and the evaluator.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <string>
+#include <vector>
+
+namespace mom {
+
+enum : int { kGeneral = 0, kLower = 1, kUpper = 2, kIdentity = 3 };
+
+// Where an operand of a binary product lives.
+enum class Where : int { Factor = 0, Temp = 1, Out = 2 };
+
+struct Operand {
+    Where where;
+    int index;     // original factor index, or temporary id
+};
+
+// One binary product C(m x n) = A(m x k) * B(k x n), in evaluation (post-) order.
+struct ProductStep {
+    Operand a, b, c;
+    int64_t m, k, n;
+    int pa, pb, pc;            // properties of A, B and of the result
+    uint64_t mults;            // scalar multiplications with no structurally-zero operand
+};
+
+struct Temp {
+    size_t offset;             // bytes from the start of the workspace, 256-byte aligned
+    size_t bytes;              // rows * cols * 4 (dense storage; a triangular temporary is
+                               // stored dense and only its triangle is ever written or read)
+};
+
+}  // namespace mom
+
+struct mom_plan {
+    int32_t n = 0;
+    std::vector<int64_t> dims;       // n + 1
+    std::vector<int32_t> props;      // n
+    std::vector<int32_t> survivors;  // original indices of the non-Identity factors
+    std::vector<int32_t> splits;     // preorder, original indices, survivors-1 entries
+    uint64_t cost = 0;
+    int64_t rows = 0, cols = 0;
+    int32_t result_prop = 0;
+    std::vector<mom::ProductStep> steps;
+    std::vector<mom::Temp> temps;
+    size_t temp_bytes = 0;           // bytes of workspace used by temporaries
+    size_t scratch_offset = 0;       // split-K partial sums start here
+    size_t scratch_bytes = 0;
+    size_t workspace_bytes = 0;
+    std::string text;
+    // batched evaluation: largest dimension and operand-stack depth of the post-order walk
+    int64_t max_dim = 0;
+    int32_t stack_depth = 0;
+};

@@ -1,0 +1,345 @@
+// Tiled f32 MFMA product kernel for gfx950 (MI355X): C = A * B where A, B and C each carry
+// one of the properties general / lowerTri / upperTri (MOM paper, Sec. 2).  One kernel covers
+// GEMM, TRMM from either side and triangular*triangular products: a property only
+//   - clips the k-range of an output tile (tiles of zeros are never loaded or multiplied),
+//   - masks the operand elements of the chunks that straddle a diagonal (the zero half of a
+//     triangular operand is never trusted to hold zeros),
+//   - removes the output tiles of the zero half of a triangular result and masks the stores
+//     of its diagonal tiles (only the triangle is written).
+// This is the non-rectangular iteration space that Sec. 5 of the paper names as future work.
+//
+// Data path: global -> registers (16-byte loads) -> LDS (double buffered) -> MFMA operands.
+// v_mfma_f32_32x32x2_f32: lane l supplies A[i = l%32][k = l/32] and B[k = l/32][j = l%32];
+// accumulator register v of lane l holds C[8*(v/4) + 4*(l/32) + v%4][l%32].
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "schedule.h"
+
+namespace mom {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+struct ProductParams {
+    const float *A;
+    const float *B;
+    float *C;              // result, or split-K partial sums (slice s at C + s * slice_stride)
+    int64_t lda, ldb, ldc;
+    int64_t slice_stride;  // elements between split-K slices (0 when split_k == 1)
+    int M, N, K;
+    int pa, pb, pc;
+    int tiles_m, tiles_n, num_tiles, order, paired;
+    int a_vec, b_vec;      // 16-byte loads are legal for A / B (base and row stride aligned)
+    int split_k;
+};
+
+// Is (i, j) inside the structure of property p?  (p is never Identity here.)
+__device__ __forceinline__ bool in_structure(int p, int i, int j)
+{
+    return p == kGeneral ? true : (p == kLower ? j <= i : j >= i);
+}
+
+__device__ __forceinline__ int isqrt_floor(int64_t x)
+{
+    int64_t r = (int64_t)sqrt((double)x);
+    while (r * r > x) --r;
+    while ((r + 1) * (r + 1) <= x) ++r;
+    return (int)r;
+}
+
+// Position t in the longest-first tile order -> tile coordinates.
+__device__ __forceinline__ void tile_coords(int order, int t, int tm, int tn, int &I, int &J)
+{
+    switch (order) {
+    case kRowsDesc: I = tm - 1 - t / tn; J = t % tn; break;
+    case kColsAsc:  J = t / tm; I = t % tm; break;
+    case kColsDesc: J = tn - 1 - t / tm; I = t % tm; break;
+    case kDiagLower:
+    case kDiagUpper: {
+        // diagonals d = tm-1, tm-2, ..., 0; diagonal d has tm-d tiles of length d+1
+        const int s = (isqrt_floor(8 * (int64_t)t + 1) - 1) / 2;      // complete diagonals before t
+        const int d = tm - 1 - s, pos = t - s * (s + 1) / 2;
+        const int hi = d + pos, lo = pos;
+        if (order == kDiagLower) { I = hi; J = lo; } else { I = lo; J = hi; }
+        break;
+    }
+    case kShellMin:
+    case kShellMax: {
+        // shells of constant min(I,J) = s, largest s first; the shell has 2*(tm-s)-1 tiles
+        const int q = isqrt_floor(t), side = q + 1, s = tm - side, pos = t - q * q;
+        int i, j;
+        if (pos < side) { i = s; j = s + pos; } else { i = s + (pos - side) + 1; j = s; }
+        if (order == kShellMin) { I = i; J = j; } else { I = tm - 1 - i; J = tn - 1 - j; }
+        break;
+    }
+    default: I = t / tn; J = t % tn; break;     // kRowMajor, kRowsAsc
+    }
+}
+
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int MIN_BLOCKS_>
+struct TileConfig {
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
+    static constexpr int MIN_BLOCKS = MIN_BLOCKS_;
+    static constexpr int NT = WM * WN * 64;           // threads per workgroup
+    static constexpr int WTM = BM / WM, WTN = BN / WN;   // tile of one wavefront
+    static constexpr int FM = WTM / 32, FN = WTN / 32;   // 32x32 MFMA blocks per wavefront
+    static constexpr int LDA = BK + 4;                // LDS row stride of the A tile [BM][BK]:
+                                                      // 16-byte rows reads hit distinct banks
+    static constexpr int LDB = BN;                    // LDS row stride of the B tile [BK][BN]
+    static constexpr int A_STAGE = BM * LDA, B_STAGE = BK * LDB;
+    static constexpr int LDS_BYTES = 2 * (A_STAGE + B_STAGE) * 4;
+    static constexpr int A_F4 = BM * BK / 4 / NT;     // 16-byte loads per thread and chunk
+    static constexpr int B_F4 = BK * BN / 4 / NT;
+    static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BK % 8 == 0, "tile shape");
+    static_assert((BM * BK / 4) % NT == 0 && (BK * BN / 4) % NT == 0, "load decomposition");
+};
+
+// Operand load modes of one k-chunk (uniform over the workgroup):
+//   0  interior: plain 16-byte loads
+//   1  in bounds and aligned, but the chunk straddles the operand's diagonal: load, then mask
+//   2  edge of the matrix or unaligned rows: element-wise, bounds-checked and masked
+template <class T>
+__device__ __forceinline__ void load_a(const ProductParams &p, int r0, int kc, int mode, int tid,
+                                       f32x4 (&ra)[T::A_F4])
+{
+#pragma unroll
+    for (int q = 0; q < T::A_F4; ++q) {
+        const int idx = tid + q * T::NT;
+        const int gi = r0 + idx / (T::BK / 4);
+        const int gk = kc + (idx % (T::BK / 4)) * 4;
+        const float *src = p.A + (int64_t)gi * p.lda + gk;
+        f32x4 v;
+        if (mode == 0) {
+            v = *reinterpret_cast<const f32x4 *>(src);
+        } else if (mode == 1) {
+            v = *reinterpret_cast<const f32x4 *>(src);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = in_structure(p.pa, gi, gk + e) ? v[e] : 0.0f;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const bool ok = gi < p.M && gk + e < p.K && in_structure(p.pa, gi, gk + e);
+                v[e] = ok ? src[e] : 0.0f;
+            }
+        }
+        ra[q] = v;
+    }
+}
+
+template <class T>
+__device__ __forceinline__ void load_b(const ProductParams &p, int c0, int kc, int mode, int tid,
+                                       f32x4 (&rb)[T::B_F4])
+{
+#pragma unroll
+    for (int q = 0; q < T::B_F4; ++q) {
+        const int idx = tid + q * T::NT;
+        const int gk = kc + idx / (T::BN / 4);
+        const int gj = c0 + (idx % (T::BN / 4)) * 4;
+        const float *src = p.B + (int64_t)gk * p.ldb + gj;
+        f32x4 v;
+        if (mode == 0) {
+            v = *reinterpret_cast<const f32x4 *>(src);
+        } else if (mode == 1) {
+            v = *reinterpret_cast<const f32x4 *>(src);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = in_structure(p.pb, gk, gj + e) ? v[e] : 0.0f;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const bool ok = gk < p.K && gj + e < p.N && in_structure(p.pb, gk, gj + e);
+                v[e] = ok ? src[e] : 0.0f;
+            }
+        }
+        rb[q] = v;
+    }
+}
+
+template <class T>
+__device__ __forceinline__ void stage_to_lds(float *As, float *Bs, int tid,
+                                             const f32x4 (&ra)[T::A_F4], const f32x4 (&rb)[T::B_F4])
+{
+#pragma unroll
+    for (int q = 0; q < T::A_F4; ++q) {
+        const int idx = tid + q * T::NT;
+        *reinterpret_cast<f32x4 *>(As + (idx / (T::BK / 4)) * T::LDA + (idx % (T::BK / 4)) * 4) = ra[q];
+    }
+#pragma unroll
+    for (int q = 0; q < T::B_F4; ++q) {
+        const int idx = tid + q * T::NT;
+        *reinterpret_cast<f32x4 *>(Bs + (idx / (T::BN / 4)) * T::LDB + (idx % (T::BN / 4)) * 4) = rb[q];
+    }
+}
+
+// One k-chunk of MFMA work from LDS.  Within each group of 8 k-values, MFMA step e (0..3)
+// multiplies k = 4*half + e, so that a lane fetches its four A values with one 16-byte read;
+// the order of summation over k is free.
+template <class T>
+__device__ __forceinline__ void mfma_chunk(const float *As, const float *Bs, int wr0, int wc0, int l32, int half,
+                                           f32x16 (&acc)[T::FM][T::FN])
+{
+#pragma unroll
+    for (int kg = 0; kg < T::BK / 8; ++kg) {
+        f32x4 a[T::FM];
+        float b[T::FN][4];
+#pragma unroll
+        for (int bi = 0; bi < T::FM; ++bi)
+            a[bi] = *reinterpret_cast<const f32x4 *>(As + (wr0 + bi * 32 + l32) * T::LDA + kg * 8 + 4 * half);
+#pragma unroll
+        for (int bj = 0; bj < T::FN; ++bj)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                b[bj][e] = Bs[(kg * 8 + 4 * half + e) * T::LDB + wc0 + bj * 32 + l32];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int bi = 0; bi < T::FM; ++bi)
+#pragma unroll
+                for (int bj = 0; bj < T::FN; ++bj)
+                    acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[bi][e], b[bj][e], acc[bi][bj], 0, 0, 0);
+    }
+}
+
+template <class T>
+__global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const ProductParams p)
+{
+    extern __shared__ __align__(16) float smem[];
+    float *const As = smem;                       // two stages of the A tile
+    float *const Bs = smem + 2 * T::A_STAGE;      // two stages of the B tile
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int wr0 = (wave / T::WN) * T::WTM, wc0 = (wave % T::WN) * T::WTN;
+    const int slice = blockIdx.y;
+
+    for (int pass = 0; pass < 2; ++pass) {
+        const int t = pass == 0 ? (int)blockIdx.x : p.num_tiles - 1 - (int)blockIdx.x;
+        if (pass == 1 && (!p.paired || t <= (int)blockIdx.x)) break;
+        int I, J;
+        tile_coords(p.order, t, p.tiles_m, p.tiles_n, I, J);
+        const int r0 = I * T::BM, c0 = J * T::BN;
+        const int r1 = min(r0 + T::BM, p.M), c1 = min(c0 + T::BN, p.N);
+
+        // k-range of this tile: the k for which some A[i][k] and some B[k][j] are both
+        // inside their structures, widened to whole chunks
+        int klo = 0, khi = p.K;
+        if (p.pa == kLower) khi = min(khi, r1);          // A[i][k] = 0 for k > i
+        if (p.pa == kUpper) klo = max(klo, r0);          // A[i][k] = 0 for k < i
+        if (p.pb == kLower) klo = max(klo, c0);          // B[k][j] = 0 for k < j
+        if (p.pb == kUpper) khi = min(khi, c1);          // B[k][j] = 0 for k > j
+        klo = (klo / T::BK) * T::BK;
+        int nchunks = khi > klo ? (khi - klo + T::BK - 1) / T::BK : 0;
+        if (p.split_k > 1) {                             // this slice's share of the chunks
+            const int per = (nchunks + p.split_k - 1) / p.split_k;
+            const int first = min(slice * per, nchunks);
+            nchunks = min(per, nchunks - first);
+            klo += first * T::BK;
+        }
+
+        const bool a_edge = !p.a_vec || r0 + T::BM > p.M;
+        const bool b_edge = !p.b_vec || c0 + T::BN > p.N;
+        auto mode_a = [&](int kc) {
+            if (a_edge || kc + T::BK > p.K) return 2;
+            if (p.pa == kLower && kc + T::BK - 1 > r0) return 1;
+            if (p.pa == kUpper && kc < r0 + T::BM - 1) return 1;
+            return 0;
+        };
+        auto mode_b = [&](int kc) {
+            if (b_edge || kc + T::BK > p.K) return 2;
+            if (p.pb == kLower && c0 + T::BN - 1 > kc) return 1;
+            if (p.pb == kUpper && kc + T::BK - 1 > c0) return 1;
+            return 0;
+        };
+
+        f32x16 acc[T::FM][T::FN];
+#pragma unroll
+        for (int bi = 0; bi < T::FM; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < T::FN; ++bj)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[bi][bj][v] = 0.0f;
+
+        if (nchunks > 0) {
+            f32x4 ra[T::A_F4], rb[T::B_F4];
+            load_a<T>(p, r0, klo, mode_a(klo), tid, ra);
+            load_b<T>(p, c0, klo, mode_b(klo), tid, rb);
+            stage_to_lds<T>(As, Bs, tid, ra, rb);
+            __syncthreads();
+            for (int c = 0; c < nchunks; ++c) {
+                const int cur = c & 1, nxt = cur ^ 1;
+                const bool more = c + 1 < nchunks;
+                if (more) {                               // next chunk's loads fly under the MFMAs
+                    const int kc = klo + (c + 1) * T::BK;
+                    load_a<T>(p, r0, kc, mode_a(kc), tid, ra);
+                    load_b<T>(p, c0, kc, mode_b(kc), tid, rb);
+                }
+                mfma_chunk<T>(As + cur * T::A_STAGE, Bs + cur * T::B_STAGE, wr0, wc0, l32, half, acc);
+                if (more) stage_to_lds<T>(As + nxt * T::A_STAGE, Bs + nxt * T::B_STAGE, tid, ra, rb);
+                __syncthreads();
+            }
+        }
+
+        // store: full tiles of a general result (or tiles strictly inside the triangle) go out
+        // unchecked; edge and diagonal tiles element by element, the triangle only
+        float *const C = p.C + (int64_t)slice * p.slice_stride;
+        bool plain = r0 + T::BM <= p.M && c0 + T::BN <= p.N;
+        if (p.pc == kLower) plain = plain && c0 + T::BN - 1 <= r0;
+        if (p.pc == kUpper) plain = plain && r0 + T::BM - 1 <= c0;
+#pragma unroll
+        for (int bi = 0; bi < T::FM; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < T::FN; ++bj)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int gi = r0 + wr0 + bi * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                    const int gj = c0 + wc0 + bj * 32 + l32;
+                    if (plain || (gi < p.M && gj < p.N && in_structure(p.pc, gi, gj)))
+                        C[(int64_t)gi * p.ldc + gj] = acc[bi][bj][v];
+                }
+    }
+}
+
+// Sum of split-K slices: C[i][j] = sum_s P[s][i][j]   (general results only)
+__global__ void reduce_slices_kernel(const float *P, int64_t slice_stride, int slices, float *C, int64_t ldc,
+                                     int M, int N)
+{
+    const int64_t total = (int64_t)M * N;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        float s = 0.0f;
+        for (int k = 0; k < slices; ++k) s += P[k * slice_stride + e];
+        C[(e / N) * ldc + (e % N)] = s;
+    }
+}
+
+// out = A restricted to its structure (single surviving factor: A*I -> A)
+__global__ void copy_structure_kernel(const float *A, int64_t lda, float *C, int64_t ldc, int M, int N, int prop)
+{
+    const int64_t total = (int64_t)M * N;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        const int i = (int)(e / N), j = (int)(e % N);
+        if (in_structure(prop, i, j)) C[(int64_t)i * ldc + j] = A[(int64_t)i * lda + j];
+    }
+}
+
+// out = I (every factor was an Identity: I*I = I)
+__global__ void write_identity_kernel(float *C, int64_t ldc, int M)
+{
+    const int64_t total = (int64_t)M * M;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        const int i = (int)(e / M), j = (int)(e % M);
+        C[(int64_t)i * ldc + j] = i == j ? 1.0f : 0.0f;
+    }
+}
+
+// zeros into the half of a triangular result that the product kernel leaves untouched
+__global__ void zero_other_half_kernel(float *C, int64_t ldc, int M, int prop)
+{
+    const int64_t total = (int64_t)M * M;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        const int i = (int)(e / M), j = (int)(e % M);
+        if (!in_structure(prop, i, j)) C[(int64_t)i * ldc + j] = 0.0f;
+    }
+}
+
+}  // namespace mom

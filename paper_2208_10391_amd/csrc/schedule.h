@@ -1,0 +1,77 @@
+// Launch geometry of one binary product: tile shape, tile order, pairing and split-K.
+// Plain integer logic shared by the planner (which sizes the workspace) and the evaluator
+// (which launches); written for the MI355X: 256 compute units in 8 XCDs.
+#pragma once
+#include "plan_internal.h"
+
+namespace mom {
+
+constexpr int kComputeUnits = 256;
+
+// Tile shapes the product kernel is instantiated for.
+enum TileShape : int { kTile128 = 0, kTile64 = 1, kNumTileShapes };
+
+// Order in which workgroups take tiles.  A property clips the k-range of a tile, so tiles
+// differ in length; the longest are handed out first.
+enum TileOrder : int {
+    kRowMajor = 0,     // general*general: all tiles equally long
+    kRowsDesc,         // L*G : tile row I needs k <  (I+1)*BM      -> bottom rows first
+    kRowsAsc,          // U*G : tile row I needs k >= I*BM          -> top rows first
+    kColsAsc,          // G*L : tile col J needs k >= J*BN          -> left columns first
+    kColsDesc,         // G*U : tile col J needs k <  (J+1)*BN      -> right columns first
+    kDiagLower,        // L*L -> L: only I >= J, length I-J+1       -> far diagonals first
+    kDiagUpper,        // U*U -> U: only J >= I, length J-I+1
+    kShellMin,         // L*U : length min(I,J)+1                   -> bottom-right shells first
+    kShellMax          // U*L : length nt - max(I,J)                -> top-left shells first
+};
+
+struct Launch {
+    int shape;             // TileShape
+    int bm, bn;
+    int tiles_m, tiles_n;
+    int num_tiles;         // tiles that exist (a triangular result has no tiles in its zero half)
+    int order;             // TileOrder
+    int paired;            // workgroup b also takes tile num_tiles-1-b (longest with shortest)
+    int grid;              // workgroups
+    int split_k;           // >1: the k-range is cut into this many slices, summed by a second kernel
+    size_t scratch_bytes;  // split_k * m * n floats of partial sums
+};
+
+inline int tile_order(const ProductStep &st)
+{
+    const bool la = st.pa == kLower, ua = st.pa == kUpper, lb = st.pb == kLower, ub = st.pb == kUpper;
+    if (la && lb) return kDiagLower;
+    if (ua && ub) return kDiagUpper;
+    if (la && ub) return kShellMin;
+    if (ua && lb) return kShellMax;
+    if (la) return kRowsDesc;
+    if (ua) return kRowsAsc;
+    if (lb) return kColsAsc;
+    if (ub) return kColsDesc;
+    return kRowMajor;
+}
+
+inline Launch choose_launch(const ProductStep &st)
+{
+    Launch L{};
+    const bool small = st.m <= 64 || st.n <= 64;
+    L.shape = small ? kTile64 : kTile128;
+    L.bm = L.bn = small ? 64 : 128;
+    L.tiles_m = (int)((st.m + L.bm - 1) / L.bm);
+    L.tiles_n = (int)((st.n + L.bn - 1) / L.bn);
+    L.order = tile_order(st);
+    if (L.order == kDiagLower || L.order == kDiagUpper)
+        L.num_tiles = (int)((int64_t)L.tiles_m * (L.tiles_m + 1) / 2);      // square, bm == bn
+    else
+        L.num_tiles = L.tiles_m * L.tiles_n;
+    // Pair the longest tile with the shortest, the second longest with the second shortest,
+    // ...: for the linear length profile of a triangular operand every workgroup then does
+    // the same amount of work.  Only worth it while the pairs still cover the chip.
+    L.paired = (L.order != kRowMajor && L.num_tiles >= 2 * kComputeUnits) ? 1 : 0;
+    L.grid = L.paired ? (L.num_tiles + 1) / 2 : L.num_tiles;
+    L.split_k = 1;
+    L.scratch_bytes = 0;
+    return L;
+}
+
+}  // namespace mom

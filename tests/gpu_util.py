@@ -1,0 +1,92 @@
+"""Helpers of the GPU parity tests: run a chain through the C ABI and compare with the oracle."""
+import numpy as np
+import torch
+
+import oracle
+import paper_2208_10391_amd as mom
+import synthetic_chains as sc
+
+G, L, U, I = 0, 1, 2, 3
+TOL = 1e-4          # max relative Frobenius error against the f64 oracle
+
+
+def rel_fro(got: np.ndarray, want: np.ndarray) -> float:
+    want = want.astype(np.float64)
+    denom = np.linalg.norm(want)
+    num = np.linalg.norm(got.astype(np.float64) - want)
+    return float(num / denom) if denom > 0 else float(num)
+
+
+def structure_mask(prop: int, rows: int, cols: int) -> np.ndarray:
+    ones = np.ones((rows, cols), dtype=bool)
+    if prop == L:
+        return np.tril(ones)
+    if prop == U:
+        return np.triu(ones)
+    if prop == I:
+        return np.eye(rows, cols, dtype=bool)
+    return ones
+
+
+def poison_other_half(t: torch.Tensor, prop: int) -> torch.Tensor:
+    """Device copy of a triangular factor whose zero half holds NaN: the library must not let
+    it reach a result (it only ever reads the triangle)."""
+    if prop not in (L, U):
+        return t
+    nan = torch.full_like(t, float("nan"))
+    keep = torch.tril(torch.ones_like(t, dtype=torch.bool)) if prop == L else torch.triu(torch.ones_like(t, dtype=torch.bool))
+    return torch.where(keep, t, nan)
+
+
+def upload(factors, props, poison=True, pad_cols=0):
+    """Host factors -> device tensors; pad_cols > 0 embeds each in a wider buffer (row stride)."""
+    dev = []
+    for f, p in zip(factors, props):
+        if f is None:
+            dev.append(None)
+            continue
+        d = f.cuda()
+        if poison:
+            d = poison_other_half(d, p)
+        if pad_cols:
+            wide = torch.full((d.shape[0], d.shape[1] + pad_cols), float("nan"), device="cuda", dtype=torch.float32)
+            wide[:, :d.shape[1]] = d
+            d = wide[:, :d.shape[1]]
+        dev.append(d)
+    return dev
+
+
+def eval_chain(dims, props, factors, splits=None, flags=0, poison=True, pad_cols=0, out_pad=0):
+    """Returns (plan, result as numpy with NaN sentinel where nothing was written)."""
+    plan = mom.mom_chain_plan(dims, props) if splits is None else mom.mom_plan_from_splits(dims, props, splits)
+    dev = upload(factors, props, poison, pad_cols)
+    rows, cols, _ = plan.result
+    out_full = torch.full((rows, cols + out_pad), float("nan"), device="cuda", dtype=torch.float32)
+    out = out_full[:, :cols]
+    mom.mom_chain_eval(plan, dev, out=out, flags=flags)
+    torch.cuda.synchronize()
+    res = out_full.cpu().numpy()
+    if out_pad:
+        assert np.all(np.isnan(res[:, cols:])), "wrote beyond the row of the result"
+    return plan, res[:, :cols]
+
+
+def check_against_dense(dims, props, factors, splits=None, flags=0, **kw):
+    plan, got = eval_chain(dims, props, factors, splits, flags, **kw)
+    np_f = [None if f is None else f.numpy() for f in factors]
+    want = oracle.eval_dense(dims, props, np_f)
+    rows, cols, prop = plan.result
+    mask = structure_mask(prop, rows, cols)
+    if prop == I:
+        assert np.array_equal(got, np.eye(rows, dtype=np.float32))
+        return plan, got
+    assert not np.any(np.isnan(got[mask])), "unwritten entries inside the result's structure"
+    err = rel_fro(np.where(mask, got, 0.0), np.where(mask, want, 0.0))
+    assert err <= TOL, "relative Frobenius error %.3e" % err
+    if prop in (L, U):
+        other = got[~mask]
+        if flags & mom.MOM_OUT_ZERO_FILL_TRIANGLE:
+            assert np.all(other == 0.0), "other half must be zero-filled"
+        else:
+            assert np.all(np.isnan(other)), "other half of a triangular result must stay untouched"
+    return plan, got

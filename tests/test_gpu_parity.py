@@ -1,0 +1,142 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2208_10391_amd as mom
+import synthetic_chains as sc
+from gpu_util import G, I, L, TOL, U, check_against_dense, eval_chain, rel_fro, structure_mask, upload
+from helpers import all_preorder_trees, golden_lines, random_chain
+
+pytestmark = pytest.mark.gpu
+
+
+def chain(dims, props, family):
+    return sc.make_chain(dims, props, family)
+
+
+def test_paper_listing_5x5_lower_times_lower():
+    lines = golden_lines("listing_5x5_lower_lower.txt")
+    want = np.array([[float(x) for x in ln.split()] for ln in lines[2:]], dtype=np.float32)
+    a = torch.tril(torch.ones(5, 5))
+    plan, got = eval_chain([5, 5, 5], [L, L], [a, a.clone()])
+    assert plan.result == (5, 5, L)
+    low = np.tril(np.ones((5, 5), dtype=bool))
+    assert np.array_equal(got[low], want[low])            # small integers: exact in f32
+    assert np.all(np.isnan(got[~low]))                    # only the triangle is written
+    _, full = eval_chain([5, 5, 5], [L, L], [a, a.clone()], flags=mom.MOM_OUT_ZERO_FILL_TRIANGLE)
+    assert np.array_equal(full, want)
+
+
+def test_workload_tiny():
+    c = sc.CONFIGS["tiny"]
+    plan, _ = check_against_dense(c.dims, c.props, sc.make_config("tiny"))
+    assert plan.string == "((0 1) 2)"
+
+
+@pytest.mark.parametrize("pa", [G, L, U])
+@pytest.mark.parametrize("pb", [G, L, U])
+@pytest.mark.parametrize("n", [1, 33, 130, 257, 300])
+def test_every_property_pair(pa, pb, n):
+    # several 128- and 64-wide tiles plus a ragged tail; unaligned rows for odd n
+    m = n if pa != G else n + 7
+    c = n if pb != G else max(n - 5, 1)
+    dims, props = [m, n, c], [pa, pb]
+    check_against_dense(dims, props, chain(dims, props, 300 + n))
+
+
+@pytest.mark.parametrize("pa,pb", [(L, L), (U, U), (L, U), (U, L), (L, G), (G, U)])
+def test_zero_fill_flag_and_strided_buffers(pa, pb):
+    n = 200
+    dims, props = [n, n, n], [pa, pb]
+    check_against_dense(dims, props, chain(dims, props, 41), flags=mom.MOM_OUT_ZERO_FILL_TRIANGLE,
+                        pad_cols=12, out_pad=20)
+    check_against_dense(dims, props, chain(dims, props, 42), pad_cols=3, out_pad=1)
+
+
+@pytest.mark.parametrize("m,k,n", [(33, 65, 17), (128, 128, 128), (129, 16, 127), (64, 1000, 64),
+                                   (500, 40, 700), (1, 1, 1), (256, 17, 384), (70, 300, 1)])
+def test_general_product_shapes(m, k, n):
+    dims, props = [m, k, n], [G, G]
+    check_against_dense(dims, props, chain(dims, props, 500 + m))
+
+
+def test_paper_sec4_chain_both_trees():
+    kv = dict(ln.split(" ", 1) for ln in golden_lines("sec4_chain.txt"))
+    dims = [int(x) for x in kv["dims"].split()]
+    props = [G] * 4
+    f = chain(dims, props, 174)
+    plan, a = check_against_dense(dims, props, f)
+    assert plan.string == kv["chosen"]
+    plan2, b = check_against_dense(dims, props, f, splits=oracle.left_to_right_splits(props))
+    assert plan2.string == kv["initial"]
+    assert rel_fro(a, b) <= 2 * TOL
+
+
+def test_identity_rules_bit_exact():
+    a = sc.make_factor(70, 70, G, 9)
+    for dims, props, fac in (([70] * 3, [G, I], [a, None]), ([70] * 3, [I, G], [None, a]),
+                             ([70] * 4, [I, G, I], [None, a, None])):
+        plan, got = eval_chain(dims, props, fac)
+        assert mom.mom_plan_num_products(plan) == 0
+        assert np.array_equal(got, a.numpy())              # A * I = A is a copy
+    lo = sc.make_factor(70, 70, L, 10)
+    plan, got = eval_chain([70] * 3, [L, I], [lo, None])
+    low = np.tril(np.ones((70, 70), dtype=bool))
+    assert plan.result == (70, 70, L)
+    assert np.array_equal(got[low], lo.numpy()[low]) and np.all(np.isnan(got[~low]))
+    plan, got = eval_chain([9] * 3, [I, I], [None, None])
+    assert plan.result == (9, 9, I) and np.array_equal(got, np.eye(9, dtype=np.float32))
+
+
+def test_every_tree_of_a_mixed_chain():
+    dims, props = [90, 90, 90, 90, 90, 50], [L, I, L, U, G]
+    f = chain(dims, props, 77)
+    surv = oracle.survivors(props)
+    results = []
+    for tree in all_preorder_trees(0, len(surv) - 1):
+        splits = [surv[s] for s in tree]
+        plan, got = check_against_dense(dims, props, f, splits=splits)
+        assert plan.cost_mults == oracle.tree_cost(dims, props, splits)[0]
+        results.append(got)
+    assert len(results) == 5
+
+
+def test_random_chains_with_random_properties():
+    rng = np.random.default_rng(99)
+    for trial in range(40):
+        n = int(rng.integers(1, 7))
+        dims, props = random_chain(rng, n, 180)
+        f = chain(dims, props, 600 + trial)
+        plan, _ = check_against_dense(dims, props, f, flags=int(rng.integers(0, 2)))
+        want = oracle.plan_bruteforce(dims, props)
+        assert (plan.cost_mults, plan.splits) == (want["cost"], want["splits"])
+
+
+def test_triangular_temporaries_feed_masked_products():
+    # (L1 L2) is a lowerTri temporary of which only the triangle is written; whatever the
+    # workspace held before must not leak into ((L1 L2) U) G
+    n = 260
+    dims, props = [n, n, n, n, 40], [L, L, U, G]
+    f = chain(dims, props, 88)
+    plan = mom.mom_plan_from_splits(dims, props, [2, 1, 0])
+    assert plan.string == "(((0 1) 2) 3)"
+    dev = upload(f, props)
+    ws = torch.full((plan.workspace_bytes // 4,), float("nan"), device="cuda", dtype=torch.float32)
+    out = mom.mom_chain_eval(plan, dev, workspace=ws)
+    torch.cuda.synchronize()
+    want = oracle.eval_dense(dims, props, [x.numpy() for x in f])
+    assert rel_fro(out.cpu().numpy(), want) <= TOL
+
+
+def test_eval_argument_errors_on_device():
+    p = mom.mom_chain_plan([64, 64, 64, 64], [G, G, G])
+    f = [torch.zeros(64, 64, device="cuda") for _ in range(3)]
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(mom.MomError):
+        mom.mom_chain_eval(p, f, workspace=small)
+    with pytest.raises(ValueError):
+        mom.mom_chain_eval(p, f[:2])
+    with pytest.raises(TypeError):
+        mom.mom_chain_eval(p, [x.cpu() for x in f])

@@ -1,0 +1,164 @@
+"""Host logic of the library (no GPU): planner against the oracle's brute force, error paths,
+exported symbols."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2208_10391_amd as mom
+import synthetic_chains as sc
+from helpers import golden_lines, random_chain
+
+G, L, U, I = 0, 1, 2, 3
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "mom.h")).read()
+    declared = set(re.findall(r"\b(mom_[a-z_]+)\s*\(", header))
+    declared -= {"mom_plan_t"}
+    assert {"mom_chain_plan", "mom_chain_eval", "mom_chain_eval_batched", "mom_plan_from_splits"} <= declared
+    lib = mom.library()
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    from paper_2208_10391_amd import binding
+    assert set(binding.EXPORTS) == declared
+
+
+def test_plans_equal_bruteforce_on_random_chains():
+    rng = np.random.default_rng(2024)
+    checked = 0
+    for trial in range(6000):
+        n = int(rng.integers(1, 10)) if trial % 10 else int(rng.integers(9, 11))
+        if trial >= 3000:
+            n = min(n, 7)
+        dims, props = random_chain(rng, n, 40)
+        want = oracle.plan_bruteforce(dims, props)
+        plan = mom.mom_chain_plan(dims, props)
+        assert plan.cost_mults == want["cost"], (dims, props)
+        assert plan.splits == want["splits"], (dims, props)
+        assert plan.string == oracle.plan_string(props, want["splits"])
+        rows, cols, prop = plan.result
+        assert (rows, cols, prop) == (dims[0], dims[-1], want["result_prop"])
+        assert mom.mom_plan_num_products(plan) == max(want["n_eff"] - 1, 0)
+        checked += 1
+    assert checked == 6000
+
+
+def test_plans_equal_bruteforce_with_few_distinct_dims():
+    # few distinct sizes produce many exact ties: the tie-break must agree as well
+    rng = np.random.default_rng(5)
+    for _ in range(3000):
+        n = int(rng.integers(2, 9))
+        props = [int(rng.choice([G, G, L, U, I])) for _ in range(n)]
+        sizes = [int(rng.choice([2, 4, 8]))]
+        for p in props:
+            sizes.append(sizes[-1] if p != G else int(rng.choice([2, 4, 8])))
+        want = oracle.plan_bruteforce(sizes, props)
+        plan = mom.mom_chain_plan(sizes, props)
+        assert (plan.cost_mults, plan.splits) == (want["cost"], want["splits"]), (sizes, props)
+
+
+def test_workload_plans():
+    for ln in golden_lines("workload_plans.txt"):
+        w = ln.split(" ", 5)
+        c = sc.CONFIGS[w[1]]
+        plan = mom.mom_chain_plan(c.dims, c.props)
+        assert plan.cost_mults == int(w[3]) and plan.string == w[5]
+
+
+def test_paper_sec4_chain_and_forced_initial_tree():
+    kv = dict(ln.split(" ", 1) for ln in golden_lines("sec4_chain.txt"))
+    dims = [int(x) for x in kv["dims"].split()]
+    plan = mom.mom_chain_plan(dims, [G] * 4)
+    assert plan.string == kv["chosen"] and plan.cost_mults == int(kv["chosen_mults"])
+    forced = mom.mom_plan_from_splits(dims, [G] * 4, oracle.left_to_right_splits([G] * 4))
+    assert forced.string == kv["initial"] and forced.cost_mults == int(kv["initial_mults"])
+
+
+def test_forced_trees_cost_like_the_oracle():
+    c = sc.CONFIGS["mixed5"]
+    for splits, text in (([2, 0, 3], "((0 2) (3 4))"), ([3, 2, 0], "(((0 2) 3) 4)"), ([0, 2, 3], "(0 (2 (3 4)))")):
+        plan = mom.mom_plan_from_splits(c.dims, c.props, splits)
+        assert plan.string == text
+        assert plan.cost_mults == oracle.tree_cost(c.dims, c.props, splits)[0]
+        assert plan.splits == splits
+
+
+def test_listing_5x5_plan():
+    plan = mom.mom_chain_plan([5, 5, 5], [L, L])
+    assert plan.cost_mults == 35 and plan.result == (5, 5, L) and plan.string == "(0 1)"
+    assert plan.workspace_bytes == 0
+
+
+def test_degenerate_chains():
+    p = mom.mom_chain_plan([7, 7, 7], [I, I])
+    assert (p.string, p.cost_mults, p.result, mom.mom_plan_num_products(p)) == ("I", 0, (7, 7, I), 0)
+    p = mom.mom_chain_plan([7, 7, 7, 7], [I, U, I])
+    assert (p.string, p.cost_mults, p.result, p.splits) == ("1", 0, (7, 7, U), [])
+    p = mom.mom_chain_plan([3, 9], [G])
+    assert (p.string, p.result) == ("0", (3, 9, G))
+
+
+def test_workspace_reuses_released_temporaries():
+    # right-nested chain of equal squares: two temporaries alternate, never more
+    n, k = 64, 6
+    plan = mom.mom_plan_from_splits([n] * (k + 1), [G] * k, list(range(k - 1)))
+    assert plan.string == "(0 (1 (2 (3 (4 5)))))"
+    assert plan.workspace_bytes == 2 * n * n * 4
+
+
+def status_of(fn, *args):
+    with pytest.raises(mom.MomError) as e:
+        fn(*args)
+    return e.value.status
+
+
+def test_error_paths():
+    names = __import__("paper_2208_10391_amd.binding", fromlist=["x"]).STATUS_NAMES
+    code = {n: i for i, n in enumerate(names)}
+    assert status_of(mom.mom_chain_plan, [4], []) == code["MOM_ERR_BAD_N"]
+    assert status_of(mom.mom_chain_plan, [4, 0], [G]) == code["MOM_ERR_BAD_DIM"]
+    assert status_of(mom.mom_chain_plan, [4, -3], [G]) == code["MOM_ERR_BAD_DIM"]
+    assert status_of(mom.mom_chain_plan, [4, 2 ** 31], [G]) == code["MOM_ERR_BAD_DIM"]
+    assert status_of(mom.mom_chain_plan, [4, 4], [7]) == code["MOM_ERR_BAD_PROP"]
+    for p in (L, U, I):
+        assert status_of(mom.mom_chain_plan, [4, 5], [p]) == code["MOM_ERR_NOT_SQUARE"]
+    assert status_of(mom.mom_plan_from_splits, [4, 4, 4, 4], [G, G, G], [2, 0]) == code["MOM_ERR_BAD_SPLITS"]
+    assert status_of(mom.mom_plan_from_splits, [4, 4, 4, 4], [G, G, G], [0, 0]) == code["MOM_ERR_BAD_SPLITS"]
+    assert status_of(mom.mom_plan_from_splits, [4, 4, 4, 4], [G, I, G], [1]) == code["MOM_ERR_BAD_SPLITS"]
+    assert status_of(mom.mom_plan_from_splits, [4, 4, 4, 4], [G, G, G], [0]) == code["MOM_ERR_BAD_SPLITS"]
+    # 2^31-1 cubed, three times over, does not fit in 64 bits
+    big = 2 ** 31 - 1
+    assert status_of(mom.mom_chain_plan, [big] * 5, [G] * 4) == code["MOM_ERR_OVERFLOW"]
+    lib = mom.library()
+    assert lib.mom_chain_plan(None, None, 1, None) == code["MOM_ERR_NULL"]
+    out = ctypes.c_void_p(123)
+    assert lib.mom_chain_plan(None, None, 1, ctypes.byref(out)) == code["MOM_ERR_NULL"] and not out.value
+    p = mom.mom_chain_plan([4, 4, 4], [G, G])
+    small = ctypes.create_string_buffer(3)
+    assert lib.mom_plan_string(p.handle, small, 3) == code["MOM_ERR_BUFFER_TOO_SMALL"]
+    assert lib.mom_plan_splits(p.handle, (ctypes.c_int32 * 1)(), 0) == code["MOM_ERR_BUFFER_TOO_SMALL"]
+    # evaluation argument checks that need no GPU: nothing is launched on these paths
+    assert lib.mom_chain_eval(p.handle, None, None, None, 0, None, 0, 0, None) == code["MOM_ERR_NULL"]
+    assert lib.mom_chain_eval(None, None, None, None, 0, None, 0, 0, None) == code["MOM_ERR_NULL"]
+    fake = (ctypes.c_void_p * 2)(256, 512)
+    fptr = ctypes.cast(fake, ctypes.POINTER(ctypes.c_void_p))
+    lds = (ctypes.c_int64 * 2)(3, 4)
+    assert lib.mom_chain_eval(p.handle, fptr, lds, ctypes.c_void_p(1024), 0, None, 0, 0, None) == code["MOM_ERR_BAD_STRIDE"]
+    assert lib.mom_chain_eval(p.handle, fptr, None, ctypes.c_void_p(1024), 2, None, 0, 0, None) == code["MOM_ERR_BAD_STRIDE"]
+    p3 = mom.mom_chain_plan([4, 4, 4, 4], [G, G, G])
+    fake3 = (ctypes.c_void_p * 3)(256, 512, 768)
+    fptr3 = ctypes.cast(fake3, ctypes.POINTER(ctypes.c_void_p))
+    assert p3.workspace_bytes > 0
+    assert lib.mom_chain_eval(p3.handle, fptr3, None, ctypes.c_void_p(1024), 0, None, 0, 0, None) == code["MOM_ERR_WORKSPACE"]
+    assert lib.mom_chain_eval(p3.handle, fptr3, None, ctypes.c_void_p(1024), 0, ctypes.c_void_p(4096), 8, 0, None) == code["MOM_ERR_WORKSPACE"]
+    assert lib.mom_chain_eval(p3.handle, fptr3, None, ctypes.c_void_p(1024), 0, ctypes.c_void_p(4100), 1 << 20, 0, None) == code["MOM_ERR_WORKSPACE"]
+    pbig = mom.mom_chain_plan([33, 33, 33], [G, G])
+    assert lib.mom_chain_eval_batched(pbig.handle, fptr, None, ctypes.c_void_p(1024), 0, 4, None) == code["MOM_ERR_UNSUPPORTED"]
+    assert lib.mom_chain_eval_batched(p.handle, fptr, None, ctypes.c_void_p(1024), 0, -1, None) == code["MOM_ERR_BAD_N"]
+    assert lib.mom_chain_eval_batched(p.handle, fptr, (ctypes.c_int64 * 2)(15, 16), ctypes.c_void_p(1024), 0, 4, None) == code["MOM_ERR_BAD_STRIDE"]
+    assert mom.mom_status_string(0) == "ok" and "square" in mom.mom_status_string(code["MOM_ERR_NOT_SQUARE"])
