@@ -13,9 +13,9 @@ namespace {
 
 using namespace mom;
 
-// 128x128x16 tiles, 4 wavefronts of 64x64: the workhorse.  64x64x16 tiles, 4 wavefronts of
+// 128x128x32 tiles, 4 wavefronts of 64x64: the workhorse.  64x64x16 tiles, 4 wavefronts of
 // 32x32: products with a short side.
-typedef TileConfig<128, 128, 16, 2, 2, 2> Tile128;
+typedef TileConfig<128, 128, 32, 2, 2, 2> Tile128;
 typedef TileConfig<64, 64, 16, 2, 2, 2> Tile64;
 
 template <class T>

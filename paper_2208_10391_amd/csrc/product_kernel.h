@@ -93,6 +93,7 @@ struct TileConfig {
     static constexpr int A_F4 = BM * BK / 4 / NT;     // 16-byte loads per thread and chunk
     static constexpr int B_F4 = BK * BN / 4 / NT;
     static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BK % 8 == 0, "tile shape");
+    static_assert(BM % BK == 0 && BN % BK == 0, "diagonals must fall on chunk boundaries");
     static_assert((BM * BK / 4) % NT == 0 && (BK * BN / 4) % NT == 0, "load decomposition");
 };
 
@@ -104,27 +105,37 @@ template <class T>
 __device__ __forceinline__ void load_a(const ProductParams &p, int r0, int kc, int mode, int tid,
                                        f32x4 (&ra)[T::A_F4])
 {
+    if (mode == 0) {
 #pragma unroll
-    for (int q = 0; q < T::A_F4; ++q) {
-        const int idx = tid + q * T::NT;
-        const int gi = r0 + idx / (T::BK / 4);
-        const int gk = kc + (idx % (T::BK / 4)) * 4;
-        const float *src = p.A + (int64_t)gi * p.lda + gk;
-        f32x4 v;
-        if (mode == 0) {
-            v = *reinterpret_cast<const f32x4 *>(src);
-        } else if (mode == 1) {
-            v = *reinterpret_cast<const f32x4 *>(src);
+        for (int q = 0; q < T::A_F4; ++q) {
+            const int idx = tid + q * T::NT;
+            const int gi = r0 + idx / (T::BK / 4), gk = kc + (idx % (T::BK / 4)) * 4;
+            ra[q] = *reinterpret_cast<const f32x4 *>(p.A + (int64_t)gi * p.lda + gk);
+        }
+    } else if (mode == 1) {
+#pragma unroll
+        for (int q = 0; q < T::A_F4; ++q) {
+            const int idx = tid + q * T::NT;
+            const int gi = r0 + idx / (T::BK / 4), gk = kc + (idx % (T::BK / 4)) * 4;
+            f32x4 v = *reinterpret_cast<const f32x4 *>(p.A + (int64_t)gi * p.lda + gk);
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] = in_structure(p.pa, gi, gk + e) ? v[e] : 0.0f;
-        } else {
+            ra[q] = v;
+        }
+    } else {
+#pragma unroll
+        for (int q = 0; q < T::A_F4; ++q) {
+            const int idx = tid + q * T::NT;
+            const int gi = r0 + idx / (T::BK / 4), gk = kc + (idx % (T::BK / 4)) * 4;
+            const float *src = p.A + (int64_t)gi * p.lda + gk;
+            f32x4 v;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const bool ok = gi < p.M && gk + e < p.K && in_structure(p.pa, gi, gk + e);
                 v[e] = ok ? src[e] : 0.0f;
             }
+            ra[q] = v;
         }
-        ra[q] = v;
     }
 }
 
@@ -132,27 +143,37 @@ template <class T>
 __device__ __forceinline__ void load_b(const ProductParams &p, int c0, int kc, int mode, int tid,
                                        f32x4 (&rb)[T::B_F4])
 {
+    if (mode == 0) {
 #pragma unroll
-    for (int q = 0; q < T::B_F4; ++q) {
-        const int idx = tid + q * T::NT;
-        const int gk = kc + idx / (T::BN / 4);
-        const int gj = c0 + (idx % (T::BN / 4)) * 4;
-        const float *src = p.B + (int64_t)gk * p.ldb + gj;
-        f32x4 v;
-        if (mode == 0) {
-            v = *reinterpret_cast<const f32x4 *>(src);
-        } else if (mode == 1) {
-            v = *reinterpret_cast<const f32x4 *>(src);
+        for (int q = 0; q < T::B_F4; ++q) {
+            const int idx = tid + q * T::NT;
+            const int gk = kc + idx / (T::BN / 4), gj = c0 + (idx % (T::BN / 4)) * 4;
+            rb[q] = *reinterpret_cast<const f32x4 *>(p.B + (int64_t)gk * p.ldb + gj);
+        }
+    } else if (mode == 1) {
+#pragma unroll
+        for (int q = 0; q < T::B_F4; ++q) {
+            const int idx = tid + q * T::NT;
+            const int gk = kc + idx / (T::BN / 4), gj = c0 + (idx % (T::BN / 4)) * 4;
+            f32x4 v = *reinterpret_cast<const f32x4 *>(p.B + (int64_t)gk * p.ldb + gj);
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] = in_structure(p.pb, gk, gj + e) ? v[e] : 0.0f;
-        } else {
+            rb[q] = v;
+        }
+    } else {
+#pragma unroll
+        for (int q = 0; q < T::B_F4; ++q) {
+            const int idx = tid + q * T::NT;
+            const int gk = kc + idx / (T::BN / 4), gj = c0 + (idx % (T::BN / 4)) * 4;
+            const float *src = p.B + (int64_t)gk * p.ldb + gj;
+            f32x4 v;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const bool ok = gk < p.K && gj + e < p.N && in_structure(p.pb, gk, gj + e);
                 v[e] = ok ? src[e] : 0.0f;
             }
+            rb[q] = v;
         }
-        rb[q] = v;
     }
 }
 
@@ -172,32 +193,48 @@ __device__ __forceinline__ void stage_to_lds(float *As, float *Bs, int tid,
     }
 }
 
-// One k-chunk of MFMA work from LDS.  Within each group of 8 k-values, MFMA step e (0..3)
-// multiplies k = 4*half + e, so that a lane fetches its four A values with one 16-byte read;
-// the order of summation over k is free.
+// MFMA operands of one group of 8 k-values: lane (l32, half) takes A[row l32][k = 4*half + e]
+// for e = 0..3 with one 16-byte LDS read per 32-row block, and B[k = 4*half + e][col l32].
 template <class T>
-__device__ __forceinline__ void mfma_chunk(const float *As, const float *Bs, int wr0, int wc0, int l32, int half,
-                                           f32x16 (&acc)[T::FM][T::FN])
+__device__ __forceinline__ void load_fragments(const float *As, const float *Bs, int kg, int wr0, int wc0, int l32,
+                                               int half, f32x4 (&a)[T::FM], float (&b)[T::FN][4])
 {
 #pragma unroll
+    for (int bi = 0; bi < T::FM; ++bi)
+        a[bi] = *reinterpret_cast<const f32x4 *>(As + (wr0 + bi * 32 + l32) * T::LDA + kg * 8 + 4 * half);
+#pragma unroll
+    for (int bj = 0; bj < T::FN; ++bj)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            b[bj][e] = Bs[(kg * 8 + 4 * half + e) * T::LDB + wc0 + bj * 32 + l32];
+}
+
+// One k-chunk of MFMA work from LDS.  Within each group of 8 k-values, MFMA step e (0..3)
+// multiplies k = 4*half + e (the order of summation over k is free).  The operands of the
+// next group are fetched from LDS before the MFMAs of the current one are issued, so the
+// matrix pipe does not wait on LDS latency.  `between` runs once, after the first operand
+// reads have been issued and before the first MFMA: the place for the memory traffic of the
+// software pipeline (LDS writes of the next chunk, global loads of the one after).
+template <class T, class Between>
+__device__ __forceinline__ void mfma_chunk(const float *As, const float *Bs, int wr0, int wc0, int l32, int half,
+                                           f32x16 (&acc)[T::FM][T::FN], Between between)
+{
+    f32x4 a[2][T::FM];
+    float b[2][T::FN][4];
+    load_fragments<T>(As, Bs, 0, wr0, wc0, l32, half, a[0], b[0]);
+    between();
+#pragma unroll
     for (int kg = 0; kg < T::BK / 8; ++kg) {
-        f32x4 a[T::FM];
-        float b[T::FN][4];
-#pragma unroll
-        for (int bi = 0; bi < T::FM; ++bi)
-            a[bi] = *reinterpret_cast<const f32x4 *>(As + (wr0 + bi * 32 + l32) * T::LDA + kg * 8 + 4 * half);
-#pragma unroll
-        for (int bj = 0; bj < T::FN; ++bj)
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                b[bj][e] = Bs[(kg * 8 + 4 * half + e) * T::LDB + wc0 + bj * 32 + l32];
+        if (kg + 1 < T::BK / 8) load_fragments<T>(As, Bs, kg + 1, wr0, wc0, l32, half, a[(kg + 1) & 1], b[(kg + 1) & 1]);
+        __builtin_amdgcn_sched_barrier(0);      // keep the LDS reads ahead of this group's MFMAs
 #pragma unroll
         for (int e = 0; e < 4; ++e)
 #pragma unroll
             for (int bi = 0; bi < T::FM; ++bi)
 #pragma unroll
                 for (int bj = 0; bj < T::FN; ++bj)
-                    acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[bi][e], b[bj][e], acc[bi][bj], 0, 0, 0);
+                    acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[kg & 1][bi][e], b[kg & 1][bj][e], acc[bi][bj],
+                                                                       0, 0, 0);
     }
 }
 
@@ -260,22 +297,61 @@ __global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const Pro
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[bi][bj][v] = 0.0f;
 
+        // Chunks [f_lo, f_hi) are interior for both operands (mode 0): in bounds, aligned and
+        // clear of every diagonal.  What a property or an edge makes special is always a run
+        // of chunks at the head and a run at the tail of the k-range.
+        int f_lo = 0, f_hi = 0;
+        if (!a_edge && !b_edge) {
+            int k_from = klo, k_to = (p.K / T::BK) * T::BK;
+            if (p.pa == kUpper) k_from = max(k_from, r0 + T::BM);
+            if (p.pb == kLower) k_from = max(k_from, c0 + T::BN);
+            if (p.pa == kLower) k_to = min(k_to, r0);
+            if (p.pb == kUpper) k_to = min(k_to, c0);
+            f_lo = min((k_from - klo) / T::BK, nchunks);
+            f_hi = max(min((k_to - klo) / T::BK, nchunks), f_lo);
+        }
+
         if (nchunks > 0) {
             f32x4 ra[T::A_F4], rb[T::B_F4];
-            load_a<T>(p, r0, klo, mode_a(klo), tid, ra);
-            load_b<T>(p, c0, klo, mode_b(klo), tid, rb);
-            stage_to_lds<T>(As, Bs, tid, ra, rb);
-            __syncthreads();
-            for (int c = 0; c < nchunks; ++c) {
-                const int cur = c & 1, nxt = cur ^ 1;
-                const bool more = c + 1 < nchunks;
-                if (more) {                               // next chunk's loads fly under the MFMAs
-                    const int kc = klo + (c + 1) * T::BK;
+            // per-thread source addresses of chunk 0; interior chunks step along k from here
+            const float *a_src[T::A_F4], *b_src[T::B_F4];
+#pragma unroll
+            for (int q = 0; q < T::A_F4; ++q) {
+                const int idx = tid + q * T::NT;
+                a_src[q] = p.A + (int64_t)(r0 + idx / (T::BK / 4)) * p.lda + klo + (idx % (T::BK / 4)) * 4;
+            }
+#pragma unroll
+            for (int q = 0; q < T::B_F4; ++q) {
+                const int idx = tid + q * T::NT;
+                b_src[q] = p.B + (int64_t)(klo + idx / (T::BN / 4)) * p.ldb + c0 + (idx % (T::BN / 4)) * 4;
+            }
+            // Software pipeline, two LDS stages.  While chunk c is multiplied out of stage c&1,
+            // chunk c+1 (loaded from HBM during the previous iteration) moves from registers
+            // into the other stage and the loads of chunk c+2 are issued into the same
+            // registers; one barrier per chunk.
+            auto fetch = [&](int j) {                     // chunk j: global -> registers
+                if (j >= f_lo && j < f_hi) {
+                    const int64_t a_step = (int64_t)j * T::BK, b_step = a_step * p.ldb;
+#pragma unroll
+                    for (int q = 0; q < T::A_F4; ++q) ra[q] = *reinterpret_cast<const f32x4 *>(a_src[q] + a_step);
+#pragma unroll
+                    for (int q = 0; q < T::B_F4; ++q) rb[q] = *reinterpret_cast<const f32x4 *>(b_src[q] + b_step);
+                } else if (j < nchunks) {
+                    const int kc = klo + j * T::BK;
                     load_a<T>(p, r0, kc, mode_a(kc), tid, ra);
                     load_b<T>(p, c0, kc, mode_b(kc), tid, rb);
                 }
-                mfma_chunk<T>(As + cur * T::A_STAGE, Bs + cur * T::B_STAGE, wr0, wc0, l32, half, acc);
-                if (more) stage_to_lds<T>(As + nxt * T::A_STAGE, Bs + nxt * T::B_STAGE, tid, ra, rb);
+            };
+            fetch(0);
+            stage_to_lds<T>(As, Bs, tid, ra, rb);
+            fetch(1);
+            __syncthreads();
+            for (int c = 0; c < nchunks; ++c) {
+                const int cur = c & 1, nxt = cur ^ 1;
+                mfma_chunk<T>(As + cur * T::A_STAGE, Bs + cur * T::B_STAGE, wr0, wc0, l32, half, acc, [&]() {
+                    if (c + 1 < nchunks) stage_to_lds<T>(As + nxt * T::A_STAGE, Bs + nxt * T::B_STAGE, tid, ra, rb);
+                    fetch(c + 2);
+                });
                 __syncthreads();
             }
         }
