@@ -9,6 +9,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <vector>
+
 namespace {
 
 using namespace mom;
@@ -19,7 +21,7 @@ typedef TileConfig<128, 128, 32, 2, 2, 2> Tile128;
 typedef TileConfig<64, 64, 16, 2, 2, 2> Tile64;
 
 template <class T>
-hipError_t launch_product(const ProductParams &p, int grid_x, int grid_y, hipStream_t stream)
+hipError_t launch_product(const ProductBatch &batch, hipStream_t stream)
 {
     static bool configured[64] = {};
     int dev = 0;
@@ -31,7 +33,8 @@ hipError_t launch_product(const ProductParams &p, int grid_x, int grid_y, hipStr
         if (e != hipSuccess) return e;
         configured[dev] = true;
     }
-    hipLaunchKernelGGL(product_kernel<T>, dim3(grid_x, grid_y), dim3(T::NT), T::LDS_BYTES, stream, p);
+    hipLaunchKernelGGL(product_kernel<T>, dim3(batch.block_end[batch.count - 1]), dim3(T::NT), T::LDS_BYTES, stream,
+                       batch);
     return hipGetLastError();
 }
 
@@ -79,38 +82,72 @@ extern "C" mom_status_t mom_chain_eval(const mom_plan_t *plan, const float *cons
         if (hipGetLastError() != hipSuccess) return MOM_ERR_HIP;
     }
 
-    for (const ProductStep &st : plan->steps) {
-        auto resolve = [&](const Operand &o, int64_t cols) {
-            if (o.where == Where::Factor) return factor(o.index);
-            if (o.where == Where::Temp)
-                return Resolved{reinterpret_cast<const float *>(ws + plan->temps[o.index].offset), cols};
-            return Resolved{d_out, ld_out};
-        };
-        const Resolved a = resolve(st.a, st.k), b = resolve(st.b, st.n), c = resolve(st.c, st.n);
-        const Launch L = choose_launch(st);
-        ProductParams p{};
-        p.A = a.ptr; p.B = b.ptr; p.C = const_cast<float *>(c.ptr);
-        p.lda = a.ld; p.ldb = b.ld; p.ldc = c.ld;
-        p.M = (int)st.m; p.N = (int)st.n; p.K = (int)st.k;
-        p.pa = st.pa; p.pb = st.pb; p.pc = st.pc;
-        p.tiles_m = L.tiles_m; p.tiles_n = L.tiles_n; p.num_tiles = L.num_tiles;
-        p.order = L.order; p.paired = L.paired;
-        p.a_vec = aligned16(a.ptr, a.ld); p.b_vec = aligned16(b.ptr, b.ld);
-        p.split_k = L.split_k;
-        p.slice_stride = 0;
-        if (L.split_k > 1) {                               // partial sums go to the scratch region
-            p.C = reinterpret_cast<float *>(ws + plan->scratch_offset);
-            p.ldc = st.n;
-            p.slice_stride = st.m * st.n;
+    // Level by level; the products of a level that share a tile shape go out in one launch
+    // (at most kMaxFused at a time), followed by one launch that sums their split-K slices.
+    auto resolve = [&](const Operand &o, int64_t cols) {
+        if (o.where == Where::Factor) return factor(o.index);
+        if (o.where == Where::Temp)
+            return Resolved{reinterpret_cast<const float *>(ws + plan->temps[o.index].offset), cols};
+        return Resolved{d_out, ld_out};
+    };
+    size_t next = 0;
+    while (next < plan->order.size()) {
+        const int level = plan->steps[plan->order[next]].level;
+        size_t level_end = next;
+        while (level_end < plan->order.size() && plan->steps[plan->order[level_end]].level == level) ++level_end;
+        std::vector<bool> done(level_end - next, false);
+        for (size_t first = next; first < level_end; ++first) {
+            if (done[first - next]) continue;
+            const int shape = choose_launch(plan->steps[plan->order[first]]).shape;
+            ProductBatch batch{};
+            ReduceBatch reduce{};
+            int64_t reduce_quads = 0;
+            bool batch_small = true;
+            for (size_t i = first; i < level_end && batch.count < kMaxFused; ++i) {
+                const ProductStep &st = plan->steps[plan->order[i]];
+                const Launch L = choose_launch(st);
+                if (done[i - next] || L.shape != shape) continue;
+                // only small products share a launch: a big one fills the chip by itself and
+                // keeps its longest-first tile order only when it is alone
+                const bool small_launch = (int64_t)L.grid * L.split_k <= 4 * kComputeUnits;
+                if (batch.count > 0 && (!small_launch || !batch_small)) continue;
+                batch_small = small_launch;
+                done[i - next] = true;
+                const Resolved a = resolve(st.a, st.k), b = resolve(st.b, st.n), c = resolve(st.c, st.n);
+                ProductParams &p = batch.prob[batch.count];
+                p.A = a.ptr; p.B = b.ptr; p.C = const_cast<float *>(c.ptr);
+                p.lda = a.ld; p.ldb = b.ld; p.ldc = c.ld;
+                p.M = (int)st.m; p.N = (int)st.n; p.K = (int)st.k;
+                p.pa = st.pa; p.pb = st.pb; p.pc = st.pc;
+                p.tiles_m = L.tiles_m; p.tiles_n = L.tiles_n; p.num_tiles = L.num_tiles;
+                p.order = L.order; p.paired = L.paired; p.grid = L.grid;
+                p.a_vec = aligned16(a.ptr, a.ld); p.b_vec = aligned16(b.ptr, b.ld);
+                p.split_k = L.split_k;
+                p.slice_stride = 0;
+                if (L.split_k > 1) {                       // partial sums go to the scratch region
+                    p.C = reinterpret_cast<float *>(ws + plan->scratch_offset + st.scratch_offset);
+                    p.ldc = st.n;
+                    p.slice_stride = st.m * st.n;
+                    ReduceParams &r = reduce.prob[reduce.count++];
+                    r.P = p.C; r.C = const_cast<float *>(c.ptr);
+                    r.slice_stride = p.slice_stride; r.ldc = c.ld;
+                    r.slices = L.split_k; r.M = p.M; r.N = p.N;
+                    reduce_quads = std::max<int64_t>(reduce_quads, (st.m * st.n + 3) / 4);
+                }
+                const int64_t blocks = (int64_t)(batch.count ? batch.block_end[batch.count - 1] : 0) + (int64_t)L.grid * L.split_k;
+                if (blocks > 0x7fffffff) return MOM_ERR_UNSUPPORTED;
+                batch.block_end[batch.count++] = (int)blocks;
+            }
+            const hipError_t e = shape == kTile128 ? launch_product<Tile128>(batch, stream)
+                                                   : launch_product<Tile64>(batch, stream);
+            if (e != hipSuccess) return MOM_ERR_HIP;
+            if (reduce.count > 0) {
+                hipLaunchKernelGGL(reduce_slices_kernel, dim3((unsigned)std::min<int64_t>((reduce_quads + 31) / 32, 8192), reduce.count),
+                                   dim3(256), 0, stream, reduce);
+                if (hipGetLastError() != hipSuccess) return MOM_ERR_HIP;
+            }
         }
-        hipError_t e = L.shape == kTile128 ? launch_product<Tile128>(p, L.grid, L.split_k, stream)
-                                           : launch_product<Tile64>(p, L.grid, L.split_k, stream);
-        if (e != hipSuccess) return MOM_ERR_HIP;
-        if (L.split_k > 1) {
-            hipLaunchKernelGGL(reduce_slices_kernel, dim3(elementwise_grid(st.m * st.n)), dim3(256), 0, stream,
-                               p.C, p.slice_stride, L.split_k, const_cast<float *>(c.ptr), c.ld, p.M, p.N);
-            if (hipGetLastError() != hipSuccess) return MOM_ERR_HIP;
-        }
+        next = level_end;
     }
 
     if (zero_fill && (plan->result_prop == kLower || plan->result_prop == kUpper)) {

@@ -108,7 +108,7 @@ struct Builder {
     const std::vector<int64_t> &d;     // dims of the survivors chain
     const std::vector<int32_t> &p;     // props of the survivors chain
     const std::vector<int32_t> &split_pos;   // preorder, positions in the survivors chain
-    Arena arena;
+    std::vector<int> producer;         // temporary id -> index of the step that writes it
     size_t cursor = 0;
     int depth = 0, max_depth = 0;
     u128 total = 0;
@@ -136,17 +136,19 @@ struct Builder {
         const u128 c = product_mults(st.m, st.k, st.n, st.pa, st.pb);
         total += c;
         st.mults = c > kU64Max ? std::numeric_limits<uint64_t>::max() : (uint64_t)c;
+        auto level_of = [&](const mom::Operand &o) {
+            return o.where == mom::Where::Temp ? plan->steps[producer[o.index]].level : 0;
+        };
+        st.level = 1 + std::max(level_of(a.op), level_of(b.op));
+        st.scratch_offset = 0;
         if (is_root) {
             st.c = {mom::Where::Out, 0};
         } else {
-            const size_t bytes = (size_t)st.m * (size_t)st.n * sizeof(float);
-            const size_t off = arena.alloc(bytes);
-            plan->temps.push_back({off, bytes});
+            plan->temps.push_back({0, (size_t)st.m * (size_t)st.n * sizeof(float)});
+            producer.push_back((int)plan->steps.size());
             st.c = {mom::Where::Temp, (int)plan->temps.size() - 1};
         }
         plan->steps.push_back(st);
-        for (const mom::Operand &o : {a.op, b.op})
-            if (o.where == mom::Where::Temp) arena.release(plan->temps[o.index].offset, plan->temps[o.index].bytes);
         --depth;    // two operands popped, one result pushed
         return Value{st.c, st.m, st.n, st.pc};
     }
@@ -179,22 +181,44 @@ mom_status_t finish(mom_plan *plan, const std::vector<int64_t> &d, const std::ve
         return MOM_OK;
     }
     if ((int)split_pos.size() != m - 1) return MOM_ERR_BAD_SPLITS;
-    Builder b{plan, d, p, split_pos};
+    Builder b{plan, d, p, split_pos, {}};
     Builder::Value root = b.walk(0, m - 1, true);
     if (!b.ok || b.cursor != split_pos.size()) return MOM_ERR_BAD_SPLITS;
     if (b.total > kU64Max) return MOM_ERR_OVERFLOW;
     plan->cost = (uint64_t)b.total;
     plan->result_prop = root.prop;
     plan->stack_depth = b.max_depth;
-    plan->temp_bytes = b.arena.peak();
     plan->splits.clear();
     for (int s : split_pos) plan->splits.push_back(plan->survivors[s]);
     size_t cursor = 0;
     render(plan, split_pos, cursor, 0, m - 1, plan->text);
-    // split-K partial sums live behind the temporaries; products run one after the other on
-    // one stream, so a single region sized for the hungriest product serves all of them
+
+    // Evaluation order: level by level.  The products of one level do not depend on each
+    // other, so the evaluator may put them into one launch; a temporary lives from the level
+    // that writes it to the level that reads it.  Split-K partial sums of a level's products
+    // sit side by side in a scratch region behind the temporaries.
+    int top = 0;
+    for (const mom::ProductStep &st : plan->steps) top = std::max(top, st.level);
+    Arena arena;
     size_t scratch = 0;
-    for (const mom::ProductStep &st : plan->steps) scratch = std::max(scratch, mom::choose_launch(st).scratch_bytes);
+    for (int level = 1; level <= top; ++level) {
+        size_t level_scratch = 0;
+        for (size_t i = 0; i < plan->steps.size(); ++i) {
+            mom::ProductStep &st = plan->steps[i];
+            if (st.level != level) continue;
+            plan->order.push_back((int32_t)i);
+            if (st.c.where == mom::Where::Temp) plan->temps[st.c.index].offset = arena.alloc(plan->temps[st.c.index].bytes);
+            st.scratch_offset = level_scratch;
+            level_scratch += (mom::choose_launch(st).scratch_bytes + 255) & ~(size_t)255;
+        }
+        scratch = std::max(scratch, level_scratch);
+        for (const mom::ProductStep &st : plan->steps) {
+            if (st.level != level) continue;
+            for (const mom::Operand &o : {st.a, st.b})
+                if (o.where == mom::Where::Temp) arena.release(plan->temps[o.index].offset, plan->temps[o.index].bytes);
+        }
+    }
+    plan->temp_bytes = arena.peak();
     plan->scratch_offset = (plan->temp_bytes + 255) & ~(size_t)255;
     plan->scratch_bytes = scratch;
     plan->workspace_bytes = scratch ? plan->scratch_offset + scratch : plan->temp_bytes;

@@ -23,6 +23,9 @@ struct ProductStep {
     int64_t m, k, n;
     int pa, pb, pc;            // properties of A, B and of the result
     uint64_t mults;            // scalar multiplications with no structurally-zero operand
+    int level;                 // 1 + the highest level among the products it consumes (factors: 0);
+                               // products of one level are independent of each other
+    size_t scratch_offset;     // split-K partial sums: bytes from the start of the scratch region
 };
 
 struct Temp {
@@ -42,7 +45,8 @@ struct mom_plan {
     uint64_t cost = 0;
     int64_t rows = 0, cols = 0;
     int32_t result_prop = 0;
-    std::vector<mom::ProductStep> steps;
+    std::vector<mom::ProductStep> steps;      // post-order
+    std::vector<int32_t> order;              // indices into steps, by level: the evaluation order
     std::vector<mom::Temp> temps;
     size_t temp_bytes = 0;           // bytes of workspace used by temporaries
     size_t scratch_offset = 0;       // split-K partial sums start here

@@ -31,8 +31,17 @@ struct ProductParams {
     int M, N, K;
     int pa, pb, pc;
     int tiles_m, tiles_n, num_tiles, order, paired;
+    int grid;              // workgroups per k-slice
     int a_vec, b_vec;      // 16-byte loads are legal for A / B (base and row stride aligned)
     int split_k;
+};
+
+// Several independent products in one launch: workgroups [block_end[i-1], block_end[i]) belong
+// to product i, slice-major (split_k slices of `grid` workgroups each).
+struct ProductBatch {
+    int count;
+    int block_end[kMaxFused];
+    ProductParams prob[kMaxFused];
 };
 
 // Is (i, j) inside the structure of property p?  (p is never Identity here.)
@@ -239,8 +248,14 @@ __device__ __forceinline__ void mfma_chunk(const float *As, const float *Bs, int
 }
 
 template <class T>
-__global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const ProductParams p)
+__global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const ProductBatch batch)
 {
+    int which = 0;
+    while (which + 1 < batch.count && (int)blockIdx.x >= batch.block_end[which]) ++which;
+    const ProductParams &p = batch.prob[which];
+    const int local = (int)blockIdx.x - (which ? batch.block_end[which - 1] : 0);
+    const int slice = local / p.grid, block = local % p.grid;
+
     extern __shared__ __align__(16) float smem[];
     float *const As = smem;                       // two stages of the A tile
     float *const Bs = smem + 2 * T::A_STAGE;      // two stages of the B tile
@@ -248,11 +263,10 @@ __global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const Pro
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
     const int wr0 = (wave / T::WN) * T::WTM, wc0 = (wave % T::WN) * T::WTN;
-    const int slice = blockIdx.y;
 
     for (int pass = 0; pass < 2; ++pass) {
-        const int t = pass == 0 ? (int)blockIdx.x : p.num_tiles - 1 - (int)blockIdx.x;
-        if (pass == 1 && (!p.paired || t <= (int)blockIdx.x)) break;
+        const int t = pass == 0 ? block : p.num_tiles - 1 - block;
+        if (pass == 1 && (!p.paired || t <= block)) break;
         int I, J;
         tile_coords(p.order, t, p.tiles_m, p.tiles_n, I, J);
         const int r0 = I * T::BM, c0 = J * T::BN;
@@ -376,15 +390,56 @@ __global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const Pro
     }
 }
 
-// Sum of split-K slices: C[i][j] = sum_s P[s][i][j]   (general results only)
-__global__ void reduce_slices_kernel(const float *P, int64_t slice_stride, int slices, float *C, int64_t ldc,
-                                     int M, int N)
+// Sum of split-K slices: C[i][j] = sum_s P[s][i][j], for up to kMaxFused products at once
+// (blockIdx.y selects the product).  The order of summation is fixed, so results repeat bit
+// for bit from run to run.
+struct ReduceParams {
+    const float *P;
+    float *C;
+    int64_t slice_stride, ldc;
+    int slices, M, N;
+};
+struct ReduceBatch {
+    int count;
+    ReduceParams prob[kMaxFused];
+};
+
+// 256 threads = 32 groups of 4 consecutive floats x 8 lanes over the slices: lane g of a group
+// sums slices g, g+8, ... with all its loads in flight, the 8 partial sums meet in LDS.
+__global__ __launch_bounds__(256) void reduce_slices_kernel(const ReduceBatch batch)
 {
-    const int64_t total = (int64_t)M * N;
-    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
-        float s = 0.0f;
-        for (int k = 0; k < slices; ++k) s += P[k * slice_stride + e];
-        C[(e / N) * ldc + (e % N)] = s;
+    __shared__ f32x4 part[8][32];
+    const ReduceParams &r = batch.prob[blockIdx.y];
+    const int64_t total = (int64_t)r.M * r.N;              // scratch slices are packed: M*N floats each
+    const int64_t quads = (total + 3) / 4;
+    const bool vec = (total % 4) == 0 && (r.N % 4) == 0 && (r.ldc % 4) == 0 && (reinterpret_cast<uintptr_t>(r.C) & 15) == 0;
+    const int q_in_block = threadIdx.x % 32, g = threadIdx.x / 32;
+    for (int64_t q0 = (int64_t)blockIdx.x * 32; q0 < quads; q0 += (int64_t)gridDim.x * 32) {
+        const int64_t q = q0 + q_in_block, e = q * 4;
+        f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (q < quads) {
+            if (vec) {
+#pragma unroll 8
+                for (int k = g; k < r.slices; k += 8) s += *reinterpret_cast<const f32x4 *>(r.P + k * r.slice_stride + e);
+            } else {
+                for (int k = g; k < r.slices; k += 8)
+                    for (int c = 0; c < 4; ++c)
+                        if (e + c < total) s[c] += r.P[k * r.slice_stride + e + c];
+            }
+        }
+        part[g][q_in_block] = s;
+        __syncthreads();
+        if (g == 0 && q < quads) {
+#pragma unroll
+            for (int k = 1; k < 8; ++k) s += part[k][q_in_block];
+            if (vec) {
+                *reinterpret_cast<f32x4 *>(r.C + (e / r.N) * r.ldc + (e % r.N)) = s;
+            } else {
+                for (int c = 0; c < 4; ++c)
+                    if (e + c < total) r.C[((e + c) / r.N) * r.ldc + ((e + c) % r.N)] = s[c];
+            }
+        }
+        __syncthreads();
     }
 }
 

@@ -2,11 +2,16 @@
 // Plain integer logic shared by the planner (which sizes the workspace) and the evaluator
 // (which launches); written for the MI355X: 256 compute units in 8 XCDs.
 #pragma once
+#include <algorithm>
+
 #include "plan_internal.h"
 
 namespace mom {
 
 constexpr int kComputeUnits = 256;
+constexpr int kMinChunksPerSlice = 8;
+constexpr int kSplitTargetWorkgroups = 384;
+constexpr int kMaxFused = 4;          // independent products one launch can carry
 
 // Tile shapes the product kernel is instantiated for.
 enum TileShape : int { kTile128 = 0, kTile64 = 1, kNumTileShapes };
@@ -69,8 +74,22 @@ inline Launch choose_launch(const ProductStep &st)
     // the same amount of work.  Only worth it while the pairs still cover the chip.
     L.paired = (L.order != kRowMajor && L.num_tiles >= 2 * kComputeUnits) ? 1 : 0;
     L.grid = L.paired ? (L.num_tiles + 1) / 2 : L.num_tiles;
+    // Split-K: a general product with few output tiles and a long k leaves most compute units
+    // idle; cut k into slices (one workgroup per tile and slice, partial sums to scratch, summed
+    // by a second small kernel) until about one and a half workgroups per compute unit exist, keeping at
+    // least kMinChunksPerSlice chunks per slice.
     L.split_k = 1;
     L.scratch_bytes = 0;
+    if (L.order == kRowMajor && L.num_tiles < kComputeUnits) {
+        const int bk = small ? 16 : 32;
+        const int chunks = (int)((st.k + bk - 1) / bk);
+        const int want = (kSplitTargetWorkgroups + L.num_tiles - 1) / L.num_tiles;
+        const int split = std::min(want, chunks / kMinChunksPerSlice);
+        if (split > 1) {
+            L.split_k = split;
+            L.scratch_bytes = (size_t)split * (size_t)st.m * (size_t)st.n * sizeof(float);
+        }
+    }
     return L;
 }
 

@@ -62,6 +62,26 @@ def test_general_product_shapes(m, k, n):
     check_against_dense(dims, props, chain(dims, props, 500 + m))
 
 
+@pytest.mark.parametrize("m,k,n", [(64, 5000, 64), (130, 2000, 70), (33, 4097, 17), (512, 8192, 64), (64, 4096, 2048)])
+def test_long_k_products_are_split(m, k, n):
+    # few output tiles and a long k: the k-range is cut into slices that a second kernel sums
+    dims, props = [m, k, n], [G, G]
+    check_against_dense(dims, props, chain(dims, props, 700 + m))
+
+
+def test_independent_products_share_a_launch():
+    # ((A B) (C D)) and (((A B) (C D)) ((E F) (G H))): products of one level run side by side,
+    # each with its own temporaries and split-K scratch
+    dims, props = [96, 1500, 80, 1200, 72], [G, G, G, G]
+    f = chain(dims, props, 810)
+    plan, _ = check_against_dense(dims, props, f, splits=[1, 0, 2])
+    assert plan.string == "((0 1) (2 3))"
+    dims, props = [70, 900, 64, 64, 64, 1000, 90, 700, 33], [G, G, L, U, G, G, G, G]
+    f = chain(dims, props, 820)
+    plan, _ = check_against_dense(dims, props, f, splits=[3, 1, 0, 2, 5, 4, 6])
+    assert plan.string == "(((0 1) (2 3)) ((4 5) (6 7)))"
+
+
 def test_paper_sec4_chain_both_trees():
     kv = dict(ln.split(" ", 1) for ln in golden_lines("sec4_chain.txt"))
     dims = [int(x) for x in kv["dims"].split()]
