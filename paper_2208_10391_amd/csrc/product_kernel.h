@@ -247,6 +247,77 @@ __device__ __forceinline__ void mfma_chunk(const float *As, const float *Bs, int
     }
 }
 
+// What one output tile needs: where it sits, its k-range in chunks, and which chunks are
+// interior for both operands.
+struct TileWork {
+    int r0, c0;            // first row / column of the tile
+    int klo;               // first k (a multiple of BK)
+    int nchunks;           // chunks of BK to multiply (0: the tile is all zeros)
+    int f_lo, f_hi;        // chunks [f_lo, f_hi) need neither masking nor bounds checks
+    bool a_edge, b_edge;   // the tile pokes over the matrix edge, or rows are not 16-byte aligned
+};
+
+template <class T>
+__device__ __forceinline__ TileWork tile_work(const ProductParams &p, int t, int slice)
+{
+    int I, J;
+    tile_coords(p.order, t, p.tiles_m, p.tiles_n, I, J);
+    TileWork w;
+    w.r0 = I * T::BM;
+    w.c0 = J * T::BN;
+    const int r1 = min(w.r0 + T::BM, p.M), c1 = min(w.c0 + T::BN, p.N);
+    // k-range: the k for which some A[i][k] and some B[k][j] are both inside their
+    // structures, widened to whole chunks
+    int klo = 0, khi = p.K;
+    if (p.pa == kLower) khi = min(khi, r1);          // A[i][k] = 0 for k > i
+    if (p.pa == kUpper) klo = max(klo, w.r0);        // A[i][k] = 0 for k < i
+    if (p.pb == kLower) klo = max(klo, w.c0);        // B[k][j] = 0 for k < j
+    if (p.pb == kUpper) khi = min(khi, c1);          // B[k][j] = 0 for k > j
+    klo = (klo / T::BK) * T::BK;
+    int nchunks = khi > klo ? (khi - klo + T::BK - 1) / T::BK : 0;
+    if (p.split_k > 1) {                             // this slice's share of the chunks
+        const int per = (nchunks + p.split_k - 1) / p.split_k;
+        const int first = min(slice * per, nchunks);
+        nchunks = min(per, nchunks - first);
+        klo += first * T::BK;
+    }
+    w.klo = klo;
+    w.nchunks = nchunks;
+    w.a_edge = !p.a_vec || w.r0 + T::BM > p.M;
+    w.b_edge = !p.b_vec || w.c0 + T::BN > p.N;
+    // What a property or an edge makes special is always a run of chunks at the head and a
+    // run at the tail of the k-range; the chunks in between are interior.
+    w.f_lo = w.f_hi = 0;
+    if (!w.a_edge && !w.b_edge) {
+        int k_from = klo, k_to = (p.K / T::BK) * T::BK;
+        if (p.pa == kUpper) k_from = max(k_from, w.r0 + T::BM);
+        if (p.pb == kLower) k_from = max(k_from, w.c0 + T::BN);
+        if (p.pa == kLower) k_to = min(k_to, w.r0);
+        if (p.pb == kUpper) k_to = min(k_to, w.c0);
+        w.f_lo = min((k_from - klo) / T::BK, nchunks);
+        w.f_hi = max(min((k_to - klo) / T::BK, nchunks), w.f_lo);
+    }
+    return w;
+}
+
+template <class T>
+__device__ __forceinline__ int load_mode_a(const ProductParams &p, const TileWork &w, int kc)
+{
+    if (w.a_edge || kc + T::BK > p.K) return 2;
+    if (p.pa == kLower && kc + T::BK - 1 > w.r0) return 1;
+    if (p.pa == kUpper && kc < w.r0 + T::BM - 1) return 1;
+    return 0;
+}
+
+template <class T>
+__device__ __forceinline__ int load_mode_b(const ProductParams &p, const TileWork &w, int kc)
+{
+    if (w.b_edge || kc + T::BK > p.K) return 2;
+    if (p.pb == kLower && w.c0 + T::BN - 1 > kc) return 1;
+    if (p.pb == kUpper && kc + T::BK - 1 > w.c0) return 1;
+    return 0;
+}
+
 template <class T>
 __global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const ProductBatch batch)
 {
@@ -264,44 +335,78 @@ __global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const Pro
     const int l32 = lane & 31, half = lane >> 5;
     const int wr0 = (wave / T::WN) * T::WTM, wc0 = (wave % T::WN) * T::WTN;
 
-    for (int pass = 0; pass < 2; ++pass) {
-        const int t = pass == 0 ? block : p.num_tiles - 1 - block;
-        if (pass == 1 && (!p.paired || t <= block)) break;
-        int I, J;
-        tile_coords(p.order, t, p.tiles_m, p.tiles_n, I, J);
-        const int r0 = I * T::BM, c0 = J * T::BN;
-        const int r1 = min(r0 + T::BM, p.M), c1 = min(c0 + T::BN, p.N);
-
-        // k-range of this tile: the k for which some A[i][k] and some B[k][j] are both
-        // inside their structures, widened to whole chunks
-        int klo = 0, khi = p.K;
-        if (p.pa == kLower) khi = min(khi, r1);          // A[i][k] = 0 for k > i
-        if (p.pa == kUpper) klo = max(klo, r0);          // A[i][k] = 0 for k < i
-        if (p.pb == kLower) klo = max(klo, c0);          // B[k][j] = 0 for k < j
-        if (p.pb == kUpper) khi = min(khi, c1);          // B[k][j] = 0 for k > j
-        klo = (klo / T::BK) * T::BK;
-        int nchunks = khi > klo ? (khi - klo + T::BK - 1) / T::BK : 0;
-        if (p.split_k > 1) {                             // this slice's share of the chunks
-            const int per = (nchunks + p.split_k - 1) / p.split_k;
-            const int first = min(slice * per, nchunks);
-            nchunks = min(per, nchunks - first);
-            klo += first * T::BK;
+    // The tiles of this workgroup, in order: tile `block` and its partner from the other end of
+    // the longest-first order when tiles are paired, else every grid-th tile.
+    auto tile_at = [&](int i) {
+        if (p.paired) {
+            const int partner = p.num_tiles - 1 - block;
+            return i == 0 ? block : (i == 1 && partner > block ? partner : -1);
         }
+        const int64_t t = block + (int64_t)i * p.grid;
+        return t < p.num_tiles ? (int)t : -1;
+    };
 
-        const bool a_edge = !p.a_vec || r0 + T::BM > p.M;
-        const bool b_edge = !p.b_vec || c0 + T::BN > p.N;
-        auto mode_a = [&](int kc) {
-            if (a_edge || kc + T::BK > p.K) return 2;
-            if (p.pa == kLower && kc + T::BK - 1 > r0) return 1;
-            if (p.pa == kUpper && kc < r0 + T::BM - 1) return 1;
-            return 0;
-        };
-        auto mode_b = [&](int kc) {
-            if (b_edge || kc + T::BK > p.K) return 2;
-            if (p.pb == kLower && c0 + T::BN - 1 > kc) return 1;
-            if (p.pb == kUpper && kc + T::BK - 1 > c0) return 1;
-            return 0;
-        };
+    // Fetch side of the software pipeline.  It walks the flat sequence of (tile, chunk) pairs
+    // of this workgroup two chunks ahead of the MFMAs and simply carries on into the next tile,
+    // so a tile's first chunks arrive while the previous tile is still being multiplied.
+    f32x4 ra[T::A_F4], rb[T::B_F4];
+    const float *a_src[T::A_F4], *b_src[T::B_F4];    // this thread's addresses of the fetch tile's chunk 0
+    TileWork fw{};
+    int f_seq = -1, f_chunk = 0;
+    bool f_live = true;
+    auto next_fetch_tile = [&]() {
+        for (;;) {
+            const int t = tile_at(++f_seq);
+            if (t < 0) { f_live = false; return; }
+            fw = tile_work<T>(p, t, slice);
+            if (fw.nchunks > 0) break;
+        }
+        f_chunk = 0;
+#pragma unroll
+        for (int q = 0; q < T::A_F4; ++q) {
+            const int idx = tid + q * T::NT;
+            a_src[q] = p.A + (int64_t)(fw.r0 + idx / (T::BK / 4)) * p.lda + fw.klo + (idx % (T::BK / 4)) * 4;
+        }
+#pragma unroll
+        for (int q = 0; q < T::B_F4; ++q) {
+            const int idx = tid + q * T::NT;
+            b_src[q] = p.B + (int64_t)(fw.klo + idx / (T::BN / 4)) * p.ldb + fw.c0 + (idx % (T::BN / 4)) * 4;
+        }
+    };
+    auto fetch_next = [&]() {                        // next chunk: global -> registers
+        if (!f_live) return false;
+        const int j = f_chunk;
+        if (j >= fw.f_lo && j < fw.f_hi) {
+            const int64_t a_step = (int64_t)j * T::BK, b_step = a_step * p.ldb;
+#pragma unroll
+            for (int q = 0; q < T::A_F4; ++q) ra[q] = *reinterpret_cast<const f32x4 *>(a_src[q] + a_step);
+#pragma unroll
+            for (int q = 0; q < T::B_F4; ++q) rb[q] = *reinterpret_cast<const f32x4 *>(b_src[q] + b_step);
+        } else {
+            const int kc = fw.klo + j * T::BK;
+            load_a<T>(p, fw.r0, kc, load_mode_a<T>(p, fw, kc), tid, ra);
+            load_b<T>(p, fw.c0, kc, load_mode_b<T>(p, fw, kc), tid, rb);
+        }
+        if (++f_chunk == fw.nchunks) next_fetch_tile();
+        return true;
+    };
+
+    // Two LDS stages, one barrier per chunk: while flat chunk g is multiplied out of stage
+    // g&1, chunk g+1 moves from registers into the other stage and the loads of chunk g+2 are
+    // issued into the same registers.
+    next_fetch_tile();
+    bool in_regs = false;
+    if (fetch_next()) {
+        stage_to_lds<T>(As, Bs, tid, ra, rb);
+        in_regs = fetch_next();
+    }
+    __syncthreads();
+
+    int g = 0;
+    for (int seq = 0;; ++seq) {
+        const int t = tile_at(seq);
+        if (t < 0) break;
+        const TileWork w = tile_work<T>(p, t, slice);
 
         f32x16 acc[T::FM][T::FN];
 #pragma unroll
@@ -311,79 +416,29 @@ __global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const Pro
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[bi][bj][v] = 0.0f;
 
-        // Chunks [f_lo, f_hi) are interior for both operands (mode 0): in bounds, aligned and
-        // clear of every diagonal.  What a property or an edge makes special is always a run
-        // of chunks at the head and a run at the tail of the k-range.
-        int f_lo = 0, f_hi = 0;
-        if (!a_edge && !b_edge) {
-            int k_from = klo, k_to = (p.K / T::BK) * T::BK;
-            if (p.pa == kUpper) k_from = max(k_from, r0 + T::BM);
-            if (p.pb == kLower) k_from = max(k_from, c0 + T::BN);
-            if (p.pa == kLower) k_to = min(k_to, r0);
-            if (p.pb == kUpper) k_to = min(k_to, c0);
-            f_lo = min((k_from - klo) / T::BK, nchunks);
-            f_hi = max(min((k_to - klo) / T::BK, nchunks), f_lo);
-        }
-
-        if (nchunks > 0) {
-            f32x4 ra[T::A_F4], rb[T::B_F4];
-            // per-thread source addresses of chunk 0; interior chunks step along k from here
-            const float *a_src[T::A_F4], *b_src[T::B_F4];
-#pragma unroll
-            for (int q = 0; q < T::A_F4; ++q) {
-                const int idx = tid + q * T::NT;
-                a_src[q] = p.A + (int64_t)(r0 + idx / (T::BK / 4)) * p.lda + klo + (idx % (T::BK / 4)) * 4;
-            }
-#pragma unroll
-            for (int q = 0; q < T::B_F4; ++q) {
-                const int idx = tid + q * T::NT;
-                b_src[q] = p.B + (int64_t)(klo + idx / (T::BN / 4)) * p.ldb + c0 + (idx % (T::BN / 4)) * 4;
-            }
-            // Software pipeline, two LDS stages.  While chunk c is multiplied out of stage c&1,
-            // chunk c+1 (loaded from HBM during the previous iteration) moves from registers
-            // into the other stage and the loads of chunk c+2 are issued into the same
-            // registers; one barrier per chunk.
-            auto fetch = [&](int j) {                     // chunk j: global -> registers
-                if (j >= f_lo && j < f_hi) {
-                    const int64_t a_step = (int64_t)j * T::BK, b_step = a_step * p.ldb;
-#pragma unroll
-                    for (int q = 0; q < T::A_F4; ++q) ra[q] = *reinterpret_cast<const f32x4 *>(a_src[q] + a_step);
-#pragma unroll
-                    for (int q = 0; q < T::B_F4; ++q) rb[q] = *reinterpret_cast<const f32x4 *>(b_src[q] + b_step);
-                } else if (j < nchunks) {
-                    const int kc = klo + j * T::BK;
-                    load_a<T>(p, r0, kc, mode_a(kc), tid, ra);
-                    load_b<T>(p, c0, kc, mode_b(kc), tid, rb);
-                }
-            };
-            fetch(0);
-            stage_to_lds<T>(As, Bs, tid, ra, rb);
-            fetch(1);
+        for (int c = 0; c < w.nchunks; ++c, ++g) {
+            const int cur = g & 1, nxt = cur ^ 1;
+            mfma_chunk<T>(As + cur * T::A_STAGE, Bs + cur * T::B_STAGE, wr0, wc0, l32, half, acc, [&]() {
+                if (in_regs) stage_to_lds<T>(As + nxt * T::A_STAGE, Bs + nxt * T::B_STAGE, tid, ra, rb);
+                in_regs = fetch_next();
+            });
             __syncthreads();
-            for (int c = 0; c < nchunks; ++c) {
-                const int cur = c & 1, nxt = cur ^ 1;
-                mfma_chunk<T>(As + cur * T::A_STAGE, Bs + cur * T::B_STAGE, wr0, wc0, l32, half, acc, [&]() {
-                    if (c + 1 < nchunks) stage_to_lds<T>(As + nxt * T::A_STAGE, Bs + nxt * T::B_STAGE, tid, ra, rb);
-                    fetch(c + 2);
-                });
-                __syncthreads();
-            }
         }
 
         // store: full tiles of a general result (or tiles strictly inside the triangle) go out
         // unchecked; edge and diagonal tiles element by element, the triangle only
         float *const C = p.C + (int64_t)slice * p.slice_stride;
-        bool plain = r0 + T::BM <= p.M && c0 + T::BN <= p.N;
-        if (p.pc == kLower) plain = plain && c0 + T::BN - 1 <= r0;
-        if (p.pc == kUpper) plain = plain && r0 + T::BM - 1 <= c0;
+        bool plain = w.r0 + T::BM <= p.M && w.c0 + T::BN <= p.N;
+        if (p.pc == kLower) plain = plain && w.c0 + T::BN - 1 <= w.r0;
+        if (p.pc == kUpper) plain = plain && w.r0 + T::BM - 1 <= w.c0;
 #pragma unroll
         for (int bi = 0; bi < T::FM; ++bi)
 #pragma unroll
             for (int bj = 0; bj < T::FN; ++bj)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int gi = r0 + wr0 + bi * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-                    const int gj = c0 + wc0 + bj * 32 + l32;
+                    const int gi = w.r0 + wr0 + bi * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                    const int gj = w.c0 + wc0 + bj * 32 + l32;
                     if (plain || (gi < p.M && gj < p.N && in_structure(p.pc, gi, gj)))
                         C[(int64_t)gi * p.ldc + gj] = acc[bi][bj][v];
                 }

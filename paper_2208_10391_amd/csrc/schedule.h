@@ -11,6 +11,7 @@ namespace mom {
 constexpr int kComputeUnits = 256;
 constexpr int kMinChunksPerSlice = 8;
 constexpr int kSplitTargetWorkgroups = 384;
+constexpr int kMinChunksToSplit = 64;      // below this the second launch costs more than it saves
 constexpr int kMaxFused = 4;          // independent products one launch can carry
 
 // Tile shapes the product kernel is instantiated for.
@@ -74,15 +75,20 @@ inline Launch choose_launch(const ProductStep &st)
     // the same amount of work.  Only worth it while the pairs still cover the chip.
     L.paired = (L.order != kRowMajor && L.num_tiles >= 2 * kComputeUnits) ? 1 : 0;
     L.grid = L.paired ? (L.num_tiles + 1) / 2 : L.num_tiles;
+    // Equal tiles (general * general) beyond what the chip holds at once, with a k long enough
+    // to matter: launch only as many workgroups as are resident together and let each walk
+    // every grid-th tile, so that the loads of its next tile overlap the MFMAs of this one.
+    const int resident = kComputeUnits * (small ? 4 : 2);
+    if (L.order == kRowMajor && L.num_tiles > resident && st.k >= 8 * (small ? 16 : 32)) L.grid = resident;
     // Split-K: a general product with few output tiles and a long k leaves most compute units
     // idle; cut k into slices (one workgroup per tile and slice, partial sums to scratch, summed
     // by a second small kernel) until about one and a half workgroups per compute unit exist, keeping at
     // least kMinChunksPerSlice chunks per slice.
     L.split_k = 1;
     L.scratch_bytes = 0;
-    if (L.order == kRowMajor && L.num_tiles < kComputeUnits) {
-        const int bk = small ? 16 : 32;
-        const int chunks = (int)((st.k + bk - 1) / bk);
+    const int bk = small ? 16 : 32;
+    const int chunks = (int)((st.k + bk - 1) / bk);
+    if (L.order == kRowMajor && L.num_tiles < kComputeUnits && chunks >= kMinChunksToSplit) {
         const int want = (kSplitTargetWorkgroups + L.num_tiles - 1) / L.num_tiles;
         const int split = std::min(want, chunks / kMinChunksPerSlice);
         if (split > 1) {
