@@ -114,6 +114,80 @@ __global__ __launch_bounds__(64) void batched_chain_kernel(const BatchedParams p
     }
 }
 
+// Register-only fast path for the chain X0 * (X1 * X2) of three full 32x32 factors (the
+// canonical plan of lowerTri * general * upperTri): nothing touches LDS.
+//   P = X1 * X2: X1 is the A operand (lane (l32, half) loads X1[l32][8kg + 4half .. +3] as one
+//   16-byte load per group kg), X2 the B operand (X2[8kg + 4half + e][l32], a coalesced 4-byte
+//   load per step).  Accumulator register v = 4kg + e of P then holds P[8kg + 4half + e][l32],
+//   which is exactly the B operand of step (kg, e) of the second product: X0 * P runs
+//   straight out of the accumulators of the first.
+// The three properties are template parameters: a general factor then costs no masking at
+// all and a triangular one a compare against a constant and a select per element.
+template <int P>
+__device__ __forceinline__ float keep(float x, int i, int j)
+{
+    if (P == kLower) return j <= i ? x : 0.0f;
+    if (P == kUpper) return j >= i ? x : 0.0f;
+    return x;
+}
+
+template <int P0, int P1, int P2>
+__global__ __launch_bounds__(256) void batched_chain3_right_kernel(const BatchedParams p)
+{
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
+    const int64_t chain = (int64_t)blockIdx.x * 4 + wave;
+    if (chain >= p.batch) return;
+    const float *X0 = p.base[0] + chain * p.stride[0];
+    const float *X1 = p.base[1] + chain * p.stride[1];
+    const float *X2 = p.base[2] + chain * p.stride[2];
+    f32x4 x0[4], x1[4];
+    float x2[16];
+#pragma unroll
+    for (int kg = 0; kg < 4; ++kg) x1[kg] = *reinterpret_cast<const f32x4 *>(X1 + l32 * 32 + kg * 8 + 4 * half);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) x2[v] = X2[((v / 4) * 8 + 4 * half + v % 4) * 32 + l32];
+#pragma unroll
+    for (int kg = 0; kg < 4; ++kg) x0[kg] = *reinterpret_cast<const f32x4 *>(X0 + l32 * 32 + kg * 8 + 4 * half);
+
+    __builtin_amdgcn_sched_barrier(0);     // all 24 loads are in flight before the first use
+    const int row = l32 - 4 * half;        // (k <= l32) with k = c + 4*half  <=>  c <= row, c a constant
+    f32x16 prod, res;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) prod[v] = res[v] = 0.0f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int c = (v / 4) * 8 + v % 4;
+        prod = __builtin_amdgcn_mfma_f32_32x32x2f32(keep<P1>(x1[v / 4][v % 4], row, c), keep<P2>(x2[v], c, row), prod, 0, 0, 0);
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int c = (v / 4) * 8 + v % 4;
+        res = __builtin_amdgcn_mfma_f32_32x32x2f32(keep<P0>(x0[v / 4][v % 4], row, c), prod[v], res, 0, 0, 0);
+    }
+    float *out = p.out + chain * p.out_stride;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) out[(8 * (v / 4) + 4 * half + v % 4) * 32 + l32] = res[v];
+}
+
+typedef void (*Chain3Kernel)(const BatchedParams);
+template <int P0, int P1>
+inline Chain3Kernel chain3_kernel_for(int p2)
+{
+    return p2 == kLower ? batched_chain3_right_kernel<P0, P1, kLower>
+         : p2 == kUpper ? batched_chain3_right_kernel<P0, P1, kUpper> : batched_chain3_right_kernel<P0, P1, kGeneral>;
+}
+template <int P0>
+inline Chain3Kernel chain3_kernel_for(int p1, int p2)
+{
+    return p1 == kLower ? chain3_kernel_for<P0, kLower>(p2)
+         : p1 == kUpper ? chain3_kernel_for<P0, kUpper>(p2) : chain3_kernel_for<P0, kGeneral>(p2);
+}
+inline Chain3Kernel chain3_kernel_for(int p0, int p1, int p2)
+{
+    return p0 == kLower ? chain3_kernel_for<kLower>(p1, p2)
+         : p0 == kUpper ? chain3_kernel_for<kUpper>(p1, p2) : chain3_kernel_for<kGeneral>(p1, p2);
+}
+
 inline hipError_t launch_batched(const mom_plan *plan, const float *const *bases, const int64_t *strides,
                                  float *d_out, int64_t out_stride, int32_t batch, hipStream_t stream)
 {
@@ -151,6 +225,12 @@ inline hipError_t launch_batched(const mom_plan *plan, const float *const *bases
     p.out_rows = (int)plan->rows;
     p.out_cols = (int)plan->cols;
     p.batch = batch;
+    // three full, aligned 32x32 factors multiplied as X0 * (X1 * X2): the register-only kernel
+    if (nl == 3 && p.vec[0] && p.vec[1] && p.vec[2] && p.num_products == 2 && p.a_slot[0] == 1 && p.b_slot[0] == 2 &&
+        p.a_slot[1] == 0 && p.b_slot[1] == 1) {
+        hipLaunchKernelGGL(chain3_kernel_for(p.prop[0], p.prop[1], p.prop[2]), dim3((batch + 3) / 4), dim3(256), 0, stream, p);
+        return hipGetLastError();
+    }
     const dim3 grid(batch), block(64);
     switch (nl) {
     case 0: hipLaunchKernelGGL(batched_chain_kernel<0>, grid, block, 0, stream, p); break;

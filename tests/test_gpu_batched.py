@@ -63,6 +63,16 @@ def test_batched_shapes_and_properties(dims, props):
     run_batched(dims, props, 19, 7)
 
 
+def test_batched_register_path_every_property_triple():
+    # three full 32x32 factors multiplied as X0 (X1 X2) take the register-only kernel, which is
+    # compiled once per property triple
+    for p0 in (G, L, U):
+        for p1 in (G, L, U):
+            for p2 in (G, L, U):
+                plan, _ = run_batched([32] * 4, [p0, p1, p2], 6, 40 + 9 * p0 + 3 * p1 + p2, splits=[0, 1])
+                assert plan.string == "(0 (1 2))"
+
+
 def test_batched_every_tree():
     from helpers import all_preorder_trees
     dims, props = [32, 32, 16, 32, 32], [U, G, G, L]
