@@ -7,7 +7,7 @@ n = 4096, whose useful work is counted as n^3 FLOP; the other workloads are reac
 --workload.  Prints ONE JSON line.
 
 The metric follows the paper's protocol for its only experiment (Sec. 4: f32 operands, the
-minimum of five runs is logged as min_ms next to the mean that `value` is computed from).
+minimum over single runs is logged as min_ms next to the mean that `value` is computed from).
 """
 import argparse
 import json
@@ -25,6 +25,22 @@ import synthetic_chains as sc  # noqa: E402
 F32_MFMA_PEAK_TFLOPS = 157.3        # 256 CUs x 256 FLOP/clk x 2.4 GHz
 HBM_PEAK_GBS = 8000.0
 
+# HBM-side bytes per launch of the dominant kernel, from two counter passes of this very
+# program (rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE; KiB per dispatch), each scaled by what
+# the same counter reads for the copy8192 workload, whose traffic is known.  The figures hold
+# for the kernel sources they were taken with: `sources` is the digest kernel_sources_digest()
+# gave then, and any other digest turns the field into null.
+# (scale factors of that calibration: FETCH_SIZE x 1.9997, WRITE_SIZE x 1.0000; all launches of one step summed)
+MEASURED_TRAFFIC = {
+    "trmm4096": {"fetch_bytes": 435861475, "write_bytes": 67108864, "sources": "a531d155d7b2722e"},
+    "general5": {"fetch_bytes": 126620388, "write_bytes": 82444288, "sources": "a531d155d7b2722e"},
+    "mixed5": {"fetch_bytes": 3715932621, "write_bytes": 100663296, "sources": "a531d155d7b2722e"},
+    "mixed5_tri_intermediate": {"fetch_bytes": 7907641157, "write_bytes": 201457664, "sources": "a531d155d7b2722e"},
+    "mixed5_left_to_right": {"fetch_bytes": 15184491229, "write_bytes": 436338688, "sources": "a531d155d7b2722e"},
+    "batched32": {"fetch_bytes": 50356393, "write_bytes": 16777216, "sources": "a531d155d7b2722e"},
+    "copy8192": {"fetch_bytes": 268435456, "write_bytes": 268435456, "sources": "a531d155d7b2722e"},
+}
+
 # forced parenthesisations of the mixed-property chain (the planner's own tree never forms
 # L1*L2, so two trees that do are timed as well)
 WORKLOADS = {
@@ -41,6 +57,24 @@ WORKLOADS = {
 }
 
 sc.CONFIGS["copy8192"] = sc.ChainConfig("copy8192", 9, (8192, 8192), (sc.GENERAL,))
+
+
+def kernel_sources_digest():
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for path in sorted(glob.glob(os.path.join(ROOT, "paper_2208_10391_amd", "csrc", "*"))):
+        with open(path, "rb") as f:
+            h.update(os.path.basename(path).encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload):
+    m = MEASURED_TRAFFIC.get(workload)
+    if not m or m["sources"] != kernel_sources_digest():
+        return None
+    return {"fetch_bytes": m["fetch_bytes"], "write_bytes": m["write_bytes"],
+            "bytes": m["fetch_bytes"] + m["write_bytes"]}
 
 
 def useful_flop(name, plan, cfg):
@@ -100,8 +134,8 @@ def cpu_baseline(cfg, host, splits, flop):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="trmm4096", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -120,54 +154,56 @@ def main():
         mom.mom_plan_from_splits(cfg.dims, cfg.props, splits)
     dev = [None if f is None else f.cuda() for f in host]
     rows, cols, _ = plan.result
+    # arguments are marshalled once; a step is one call of the C entry point
     if cfg.batch:
         out = torch.empty((cfg.batch, rows, cols), dtype=torch.float32, device="cuda")
-
-        def step():
-            mom.mom_chain_eval_batched(plan, dev, out=out)
+        step = mom.bind_chain_eval_batched(plan, dev, out=out)
     else:
         out = torch.empty((rows, cols), dtype=torch.float32, device="cuda")
         ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device="cuda")
-
-        def step():
-            mom.mom_chain_eval(plan, dev, out=out, workspace=ws)
+        step = mom.bind_chain_eval(plan, dev, out=out, workspace=ws)
 
     flop = useful_flop(args.workload, plan, cfg)
 
+    # The clocks take some tens of launches to settle, hence the long default warm-up.  The
+    # event pair sits on the launch stream (the library enqueues on torch's current stream) and
+    # brackets the timed region: device time per step, which feeds the roofline.
     for _ in range(args.warmup):
         step()
+    first, last = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    first.record()
     for _ in range(args.steps):
         step()
+    last.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
+    avg_ms = first.elapsed_time(last) / args.steps
 
-    # per-evaluation device time with events on the launch stream (the library enqueues on
-    # torch's current stream): minimum and median, and the average that feeds the roofline
+    # one evaluation at a time: minimum and median (the paper logs the minimum of its runs)
     events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-              for _ in range(args.steps)]
+              for _ in range(min(args.steps, 50))]
     for s, e in events:
         s.record()
         step()
         e.record()
     torch.cuda.synchronize()
     per = sorted(s.elapsed_time(e) for s, e in events)
-    avg_ms = sum(per) / len(per)
 
     value = flop / (ms_per_step * 1e-3) / 1e9
     if cfg.batch or args.workload == "copy8192":   # HBM-bound: factors in and result out, once
         byts = algorithmic_bytes(cfg)
         ach = byts / (avg_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": ach / HBM_PEAK_GBS, "traffic": None,
-                    "kernel": "batched_chain_kernel" if cfg.batch else "copy_structure_kernel",
+                    "frac": ach / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload),
+                    "kernel": "batched_chain3_right_kernel" if cfg.batch else "copy_structure_kernel",
                     "algorithmic_bytes_per_launch": byts}
     else:
         ach = flop / (avg_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": ach, "peak": F32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": ach / F32_MFMA_PEAK_TFLOPS, "traffic": None,
+                    "frac": ach / F32_MFMA_PEAK_TFLOPS, "traffic": measured_traffic(args.workload),
                     "kernel": "product_kernel", "launches_per_step": mom.mom_plan_num_products(plan),
                     "algorithmic_flop_per_step": flop}
     line = {
@@ -187,6 +223,7 @@ def main():
                    "batch": cfg.batch, "plan": plan.string, "mults": plan.cost_mults,
                    "useful_flop": flop},
         "pct_of_f32_mfma_peak": 100.0 * value / 1e3 / F32_MFMA_PEAK_TFLOPS,
+        "device_ms_per_step": avg_ms,
         "min_ms": per[0],
         "median_ms": per[len(per) // 2],
         "roofline": roofline,

@@ -201,12 +201,30 @@ def _check_factor(t: torch.Tensor, what: str):
         raise TypeError("%s must be a float32 tensor on the GPU" % what)
 
 
-def mom_chain_eval(plan: Plan, factors: Sequence[Optional[torch.Tensor]], out: Optional[torch.Tensor] = None,
-                   workspace: Optional[torch.Tensor] = None, flags: int = 0, stream=None) -> torch.Tensor:
-    """Enqueue the plan on the (current) stream.  factors[t] is a 2-D f32 CUDA tensor with unit
-    column stride (None for Identity factors); `out` and `workspace` are allocated with torch
-    when not given (out is NOT cleared: a triangular result leaves its other half untouched
-    unless flags has MOM_OUT_ZERO_FILL_TRIANGLE)."""
+class BoundEval:
+    """The marshalled arguments of one mom_chain_eval / mom_chain_eval_batched call, kept so that
+    the same evaluation can be enqueued again without marshalling again (a launch-bound caller
+    pays microseconds per call otherwise).  Holds references to every tensor it points into."""
+
+    def __init__(self, entry, where: str, head: tuple, tail: tuple, out: torch.Tensor, keep: tuple):
+        self._entry, self._where, self._head, self._tail = entry, where, head, tail
+        self.out = out
+        self._keep = keep
+
+    def __call__(self, stream=None) -> torch.Tensor:
+        st = self._entry(*self._head, _stream_handle(stream), *self._tail)
+        if st != MOM_OK:
+            raise MomError(st, self._where)
+        return self.out
+
+
+def bind_chain_eval(plan: Plan, factors: Sequence[Optional[torch.Tensor]], out: Optional[torch.Tensor] = None,
+                    workspace: Optional[torch.Tensor] = None, flags: int = 0) -> BoundEval:
+    """Checks and marshals the arguments of mom_chain_eval; calling the result enqueues the plan
+    on the (current) stream.  factors[t] is a 2-D f32 CUDA tensor with unit column stride (None
+    for Identity factors); `out` and `workspace` are allocated with torch when not given (out is
+    NOT cleared: a triangular result leaves its other half untouched unless flags has
+    MOM_OUT_ZERO_FILL_TRIANGLE)."""
     n = plan.n
     if len(factors) != n:
         raise ValueError("expected %d factors" % n)
@@ -235,17 +253,23 @@ def mom_chain_eval(plan: Plan, factors: Sequence[Optional[torch.Tensor]], out: O
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     ld_out = out.stride(0) if rows > 1 else max(out.stride(0), cols)
-    st = _lib.mom_chain_eval(plan.handle, ctypes.cast(ptrs, _vpp), lds, ctypes.c_void_p(out.data_ptr()),
-                             ld_out, ctypes.c_void_p(ws_ptr), ws_bytes, int(flags), _stream_handle(stream))
-    if st != MOM_OK:
-        raise MomError(st, "mom_chain_eval")
-    return out
+    head = (plan.handle, ctypes.cast(ptrs, _vpp), lds, ctypes.c_void_p(out.data_ptr()), ld_out,
+            ctypes.c_void_p(ws_ptr), ws_bytes, int(flags))
+    return BoundEval(_lib.mom_chain_eval, "mom_chain_eval", head, (), out,
+                     (plan, ptrs, lds, tuple(factors), workspace))
 
 
-def mom_chain_eval_batched(plan: Plan, factors: Sequence[Optional[torch.Tensor]],
-                           out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
-    """factors[t]: [batch, dims[t], dims[t+1]] f32 CUDA tensor whose matrices are packed
-    (None for Identity factors).  One kernel launch for the whole batch."""
+def mom_chain_eval(plan: Plan, factors: Sequence[Optional[torch.Tensor]], out: Optional[torch.Tensor] = None,
+                   workspace: Optional[torch.Tensor] = None, flags: int = 0, stream=None) -> torch.Tensor:
+    """One call of the C entry point: marshal (bind_chain_eval) and enqueue."""
+    return bind_chain_eval(plan, factors, out, workspace, flags)(stream)
+
+
+def bind_chain_eval_batched(plan: Plan, factors: Sequence[Optional[torch.Tensor]],
+                            out: Optional[torch.Tensor] = None) -> BoundEval:
+    """Checks and marshals the arguments of mom_chain_eval_batched.  factors[t]: [batch, dims[t],
+    dims[t+1]] f32 CUDA tensor whose matrices are packed (None for Identity factors).  One kernel
+    launch for the whole batch."""
     n = plan.n
     if len(factors) != n:
         raise ValueError("expected %d factors" % n)
@@ -277,8 +301,12 @@ def mom_chain_eval_batched(plan: Plan, factors: Sequence[Optional[torch.Tensor]]
     if tuple(out.shape) != (batch, rows, cols) or not out[0].is_contiguous():
         raise ValueError("out must be [batch, %d, %d] with packed matrices" % (rows, cols))
     out_stride = out.stride(0) if batch > 1 else max(out.stride(0), rows * cols)
-    st = _lib.mom_chain_eval_batched(plan.handle, ctypes.cast(ptrs, _vpp), strides,
-                                     ctypes.c_void_p(out.data_ptr()), out_stride, batch, _stream_handle(stream))
-    if st != MOM_OK:
-        raise MomError(st, "mom_chain_eval_batched")
-    return out
+    head = (plan.handle, ctypes.cast(ptrs, _vpp), strides, ctypes.c_void_p(out.data_ptr()), out_stride, batch)
+    return BoundEval(_lib.mom_chain_eval_batched, "mom_chain_eval_batched", head, (), out,
+                     (plan, ptrs, strides, tuple(factors)))
+
+
+def mom_chain_eval_batched(plan: Plan, factors: Sequence[Optional[torch.Tensor]],
+                           out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """One call of the C entry point: marshal (bind_chain_eval_batched) and enqueue."""
+    return bind_chain_eval_batched(plan, factors, out)(stream)

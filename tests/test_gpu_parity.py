@@ -160,3 +160,27 @@ def test_eval_argument_errors_on_device():
         mom.mom_chain_eval(p, f[:2])
     with pytest.raises(TypeError):
         mom.mom_chain_eval(p, [x.cpu() for x in f])
+
+
+def test_bound_call_can_be_enqueued_again():
+    """Arguments marshalled once: every later call of the bound object is the same evaluation."""
+    dims, props = [130, 70, 70, 45], [G, L, G]
+    host = chain(dims, props, 77)
+    want = oracle.eval_dense(dims, props, [f.numpy() for f in host])
+    plan = mom.mom_chain_plan(dims, props)
+    call = mom.bind_chain_eval(plan, upload(host, props))
+    for _ in range(3):
+        call.out.fill_(float("nan"))
+        got = call().cpu().numpy()
+        assert rel_fro(got, want) <= TOL
+
+    bdims, bprops, batch = [32, 32, 32, 32], [L, G, U], 9
+    bhost = [sc.make_factor(32, 32, p, 500 + t, batch) for t, p in enumerate(bprops)]
+    bplan = mom.mom_chain_plan(bdims, bprops)
+    bcall = mom.bind_chain_eval_batched(bplan, [f.cuda() for f in bhost])
+    for _ in range(3):
+        bcall.out.fill_(float("nan"))
+        got = bcall().cpu().numpy()
+        for b in range(batch):
+            w = oracle.eval_dense(bdims, bprops, [f[b].numpy() for f in bhost])
+            assert rel_fro(got[b], w) <= TOL
