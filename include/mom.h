@@ -110,13 +110,16 @@ mom_status_t mom_plan_string(const mom_plan_t *plan, char *buf, size_t cap);
 /* Preorder splits (original indices) of the plan; cap entries available in out [host]. */
 mom_status_t mom_plan_splits(const mom_plan_t *plan, int32_t *out, int32_t cap);
 
-/* Bytes of device workspace mom_chain_eval needs for temporaries (may be 0). */
+/* Bytes of device workspace mom_chain_eval needs for temporaries and k-slices (may be 0). */
 size_t mom_plan_workspace_bytes(const mom_plan_t *plan);
 
 /*
  * Enqueue the evaluation of the plan on `stream` (a hipStream_t passed as void*; NULL = the
- * default stream).  Asynchronous; one kernel per binary product plus, where needed, a
- * split-K reduction or a zero-fill pass.
+ * default stream).  Asynchronous.  The products run level by level of the tree; small
+ * independent products of one level share a kernel launch, a product cut along k is followed
+ * by a launch that adds its slices, and a zero-fill pass runs last when asked for.  The
+ * library allocates nothing and never synchronises; calls on one stream run in order, calls
+ * that share a workspace or an output on different streams race.
  *   d_factors [host] array of n DEVICE pointers, entry t -> dims[t] x dims[t+1] f32;
  *             entries of Identity factors are ignored and may be NULL.
  *   lds       [host] n row strides in elements (>= dims[t+1]), or NULL for packed rows.

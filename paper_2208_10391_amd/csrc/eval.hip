@@ -1,4 +1,4 @@
-// Evaluator: walks a plan's binary products and enqueues one product kernel per step on the
+// Evaluator: walks a plan's binary products level by level and enqueues their kernels on the
 // caller's stream (MOM paper, Sec. 2 "Operations": a variadic Mul rewritten into binary
 // multiplications).  No allocation, no synchronisation, no device memory owned here.
 #include "../../include/mom.h"
