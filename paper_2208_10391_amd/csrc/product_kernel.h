@@ -8,7 +8,8 @@
 //     of its diagonal tiles (only the triangle is written).
 // This is the non-rectangular iteration space that Sec. 5 of the paper names as future work.
 //
-// Data path: global -> registers (16-byte loads) -> LDS (double buffered) -> MFMA operands.
+// Data path: global -> registers (16-byte loads, two chunks ahead) -> LDS (two stages, one
+// barrier per chunk) -> MFMA operands (read one group of 8 k-values ahead).
 // v_mfma_f32_32x32x2_f32: lane l supplies A[i = l%32][k = l/32] and B[k = l/32][j = l%32];
 // accumulator register v of lane l holds C[8*(v/4) + 4*(l/32) + v%4][l%32].
 #pragma once
@@ -106,83 +107,43 @@ struct TileConfig {
     static_assert((BM * BK / 4) % NT == 0 && (BK * BN / 4) % NT == 0, "load decomposition");
 };
 
-// Operand load modes of one k-chunk (uniform over the workgroup):
-//   0  interior: plain 16-byte loads
-//   1  in bounds and aligned, but the chunk straddles the operand's diagonal: load, then mask
-//   2  edge of the matrix or unaligned rows: element-wise, bounds-checked and masked
+// Element-wise loads of one k-chunk for the edges of a matrix and for rows that are not
+// 16-byte aligned: bounds-checked and predicated on the structure, so nothing outside the
+// matrix or the triangle is touched.  src[q] is this thread's address of the q-th group of
+// four elements in the chunk that starts at k = kc.
 template <class T>
-__device__ __forceinline__ void load_a(const ProductParams &p, int r0, int kc, int mode, int tid,
-                                       f32x4 (&ra)[T::A_F4])
+__device__ __forceinline__ void load_a_checked(const ProductParams &p, int r0, int kc, int tid,
+                                               const float *const (&src)[T::A_F4], f32x4 (&ra)[T::A_F4])
 {
-    if (mode == 0) {
 #pragma unroll
-        for (int q = 0; q < T::A_F4; ++q) {
-            const int idx = tid + q * T::NT;
-            const int gi = r0 + idx / (T::BK / 4), gk = kc + (idx % (T::BK / 4)) * 4;
-            ra[q] = *reinterpret_cast<const f32x4 *>(p.A + (int64_t)gi * p.lda + gk);
+    for (int q = 0; q < T::A_F4; ++q) {
+        const int idx = tid + q * T::NT;
+        const int gi = r0 + idx / (T::BK / 4), gk = kc + (idx % (T::BK / 4)) * 4;
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const bool ok = gi < p.M && gk + e < p.K && in_structure(p.pa, gi, gk + e);
+            v[e] = ok ? src[q][e] : 0.0f;
         }
-    } else if (mode == 1) {
-#pragma unroll
-        for (int q = 0; q < T::A_F4; ++q) {
-            const int idx = tid + q * T::NT;
-            const int gi = r0 + idx / (T::BK / 4), gk = kc + (idx % (T::BK / 4)) * 4;
-            f32x4 v = *reinterpret_cast<const f32x4 *>(p.A + (int64_t)gi * p.lda + gk);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = in_structure(p.pa, gi, gk + e) ? v[e] : 0.0f;
-            ra[q] = v;
-        }
-    } else {
-#pragma unroll
-        for (int q = 0; q < T::A_F4; ++q) {
-            const int idx = tid + q * T::NT;
-            const int gi = r0 + idx / (T::BK / 4), gk = kc + (idx % (T::BK / 4)) * 4;
-            const float *src = p.A + (int64_t)gi * p.lda + gk;
-            f32x4 v;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const bool ok = gi < p.M && gk + e < p.K && in_structure(p.pa, gi, gk + e);
-                v[e] = ok ? src[e] : 0.0f;
-            }
-            ra[q] = v;
-        }
+        ra[q] = v;
     }
 }
 
 template <class T>
-__device__ __forceinline__ void load_b(const ProductParams &p, int c0, int kc, int mode, int tid,
-                                       f32x4 (&rb)[T::B_F4])
+__device__ __forceinline__ void load_b_checked(const ProductParams &p, int c0, int kc, int tid,
+                                               const float *const (&src)[T::B_F4], f32x4 (&rb)[T::B_F4])
 {
-    if (mode == 0) {
 #pragma unroll
-        for (int q = 0; q < T::B_F4; ++q) {
-            const int idx = tid + q * T::NT;
-            const int gk = kc + idx / (T::BN / 4), gj = c0 + (idx % (T::BN / 4)) * 4;
-            rb[q] = *reinterpret_cast<const f32x4 *>(p.B + (int64_t)gk * p.ldb + gj);
+    for (int q = 0; q < T::B_F4; ++q) {
+        const int idx = tid + q * T::NT;
+        const int gk = kc + idx / (T::BN / 4), gj = c0 + (idx % (T::BN / 4)) * 4;
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const bool ok = gk < p.K && gj + e < p.N && in_structure(p.pb, gk, gj + e);
+            v[e] = ok ? src[q][e] : 0.0f;
         }
-    } else if (mode == 1) {
-#pragma unroll
-        for (int q = 0; q < T::B_F4; ++q) {
-            const int idx = tid + q * T::NT;
-            const int gk = kc + idx / (T::BN / 4), gj = c0 + (idx % (T::BN / 4)) * 4;
-            f32x4 v = *reinterpret_cast<const f32x4 *>(p.B + (int64_t)gk * p.ldb + gj);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = in_structure(p.pb, gk, gj + e) ? v[e] : 0.0f;
-            rb[q] = v;
-        }
-    } else {
-#pragma unroll
-        for (int q = 0; q < T::B_F4; ++q) {
-            const int idx = tid + q * T::NT;
-            const int gk = kc + idx / (T::BN / 4), gj = c0 + (idx % (T::BN / 4)) * 4;
-            const float *src = p.B + (int64_t)gk * p.ldb + gj;
-            f32x4 v;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const bool ok = gk < p.K && gj + e < p.N && in_structure(p.pb, gk, gj + e);
-                v[e] = ok ? src[e] : 0.0f;
-            }
-            rb[q] = v;
-        }
+        rb[q] = v;
     }
 }
 
@@ -204,47 +165,39 @@ __device__ __forceinline__ void stage_to_lds(float *As, float *Bs, int tid,
 
 // MFMA operands of one group of 8 k-values: lane (l32, half) takes A[row l32][k = 4*half + e]
 // for e = 0..3 with one 16-byte LDS read per 32-row block, and B[k = 4*half + e][col l32].
+// a_lane / b_lane are the lane's own offsets inside a stage: (wr0 + l32) * LDA + 4 * half and
+// 4 * half * LDB + wc0 + l32.
 template <class T>
-__device__ __forceinline__ void load_fragments(const float *As, const float *Bs, int kg, int wr0, int wc0, int l32,
-                                               int half, f32x4 (&a)[T::FM], float (&b)[T::FN][4])
+struct Fragments {
+    f32x4 a[T::FM];
+    float b[T::FN][4];
+};
+
+template <class T>
+__device__ __forceinline__ void read_fragments(const float *As, const float *Bs, int a_lane, int b_lane, int kg,
+                                               Fragments<T> &f)
 {
 #pragma unroll
     for (int bi = 0; bi < T::FM; ++bi)
-        a[bi] = *reinterpret_cast<const f32x4 *>(As + (wr0 + bi * 32 + l32) * T::LDA + kg * 8 + 4 * half);
+        f.a[bi] = *reinterpret_cast<const f32x4 *>(As + a_lane + bi * 32 * T::LDA + kg * 8);
 #pragma unroll
     for (int bj = 0; bj < T::FN; ++bj)
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-            b[bj][e] = Bs[(kg * 8 + 4 * half + e) * T::LDB + wc0 + bj * 32 + l32];
+        for (int e = 0; e < 4; ++e) f.b[bj][e] = Bs[b_lane + (kg * 8 + e) * T::LDB + bj * 32];
 }
 
-// One k-chunk of MFMA work from LDS.  Within each group of 8 k-values, MFMA step e (0..3)
-// multiplies k = 4*half + e (the order of summation over k is free).  The operands of the
-// next group are fetched from LDS before the MFMAs of the current one are issued, so the
-// matrix pipe does not wait on LDS latency.  `between` runs once, after the first operand
-// reads have been issued and before the first MFMA: the place for the memory traffic of the
-// software pipeline (LDS writes of the next chunk, global loads of the one after).
-template <class T, class Between>
-__device__ __forceinline__ void mfma_chunk(const float *As, const float *Bs, int wr0, int wc0, int l32, int half,
-                                           f32x16 (&acc)[T::FM][T::FN], Between between)
+// The 4 * FM * FN MFMAs of one group of 8 k-values: step e multiplies k = 4*half + e (the
+// order of summation over k is free).
+template <class T>
+__device__ __forceinline__ void mfma_group(const Fragments<T> &f, f32x16 (&acc)[T::FM][T::FN])
 {
-    f32x4 a[2][T::FM];
-    float b[2][T::FN][4];
-    load_fragments<T>(As, Bs, 0, wr0, wc0, l32, half, a[0], b[0]);
-    between();
 #pragma unroll
-    for (int kg = 0; kg < T::BK / 8; ++kg) {
-        if (kg + 1 < T::BK / 8) load_fragments<T>(As, Bs, kg + 1, wr0, wc0, l32, half, a[(kg + 1) & 1], b[(kg + 1) & 1]);
-        __builtin_amdgcn_sched_barrier(0);      // keep the LDS reads ahead of this group's MFMAs
+    for (int e = 0; e < 4; ++e)
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
+        for (int bi = 0; bi < T::FM; ++bi)
 #pragma unroll
-            for (int bi = 0; bi < T::FM; ++bi)
-#pragma unroll
-                for (int bj = 0; bj < T::FN; ++bj)
-                    acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[kg & 1][bi][e], b[kg & 1][bj][e], acc[bi][bj],
-                                                                       0, 0, 0);
-    }
+            for (int bj = 0; bj < T::FN; ++bj)
+                acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[bi][e], f.b[bj][e], acc[bi][bj], 0, 0, 0);
 }
 
 // What one output tile needs: where it sits, its k-range in chunks, and which chunks are
@@ -300,22 +253,142 @@ __device__ __forceinline__ TileWork tile_work(const ProductParams &p, int t, int
     return w;
 }
 
-template <class T>
-__device__ __forceinline__ int load_mode_a(const ProductParams &p, const TileWork &w, int kc)
-{
-    if (w.a_edge || kc + T::BK > p.K) return 2;
-    if (p.pa == kLower && kc + T::BK - 1 > w.r0) return 1;
-    if (p.pa == kUpper && kc < w.r0 + T::BM - 1) return 1;
-    return 0;
-}
+// How the operands of chunk j of a tile get from HBM to LDS (uniform over the workgroup):
+//   kPlain  16-byte loads, staged as they are
+//   kDiag   16-byte loads; the chunk straddles a diagonal, so the elements outside the
+//           structure are zeroed when the registers are staged (one chunk after the load, when
+//           the data has long arrived)
+//   kEdge   edge of a matrix or unaligned rows: element-wise loads, bounds-checked and
+//           predicated on the structure; staged as they are
+enum ChunkKind : int { kPlain = 0, kDiag = 1, kEdge = 2 };
 
 template <class T>
-__device__ __forceinline__ int load_mode_b(const ProductParams &p, const TileWork &w, int kc)
+__device__ __forceinline__ int chunk_kind(const ProductParams &p, const TileWork &w, int j)
 {
-    if (w.b_edge || kc + T::BK > p.K) return 2;
-    if (p.pb == kLower && w.c0 + T::BN - 1 > kc) return 1;
-    if (p.pb == kUpper && kc + T::BK - 1 > w.c0) return 1;
-    return 0;
+    if (j >= w.f_lo && j < w.f_hi) return kPlain;
+    return (w.a_edge || w.b_edge || w.klo + (j + 1) * T::BK > p.K) ? kEdge : kDiag;
+}
+
+// Zero what lies outside the structures in the registers of the chunk that starts at k = kc.
+template <class T>
+__device__ __forceinline__ void mask_registers(const ProductParams &p, int r0, int c0, int kc, int tid,
+                                               f32x4 (&ra)[T::A_F4], f32x4 (&rb)[T::B_F4])
+{
+    if (p.pa != kGeneral) {
+#pragma unroll
+        for (int q = 0; q < T::A_F4; ++q) {
+            const int idx = tid + q * T::NT;
+            const int gi = r0 + idx / (T::BK / 4), gk = kc + (idx % (T::BK / 4)) * 4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) ra[q][e] = in_structure(p.pa, gi, gk + e) ? ra[q][e] : 0.0f;
+        }
+    }
+    if (p.pb != kGeneral) {
+#pragma unroll
+        for (int q = 0; q < T::B_F4; ++q) {
+            const int idx = tid + q * T::NT;
+            const int gk = kc + idx / (T::BN / 4), gj = c0 + (idx % (T::BN / 4)) * 4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) rb[q][e] = in_structure(p.pb, gk, gj + e) ? rb[q][e] : 0.0f;
+        }
+    }
+}
+
+// Scheduling groups (masks of __builtin_amdgcn_sched_group_barrier).
+constexpr int kSchedMfma = 0x008, kSchedVmemRead = 0x020, kSchedLdsRead = 0x100, kSchedLdsWrite = 0x200;
+
+// Per-thread state of the software pipeline of one workgroup.
+template <class T>
+struct Pipeline {
+    f32x4 ra[T::A_F4], rb[T::B_F4];     // the chunk on its way from HBM to LDS
+    const float *a_src[T::A_F4];        // this thread's addresses in the next chunk to load
+    const float *b_src[T::B_F4];        // (they advance with every chunk fetched)
+    Fragments<T> f0, f1;                // MFMA operands: current group, next group
+};
+
+// One k-chunk: the MFMAs of chunk c out of LDS stage s while chunk c+1 moves from registers to
+// the other stage and the loads of chunk c+2 are issued.  On entry pl.f0 holds the operands
+// of the chunk's first group; on exit those of chunk c+1's first group.  The workgroup barrier
+// sits before the last group's MFMAs: by then every read of stage s has returned and the other
+// stage is complete, so the first operands of chunk c+1 are read under the last MFMAs.
+//   stage: 0 nothing left to stage, 1 stage the registers, 2 mask them first (kDiag)
+//   load:  0 nothing left to load, 1 16-byte loads, 2 element-wise (kEdge)
+// With HOT the three are compile-time constants (s, 1, 1) and the body is a single basic
+// block whose instruction mix is laid out by scheduling groups: LDS writes and global loads
+// one per MFMA in the first group, LDS reads spread over the MFMAs of every group.
+template <class T, bool HOT, int S>
+__device__ __forceinline__ void chunk_step(float *smem, const ProductParams &p, const TileWork &w, int c, int s_,
+                                           int stage_, int load_, int tid, int a_lane, int b_lane,
+                                           Pipeline<T> &pl, f32x16 (&acc)[T::FM][T::FN])
+{
+    constexpr int NKG = T::BK / 8;
+    static_assert(NKG % 2 == 0, "the operand double buffer returns to f0 after an even number of groups");
+    constexpr int NMFMA = 4 * T::FM * T::FN, NREAD = T::FM + 2 * T::FN, NMOVE = T::A_F4 + T::B_F4;
+    const int s = HOT ? S : s_, stage = HOT ? 1 : stage_, load = HOT ? 1 : load_;
+    const float *As = smem + s * T::A_STAGE, *Bs = smem + 2 * T::A_STAGE + s * T::B_STAGE;
+    float *An = smem + (s ^ 1) * T::A_STAGE, *Bn = smem + 2 * T::A_STAGE + (s ^ 1) * T::B_STAGE;
+
+    read_fragments<T>(As, Bs, a_lane, b_lane, 1, pl.f1);
+    if (stage) {
+        if (stage == 2) mask_registers<T>(p, w.r0, w.c0, w.klo + (c + 1) * T::BK, tid, pl.ra, pl.rb);
+        stage_to_lds<T>(An, Bn, tid, pl.ra, pl.rb);
+    }
+    if (load) {
+        if (load == 1) {
+#pragma unroll
+            for (int q = 0; q < T::A_F4; ++q) pl.ra[q] = *reinterpret_cast<const f32x4 *>(pl.a_src[q]);
+#pragma unroll
+            for (int q = 0; q < T::B_F4; ++q) pl.rb[q] = *reinterpret_cast<const f32x4 *>(pl.b_src[q]);
+        } else {
+            const int kc = w.klo + (c + 2) * T::BK;
+            load_a_checked<T>(p, w.r0, kc, tid, pl.a_src, pl.ra);
+            load_b_checked<T>(p, w.c0, kc, tid, pl.b_src, pl.rb);
+        }
+        const int64_t b_step = (int64_t)T::BK * p.ldb;
+#pragma unroll
+        for (int q = 0; q < T::A_F4; ++q) pl.a_src[q] += T::BK;
+#pragma unroll
+        for (int q = 0; q < T::B_F4; ++q) pl.b_src[q] += b_step;
+    }
+    mfma_group<T>(pl.f0, acc);
+    if (HOT) {
+        __builtin_amdgcn_sched_group_barrier(kSchedLdsRead, NREAD, 0);
+#pragma unroll
+        for (int i = 0; i < NMOVE; ++i) {
+            __builtin_amdgcn_sched_group_barrier(kSchedMfma, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(kSchedLdsWrite, 1, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < NMOVE; ++i) {
+            __builtin_amdgcn_sched_group_barrier(kSchedMfma, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(kSchedVmemRead, 1, 0);
+        }
+    } else {
+        __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int kg = 1; kg < NKG; ++kg) {
+        Fragments<T> &now = (kg & 1) ? pl.f1 : pl.f0;
+        Fragments<T> &next = (kg & 1) ? pl.f0 : pl.f1;
+        if (kg + 1 < NKG) {
+            read_fragments<T>(As, Bs, a_lane, b_lane, kg + 1, next);
+        } else {
+            __syncthreads();
+            if (stage) read_fragments<T>(An, Bn, a_lane, b_lane, 0, next);
+        }
+        mfma_group<T>(now, acc);
+        if (HOT) {
+            constexpr int PER = NMFMA / NREAD > 0 ? NMFMA / NREAD : 1;
+#pragma unroll
+            for (int i = 0; i < NREAD; ++i) {
+                __builtin_amdgcn_sched_group_barrier(kSchedLdsRead, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(kSchedMfma, PER, 0);
+            }
+            if (NMFMA > PER * NREAD) __builtin_amdgcn_sched_group_barrier(kSchedMfma, NMFMA - PER * NREAD, 0);
+        } else {
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
 }
 
 template <class T>
@@ -327,86 +400,28 @@ __global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const Pro
     const int local = (int)blockIdx.x - (which ? batch.block_end[which - 1] : 0);
     const int slice = local / p.grid, block = local % p.grid;
 
-    extern __shared__ __align__(16) float smem[];
-    float *const As = smem;                       // two stages of the A tile
-    float *const Bs = smem + 2 * T::A_STAGE;      // two stages of the B tile
+    extern __shared__ __align__(16) float smem[];     // A stages 0 and 1, then B stages 0 and 1
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
     const int wr0 = (wave / T::WN) * T::WTM, wc0 = (wave % T::WN) * T::WTN;
+    const int a_lane = (wr0 + l32) * T::LDA + 4 * half, b_lane = 4 * half * T::LDB + wc0 + l32;
 
-    // The tiles of this workgroup, in order: tile `block` and its partner from the other end of
-    // the longest-first order when tiles are paired, else every grid-th tile.
-    auto tile_at = [&](int i) {
+    Pipeline<T> pl;
+    for (int seq = 0;; ++seq) {
+        // the tiles of this workgroup: tile `block` and its partner from the other end of the
+        // longest-first order when tiles are paired, else every grid-th tile
+        int t;
         if (p.paired) {
             const int partner = p.num_tiles - 1 - block;
-            return i == 0 ? block : (i == 1 && partner > block ? partner : -1);
-        }
-        const int64_t t = block + (int64_t)i * p.grid;
-        return t < p.num_tiles ? (int)t : -1;
-    };
-
-    // Fetch side of the software pipeline.  It walks the flat sequence of (tile, chunk) pairs
-    // of this workgroup two chunks ahead of the MFMAs and simply carries on into the next tile,
-    // so a tile's first chunks arrive while the previous tile is still being multiplied.
-    f32x4 ra[T::A_F4], rb[T::B_F4];
-    const float *a_src[T::A_F4], *b_src[T::B_F4];    // this thread's addresses of the fetch tile's chunk 0
-    TileWork fw{};
-    int f_seq = -1, f_chunk = 0;
-    bool f_live = true;
-    auto next_fetch_tile = [&]() {
-        for (;;) {
-            const int t = tile_at(++f_seq);
-            if (t < 0) { f_live = false; return; }
-            fw = tile_work<T>(p, t, slice);
-            if (fw.nchunks > 0) break;
-        }
-        f_chunk = 0;
-#pragma unroll
-        for (int q = 0; q < T::A_F4; ++q) {
-            const int idx = tid + q * T::NT;
-            a_src[q] = p.A + (int64_t)(fw.r0 + idx / (T::BK / 4)) * p.lda + fw.klo + (idx % (T::BK / 4)) * 4;
-        }
-#pragma unroll
-        for (int q = 0; q < T::B_F4; ++q) {
-            const int idx = tid + q * T::NT;
-            b_src[q] = p.B + (int64_t)(fw.klo + idx / (T::BN / 4)) * p.ldb + fw.c0 + (idx % (T::BN / 4)) * 4;
-        }
-    };
-    auto fetch_next = [&]() {                        // next chunk: global -> registers
-        if (!f_live) return false;
-        const int j = f_chunk;
-        if (j >= fw.f_lo && j < fw.f_hi) {
-            const int64_t a_step = (int64_t)j * T::BK, b_step = a_step * p.ldb;
-#pragma unroll
-            for (int q = 0; q < T::A_F4; ++q) ra[q] = *reinterpret_cast<const f32x4 *>(a_src[q] + a_step);
-#pragma unroll
-            for (int q = 0; q < T::B_F4; ++q) rb[q] = *reinterpret_cast<const f32x4 *>(b_src[q] + b_step);
+            t = seq == 0 ? block : (seq == 1 && partner > block ? partner : -1);
         } else {
-            const int kc = fw.klo + j * T::BK;
-            load_a<T>(p, fw.r0, kc, load_mode_a<T>(p, fw, kc), tid, ra);
-            load_b<T>(p, fw.c0, kc, load_mode_b<T>(p, fw, kc), tid, rb);
+            const int64_t far = block + (int64_t)seq * p.grid;
+            t = far < p.num_tiles ? (int)far : -1;
         }
-        if (++f_chunk == fw.nchunks) next_fetch_tile();
-        return true;
-    };
-
-    // Two LDS stages, one barrier per chunk: while flat chunk g is multiplied out of stage
-    // g&1, chunk g+1 moves from registers into the other stage and the loads of chunk g+2 are
-    // issued into the same registers.
-    next_fetch_tile();
-    bool in_regs = false;
-    if (fetch_next()) {
-        stage_to_lds<T>(As, Bs, tid, ra, rb);
-        in_regs = fetch_next();
-    }
-    __syncthreads();
-
-    int g = 0;
-    for (int seq = 0;; ++seq) {
-        const int t = tile_at(seq);
         if (t < 0) break;
         const TileWork w = tile_work<T>(p, t, slice);
+        const int n = w.nchunks;
 
         f32x16 acc[T::FM][T::FN];
 #pragma unroll
@@ -416,13 +431,62 @@ __global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const Pro
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[bi][bj][v] = 0.0f;
 
-        for (int c = 0; c < w.nchunks; ++c, ++g) {
-            const int cur = g & 1, nxt = cur ^ 1;
-            mfma_chunk<T>(As + cur * T::A_STAGE, Bs + cur * T::B_STAGE, wr0, wc0, l32, half, acc, [&]() {
-                if (in_regs) stage_to_lds<T>(As + nxt * T::A_STAGE, Bs + nxt * T::B_STAGE, tid, ra, rb);
-                in_regs = fetch_next();
-            });
+        if (n > 0) {
+            // prologue: chunk 0 into stage 0, chunk 1 into the registers.  Every wavefront has
+            // passed the last barrier of the previous tile, after which nobody reads LDS.
+#pragma unroll
+            for (int q = 0; q < T::A_F4; ++q) {
+                const int idx = tid + q * T::NT;
+                pl.a_src[q] = p.A + (int64_t)(w.r0 + idx / (T::BK / 4)) * p.lda + w.klo + (idx % (T::BK / 4)) * 4;
+            }
+#pragma unroll
+            for (int q = 0; q < T::B_F4; ++q) {
+                const int idx = tid + q * T::NT;
+                pl.b_src[q] = p.B + (int64_t)(w.klo + idx / (T::BN / 4)) * p.ldb + w.c0 + (idx % (T::BN / 4)) * 4;
+            }
+            auto fetch = [&](int j) __attribute__((always_inline)) {       // chunk j: HBM -> registers
+                if (chunk_kind<T>(p, w, j) == kEdge) {
+                    load_a_checked<T>(p, w.r0, w.klo + j * T::BK, tid, pl.a_src, pl.ra);
+                    load_b_checked<T>(p, w.c0, w.klo + j * T::BK, tid, pl.b_src, pl.rb);
+                } else {
+#pragma unroll
+                    for (int q = 0; q < T::A_F4; ++q) pl.ra[q] = *reinterpret_cast<const f32x4 *>(pl.a_src[q]);
+#pragma unroll
+                    for (int q = 0; q < T::B_F4; ++q) pl.rb[q] = *reinterpret_cast<const f32x4 *>(pl.b_src[q]);
+                }
+                const int64_t b_step = (int64_t)T::BK * p.ldb;
+#pragma unroll
+                for (int q = 0; q < T::A_F4; ++q) pl.a_src[q] += T::BK;
+#pragma unroll
+                for (int q = 0; q < T::B_F4; ++q) pl.b_src[q] += b_step;
+            };
+            fetch(0);
+            if (chunk_kind<T>(p, w, 0) == kDiag) mask_registers<T>(p, w.r0, w.c0, w.klo, tid, pl.ra, pl.rb);
+            stage_to_lds<T>(smem, smem + 2 * T::A_STAGE, tid, pl.ra, pl.rb);
+            if (n > 1) fetch(1);
             __syncthreads();
+            read_fragments<T>(smem, smem + 2 * T::A_STAGE, a_lane, b_lane, 0, pl.f0);
+
+            // Chunk c stages chunk c+1 and loads chunk c+2.  Where both are plain, pairs of
+            // chunks (stage 0, stage 1) run the decision-free body; everything else (heads and
+            // tails of the k-range, diagonals, edges) takes the general body one chunk at a time.
+            int c = 0;
+            while (c < n) {
+                const int hot_from = max(w.f_lo - 1, 0), hot_to = w.f_hi - 2;   // c in [hot_from, hot_to)
+                if (!(c & 1) && c >= hot_from && c + 2 <= hot_to) {
+                    const int pairs = (hot_to - c) / 2;
+                    for (int i = 0; i < pairs; ++i) {
+                        chunk_step<T, true, 0>(smem, p, w, 0, 0, 1, 1, tid, a_lane, b_lane, pl, acc);
+                        chunk_step<T, true, 1>(smem, p, w, 0, 1, 1, 1, tid, a_lane, b_lane, pl, acc);
+                    }
+                    c += 2 * pairs;
+                    continue;
+                }
+                const int stage = c + 1 < n ? (chunk_kind<T>(p, w, c + 1) == kDiag ? 2 : 1) : 0;
+                const int load = c + 2 < n ? (chunk_kind<T>(p, w, c + 2) == kEdge ? 2 : 1) : 0;
+                chunk_step<T, false, 0>(smem, p, w, c, c & 1, stage, load, tid, a_lane, b_lane, pl, acc);
+                ++c;
+            }
         }
 
         // store: full tiles of a general result (or tiles strictly inside the triangle) go out
