@@ -297,58 +297,121 @@ __device__ __forceinline__ void mask_registers(const ProductParams &p, int r0, i
 // Scheduling groups (masks of __builtin_amdgcn_sched_group_barrier).
 constexpr int kSchedMfma = 0x008, kSchedVmemRead = 0x020, kSchedLdsRead = 0x100, kSchedLdsWrite = 0x200;
 
-// Per-thread state of the software pipeline of one workgroup.
+// Per-thread state of the software pipeline of one workgroup.  The pipeline is flat over the
+// (tile, chunk) pairs of the workgroup: the fetch side runs two chunks ahead of the MFMAs and
+// simply carries on into the next tile, so a tile's first chunks arrive while the previous
+// tile is still being multiplied and stored.
 template <class T>
 struct Pipeline {
     f32x4 ra[T::A_F4], rb[T::B_F4];     // the chunk on its way from HBM to LDS
     const float *a_src[T::A_F4];        // this thread's addresses in the next chunk to load
     const float *b_src[T::B_F4];        // (they advance with every chunk fetched)
     Fragments<T> f0, f1;                // MFMA operands: current group, next group
+    // fetch cursor: the next chunk to load is chunk fj of tile fw (the f_seq-th of the workgroup)
+    TileWork fw;
+    int f_seq, fj;
+    bool f_live;                        // false once every chunk of the workgroup has been loaded
+    // the chunk that sits in ra / rb
+    bool in_regs;
+    int reg_kind, reg_r0, reg_c0, reg_kc;
 };
 
-// One k-chunk: the MFMAs of chunk c out of LDS stage s while chunk c+1 moves from registers to
-// the other stage and the loads of chunk c+2 are issued.  On entry pl.f0 holds the operands
-// of the chunk's first group; on exit those of chunk c+1's first group.  The workgroup barrier
-// sits before the last group's MFMAs: by then every read of stage s has returned and the other
-// stage is complete, so the first operands of chunk c+1 are read under the last MFMAs.
-//   stage: 0 nothing left to stage, 1 stage the registers, 2 mask them first (kDiag)
-//   load:  0 nothing left to load, 1 16-byte loads, 2 element-wise (kEdge)
-// With HOT the three are compile-time constants (s, 1, 1) and the body is a single basic
-// block whose instruction mix is laid out by scheduling groups: LDS writes and global loads
-// one per MFMA in the first group, LDS reads spread over the MFMAs of every group.
+// The i-th tile of a workgroup (-1: none): tile `block` and its partner from the other end of
+// the longest-first order when tiles are paired, else every grid-th tile.
+__device__ __forceinline__ int tile_at(const ProductParams &p, int block, int i)
+{
+    if (p.paired) {
+        const int partner = p.num_tiles - 1 - block;
+        return i == 0 ? block : (i == 1 && partner > block ? partner : -1);
+    }
+    const int64_t t = block + (int64_t)i * p.grid;
+    return t < p.num_tiles ? (int)t : -1;
+}
+
+template <class T>
+__device__ __forceinline__ void next_fetch_tile(const ProductParams &p, int block, int slice, int tid, Pipeline<T> &pl)
+{
+    for (;;) {
+        const int t = tile_at(p, block, ++pl.f_seq);
+        if (t < 0) { pl.f_live = false; return; }
+        pl.fw = tile_work<T>(p, t, slice);
+        if (pl.fw.nchunks > 0) break;
+    }
+    pl.fj = 0;
+#pragma unroll
+    for (int q = 0; q < T::A_F4; ++q) {
+        const int idx = tid + q * T::NT;
+        pl.a_src[q] = p.A + (int64_t)(pl.fw.r0 + idx / (T::BK / 4)) * p.lda + pl.fw.klo + (idx % (T::BK / 4)) * 4;
+    }
+#pragma unroll
+    for (int q = 0; q < T::B_F4; ++q) {
+        const int idx = tid + q * T::NT;
+        pl.b_src[q] = p.B + (int64_t)(pl.fw.klo + idx / (T::BN / 4)) * p.ldb + pl.fw.c0 + (idx % (T::BN / 4)) * 4;
+    }
+}
+
+// Next chunk of the flat sequence: HBM -> registers.
+template <class T>
+__device__ __forceinline__ void fetch_chunk(const ProductParams &p, int block, int slice, int tid, Pipeline<T> &pl)
+{
+    pl.in_regs = pl.f_live;
+    if (!pl.f_live) return;
+    const int kind = chunk_kind<T>(p, pl.fw, pl.fj), kc = pl.fw.klo + pl.fj * T::BK;
+    if (kind == kEdge) {
+        load_a_checked<T>(p, pl.fw.r0, kc, tid, pl.a_src, pl.ra);
+        load_b_checked<T>(p, pl.fw.c0, kc, tid, pl.b_src, pl.rb);
+    } else {
+#pragma unroll
+        for (int q = 0; q < T::A_F4; ++q) pl.ra[q] = *reinterpret_cast<const f32x4 *>(pl.a_src[q]);
+#pragma unroll
+        for (int q = 0; q < T::B_F4; ++q) pl.rb[q] = *reinterpret_cast<const f32x4 *>(pl.b_src[q]);
+    }
+    const int64_t b_step = (int64_t)T::BK * p.ldb;
+#pragma unroll
+    for (int q = 0; q < T::A_F4; ++q) pl.a_src[q] += T::BK;
+#pragma unroll
+    for (int q = 0; q < T::B_F4; ++q) pl.b_src[q] += b_step;
+    pl.reg_kind = kind; pl.reg_r0 = pl.fw.r0; pl.reg_c0 = pl.fw.c0; pl.reg_kc = kc;
+    if (++pl.fj == pl.fw.nchunks) next_fetch_tile<T>(p, block, slice, tid, pl);
+}
+
+// One k-chunk: the MFMAs of flat chunk g out of LDS stage s while chunk g+1 moves from the
+// registers to the other stage and the loads of chunk g+2 are issued.  On entry pl.f0 holds
+// the operands of the chunk's first group; on exit those of chunk g+1's first group.  The
+// workgroup barrier sits before the last group's MFMAs: by then every read of stage s has
+// returned and the other stage is complete, so the first operands of chunk g+1 are read under
+// the last MFMAs.
+// With HOT the chunk in the registers and the one to load are both plain and s is the
+// compile-time S: the body is a single basic block whose instruction mix is laid out by
+// scheduling groups, LDS writes and global loads one per MFMA in the first group, LDS reads
+// spread over the MFMAs of every group.  Without HOT the body decides as it goes: mask
+// (kDiag), element-wise loads (kEdge), a new fetch tile, the end of the workgroup's chunks.
 template <class T, bool HOT, int S>
-__device__ __forceinline__ void chunk_step(float *smem, const ProductParams &p, const TileWork &w, int c, int s_,
-                                           int stage_, int load_, int tid, int a_lane, int b_lane,
-                                           Pipeline<T> &pl, f32x16 (&acc)[T::FM][T::FN])
+__device__ __forceinline__ void chunk_step(float *smem, const ProductParams &p, int block, int slice, int s_, int tid,
+                                           int a_lane, int b_lane, Pipeline<T> &pl, f32x16 (&acc)[T::FM][T::FN])
 {
     constexpr int NKG = T::BK / 8;
     static_assert(NKG % 2 == 0, "the operand double buffer returns to f0 after an even number of groups");
     constexpr int NMFMA = 4 * T::FM * T::FN, NREAD = T::FM + 2 * T::FN, NMOVE = T::A_F4 + T::B_F4;
-    const int s = HOT ? S : s_, stage = HOT ? 1 : stage_, load = HOT ? 1 : load_;
+    const int s = HOT ? S : s_;
     const float *As = smem + s * T::A_STAGE, *Bs = smem + 2 * T::A_STAGE + s * T::B_STAGE;
     float *An = smem + (s ^ 1) * T::A_STAGE, *Bn = smem + 2 * T::A_STAGE + (s ^ 1) * T::B_STAGE;
 
     read_fragments<T>(As, Bs, a_lane, b_lane, 1, pl.f1);
-    if (stage) {
-        if (stage == 2) mask_registers<T>(p, w.r0, w.c0, w.klo + (c + 1) * T::BK, tid, pl.ra, pl.rb);
+    const bool staged = HOT ? true : pl.in_regs;
+    if (HOT) {
         stage_to_lds<T>(An, Bn, tid, pl.ra, pl.rb);
-    }
-    if (load) {
-        if (load == 1) {
-#pragma unroll
-            for (int q = 0; q < T::A_F4; ++q) pl.ra[q] = *reinterpret_cast<const f32x4 *>(pl.a_src[q]);
-#pragma unroll
-            for (int q = 0; q < T::B_F4; ++q) pl.rb[q] = *reinterpret_cast<const f32x4 *>(pl.b_src[q]);
-        } else {
-            const int kc = w.klo + (c + 2) * T::BK;
-            load_a_checked<T>(p, w.r0, kc, tid, pl.a_src, pl.ra);
-            load_b_checked<T>(p, w.c0, kc, tid, pl.b_src, pl.rb);
-        }
         const int64_t b_step = (int64_t)T::BK * p.ldb;
 #pragma unroll
-        for (int q = 0; q < T::A_F4; ++q) pl.a_src[q] += T::BK;
+        for (int q = 0; q < T::A_F4; ++q) { pl.ra[q] = *reinterpret_cast<const f32x4 *>(pl.a_src[q]); pl.a_src[q] += T::BK; }
 #pragma unroll
-        for (int q = 0; q < T::B_F4; ++q) pl.b_src[q] += b_step;
+        for (int q = 0; q < T::B_F4; ++q) { pl.rb[q] = *reinterpret_cast<const f32x4 *>(pl.b_src[q]); pl.b_src[q] += b_step; }
+    } else {
+        if (pl.in_regs) {
+            if (pl.reg_kind == kDiag) mask_registers<T>(p, pl.reg_r0, pl.reg_c0, pl.reg_kc, tid, pl.ra, pl.rb);
+            stage_to_lds<T>(An, Bn, tid, pl.ra, pl.rb);
+        }
+        fetch_chunk<T>(p, block, slice, tid, pl);
     }
     mfma_group<T>(pl.f0, acc);
     if (HOT) {
@@ -374,7 +437,7 @@ __device__ __forceinline__ void chunk_step(float *smem, const ProductParams &p, 
             read_fragments<T>(As, Bs, a_lane, b_lane, kg + 1, next);
         } else {
             __syncthreads();
-            if (stage) read_fragments<T>(An, Bn, a_lane, b_lane, 0, next);
+            if (staged) read_fragments<T>(An, Bn, a_lane, b_lane, 0, next);
         }
         mfma_group<T>(now, acc);
         if (HOT) {
@@ -407,18 +470,23 @@ __global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const Pro
     const int wr0 = (wave / T::WN) * T::WTM, wc0 = (wave % T::WN) * T::WTN;
     const int a_lane = (wr0 + l32) * T::LDA + 4 * half, b_lane = 4 * half * T::LDB + wc0 + l32;
 
+    // prologue of the whole workgroup: flat chunk 0 into stage 0, flat chunk 1 into the registers
     Pipeline<T> pl;
+    pl.f_seq = -1;
+    pl.f_live = true;
+    next_fetch_tile<T>(p, block, slice, tid, pl);
+    fetch_chunk<T>(p, block, slice, tid, pl);
+    if (pl.in_regs) {
+        if (pl.reg_kind == kDiag) mask_registers<T>(p, pl.reg_r0, pl.reg_c0, pl.reg_kc, tid, pl.ra, pl.rb);
+        stage_to_lds<T>(smem, smem + 2 * T::A_STAGE, tid, pl.ra, pl.rb);
+        fetch_chunk<T>(p, block, slice, tid, pl);
+    }
+    __syncthreads();
+    read_fragments<T>(smem, smem + 2 * T::A_STAGE, a_lane, b_lane, 0, pl.f0);
+
+    int g = 0;                                         // flat chunk counter: chunk g sits in stage g & 1
     for (int seq = 0;; ++seq) {
-        // the tiles of this workgroup: tile `block` and its partner from the other end of the
-        // longest-first order when tiles are paired, else every grid-th tile
-        int t;
-        if (p.paired) {
-            const int partner = p.num_tiles - 1 - block;
-            t = seq == 0 ? block : (seq == 1 && partner > block ? partner : -1);
-        } else {
-            const int64_t far = block + (int64_t)seq * p.grid;
-            t = far < p.num_tiles ? (int)far : -1;
-        }
+        const int t = tile_at(p, block, seq);
         if (t < 0) break;
         const TileWork w = tile_work<T>(p, t, slice);
         const int n = w.nchunks;
@@ -431,62 +499,28 @@ __global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const Pro
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[bi][bj][v] = 0.0f;
 
-        if (n > 0) {
-            // prologue: chunk 0 into stage 0, chunk 1 into the registers.  Every wavefront has
-            // passed the last barrier of the previous tile, after which nobody reads LDS.
-#pragma unroll
-            for (int q = 0; q < T::A_F4; ++q) {
-                const int idx = tid + q * T::NT;
-                pl.a_src[q] = p.A + (int64_t)(w.r0 + idx / (T::BK / 4)) * p.lda + w.klo + (idx % (T::BK / 4)) * 4;
-            }
-#pragma unroll
-            for (int q = 0; q < T::B_F4; ++q) {
-                const int idx = tid + q * T::NT;
-                pl.b_src[q] = p.B + (int64_t)(w.klo + idx / (T::BN / 4)) * p.ldb + w.c0 + (idx % (T::BN / 4)) * 4;
-            }
-            auto fetch = [&](int j) __attribute__((always_inline)) {       // chunk j: HBM -> registers
-                if (chunk_kind<T>(p, w, j) == kEdge) {
-                    load_a_checked<T>(p, w.r0, w.klo + j * T::BK, tid, pl.a_src, pl.ra);
-                    load_b_checked<T>(p, w.c0, w.klo + j * T::BK, tid, pl.b_src, pl.rb);
-                } else {
-#pragma unroll
-                    for (int q = 0; q < T::A_F4; ++q) pl.ra[q] = *reinterpret_cast<const f32x4 *>(pl.a_src[q]);
-#pragma unroll
-                    for (int q = 0; q < T::B_F4; ++q) pl.rb[q] = *reinterpret_cast<const f32x4 *>(pl.b_src[q]);
-                }
-                const int64_t b_step = (int64_t)T::BK * p.ldb;
-#pragma unroll
-                for (int q = 0; q < T::A_F4; ++q) pl.a_src[q] += T::BK;
-#pragma unroll
-                for (int q = 0; q < T::B_F4; ++q) pl.b_src[q] += b_step;
-            };
-            fetch(0);
-            if (chunk_kind<T>(p, w, 0) == kDiag) mask_registers<T>(p, w.r0, w.c0, w.klo, tid, pl.ra, pl.rb);
-            stage_to_lds<T>(smem, smem + 2 * T::A_STAGE, tid, pl.ra, pl.rb);
-            if (n > 1) fetch(1);
-            __syncthreads();
-            read_fragments<T>(smem, smem + 2 * T::A_STAGE, a_lane, b_lane, 0, pl.f0);
-
-            // Chunk c stages chunk c+1 and loads chunk c+2.  Where both are plain, pairs of
-            // chunks (stage 0, stage 1) run the decision-free body; everything else (heads and
-            // tails of the k-range, diagonals, edges) takes the general body one chunk at a time.
-            int c = 0;
-            while (c < n) {
-                const int hot_from = max(w.f_lo - 1, 0), hot_to = w.f_hi - 2;   // c in [hot_from, hot_to)
-                if (!(c & 1) && c >= hot_from && c + 2 <= hot_to) {
-                    const int pairs = (hot_to - c) / 2;
+        int c = 0;
+        while (c < n) {
+            // Pairs of chunks (stage 0, stage 1) run the decision-free body for as long as the
+            // chunk in the registers and the ones to load are plain chunks of the fetch tile.
+            if (!(g & 1) && pl.in_regs && pl.reg_kind == kPlain && pl.f_live && pl.fj >= pl.fw.f_lo) {
+                const int pairs = min(n - c, pl.fw.f_hi - pl.fj) / 2;
+                if (pairs > 0) {
                     for (int i = 0; i < pairs; ++i) {
-                        chunk_step<T, true, 0>(smem, p, w, 0, 0, 1, 1, tid, a_lane, b_lane, pl, acc);
-                        chunk_step<T, true, 1>(smem, p, w, 0, 1, 1, 1, tid, a_lane, b_lane, pl, acc);
+                        chunk_step<T, true, 0>(smem, p, block, slice, 0, tid, a_lane, b_lane, pl, acc);
+                        chunk_step<T, true, 1>(smem, p, block, slice, 1, tid, a_lane, b_lane, pl, acc);
                     }
                     c += 2 * pairs;
+                    g += 2 * pairs;
+                    pl.fj += 2 * pairs;                          // the registers hold chunk fj-1 of the fetch tile
+                    pl.reg_r0 = pl.fw.r0; pl.reg_c0 = pl.fw.c0; pl.reg_kc = pl.fw.klo + (pl.fj - 1) * T::BK;
+                    if (pl.fj == pl.fw.nchunks) next_fetch_tile<T>(p, block, slice, tid, pl);
                     continue;
                 }
-                const int stage = c + 1 < n ? (chunk_kind<T>(p, w, c + 1) == kDiag ? 2 : 1) : 0;
-                const int load = c + 2 < n ? (chunk_kind<T>(p, w, c + 2) == kEdge ? 2 : 1) : 0;
-                chunk_step<T, false, 0>(smem, p, w, c, c & 1, stage, load, tid, a_lane, b_lane, pl, acc);
-                ++c;
             }
+            chunk_step<T, false, 0>(smem, p, block, slice, g & 1, tid, a_lane, b_lane, pl, acc);
+            ++c;
+            ++g;
         }
 
         // store: full tiles of a general result (or tiles strictly inside the triangle) go out
