@@ -72,8 +72,10 @@ inline Launch choose_launch(const ProductStep &st)
         L.num_tiles = L.tiles_m * L.tiles_n;
     // Pair the longest tile with the shortest, the second longest with the second shortest,
     // ...: for the linear length profile of a triangular operand every workgroup then does
-    // the same amount of work.  Only worth it while the pairs still cover the chip.
-    L.paired = (L.order != kRowMajor && L.num_tiles >= 2 * kComputeUnits) ? 1 : 0;
+    // the same amount of work.  Worth it while the pairs still cover the chip and the tiles are
+    // few: from about four rounds of resident workgroups on, handing out single tiles longest
+    // first balances by itself and keeps more workgroups in flight.
+    L.paired = (L.order != kRowMajor && L.num_tiles >= 2 * kComputeUnits && L.num_tiles < 8 * kComputeUnits) ? 1 : 0;
     L.grid = L.paired ? (L.num_tiles + 1) / 2 : L.num_tiles;
     // Equal tiles (general * general) beyond what the chip holds at once, with a k long enough
     // to matter: launch only as many workgroups as are resident together and let each walk
