@@ -15,10 +15,10 @@ namespace {
 
 using namespace mom;
 
-// 128x128x32 tiles, 4 wavefronts of 64x64: the workhorse.  64x64x16 tiles, 4 wavefronts of
-// 32x32: products with a short side.
-typedef TileConfig<128, 128, 32, 2, 2, 2> Tile128;
-typedef TileConfig<64, 64, 16, 2, 2, 2> Tile64;
+// 128x128 tiles, 4 wavefronts of 64x64, two workgroups per compute unit: the workhorse.
+// 64x64 tiles, 4 wavefronts of 32x32, four or more per compute unit: products with a short side.
+typedef TileConfig<128, 128, kChunk128, 2, 2, 2> Tile128;
+typedef TileConfig<64, 64, kChunk64, 2, 2, 4> Tile64;
 
 template <class T>
 hipError_t launch_product(const ProductBatch &batch, hipStream_t stream)

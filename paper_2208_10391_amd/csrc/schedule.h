@@ -13,6 +13,7 @@ constexpr int kMinChunksPerSlice = 8;
 constexpr int kSplitTargetWorkgroups = 384;
 constexpr int kMinChunksToSplit = 64;      // below this the second launch costs more than it saves
 constexpr int kMaxFused = 4;          // independent products one launch can carry
+constexpr int kChunk128 = 32, kChunk64 = 32;   // k-chunk (BK) of the 128x128 and of the 64x64 tile shape
 
 // Tile shapes the product kernel is instantiated for.
 enum TileShape : int { kTile128 = 0, kTile64 = 1, kNumTileShapes };
@@ -81,14 +82,14 @@ inline Launch choose_launch(const ProductStep &st)
     // to matter: launch only as many workgroups as are resident together and let each walk
     // every grid-th tile, so that the loads of its next tile overlap the MFMAs of this one.
     const int resident = kComputeUnits * (small ? 4 : 2);
-    if (L.order == kRowMajor && L.num_tiles > resident && st.k >= 8 * (small ? 16 : 32)) L.grid = resident;
+    if (L.order == kRowMajor && L.num_tiles > resident && st.k >= 8 * (small ? kChunk64 : kChunk128)) L.grid = resident;
     // Split-K: a general product with few output tiles and a long k leaves most compute units
     // idle; cut k into slices (one workgroup per tile and slice, partial sums to scratch, summed
     // by a second small kernel) until about one and a half workgroups per compute unit exist, keeping at
     // least kMinChunksPerSlice chunks per slice.
     L.split_k = 1;
     L.scratch_bytes = 0;
-    const int bk = small ? 16 : 32;
+    const int bk = small ? kChunk64 : kChunk128;
     const int chunks = (int)((st.k + bk - 1) / bk);
     if (L.order == kRowMajor && L.num_tiles < kComputeUnits && chunks >= kMinChunksToSplit) {
         const int want = (kSplitTargetWorkgroups + L.num_tiles - 1) / L.num_tiles;
