@@ -46,6 +46,30 @@ def test_every_property_pair(pa, pb, n):
     check_against_dense(dims, props, chain(dims, props, 300 + n))
 
 
+@pytest.mark.parametrize("pa", [G, L, U])
+@pytest.mark.parametrize("pb", [G, L, U])
+@pytest.mark.parametrize("n", [128, 256, 384, 640])
+def test_every_property_pair_whole_tiles(pa, pb, n):
+    # nothing ragged: every tile takes 16-byte loads, the long k-ranges run the steady-state
+    # chunk body in pairs, diagonals are masked when staged, and k-ranges of 4, 8, 12, ...
+    # chunks start the pairs at either parity
+    dims, props = [n, n, n], [pa, pb]
+    check_against_dense(dims, props, chain(dims, props, 900 + n))
+
+
+@pytest.mark.parametrize("k", [32, 64, 96, 160, 224, 288])
+def test_short_k_ranges_of_whole_tiles(k):
+    # 1, 2, 3, 5, 7, 9 chunks per tile, several tiles per workgroup never: one launch, 2x3 tiles
+    dims, props = [256, k, 384], [G, G]
+    check_against_dense(dims, props, chain(dims, props, 950 + k))
+
+
+def test_split_k_with_empty_slices():
+    # 400 chunks of 32 over 48 slices of 9: the last slices get no chunk and write zeros
+    dims, props = [512, 12800, 64], [G, G]
+    check_against_dense(dims, props, chain(dims, props, 960))
+
+
 @pytest.mark.parametrize("pa,pb", [(L, L), (U, U), (L, U), (U, L), (L, G), (G, U)])
 def test_zero_fill_flag_and_strided_buffers(pa, pb):
     n = 200
