@@ -193,6 +193,18 @@ def main():
     per = sorted(s.elapsed_time(e) for s, e in events)
 
     value = flop / (ms_per_step * 1e-3) / 1e9
+
+    # what the matrix pipes of this very GPU sustain with no memory traffic (register-only MFMA
+    # loop of the library), best of five launches: reported beside the nominal peak
+    sink = torch.zeros(256, dtype=torch.float32, device="cuda")
+    probe_tflops = 0.0
+    for _ in range(8):
+        ps, pe = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ps.record()
+        probe_flop = mom.mom_probe_mfma_peak(2000, sink)
+        pe.record()
+        torch.cuda.synchronize()
+        probe_tflops = max(probe_tflops, probe_flop / (ps.elapsed_time(pe) * 1e-3) / 1e12)
     if cfg.batch or args.workload == "copy8192":   # HBM-bound: factors in and result out, once
         byts = algorithmic_bytes(cfg)
         ach = byts / (avg_ms * 1e-3) / 1e9
@@ -205,7 +217,8 @@ def main():
         roofline = {"bound": "mfma", "achieved": ach, "peak": F32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": ach / F32_MFMA_PEAK_TFLOPS, "traffic": measured_traffic(args.workload),
                     "kernel": "product_kernel", "launches_per_step": mom.mom_plan_num_products(plan),
-                    "algorithmic_flop_per_step": flop}
+                    "algorithmic_flop_per_step": flop, "measured_peak": probe_tflops,
+                    "frac_of_measured_peak": ach / probe_tflops}
     line = {
         "metric": "useful GFLOP/s per chain eval (f32)",
         "value": value,

@@ -148,6 +148,18 @@ mom_status_t mom_chain_eval_batched(const mom_plan_t *plan, const float *const *
                                     const int64_t *batch_strides, float *d_out,
                                     int64_t out_batch_stride, int32_t batch, void *stream);
 
+/*
+ * Calibration aid for measurements (not a step of the method): enqueue one launch of a
+ * register-only v_mfma_f32_32x32x2_f32 loop, the rate the matrix pipes of this GPU sustain
+ * with no memory traffic at all, which is what the product kernels' f32 throughput (the f32
+ * operands of Sec. 4) is to be read against.  The caller times the launch with events.
+ *   iters   loop trips per wavefront (32 MFMAs each), > 0.
+ *   d_sink  [device] at least 1024 bytes; kept only so that the loop has a visible result, it
+ *           is written if the accumulators reach a value they cannot reach.
+ *   flop    [host] receives the floating-point operations of one launch.
+ */
+mom_status_t mom_probe_mfma_peak(int32_t iters, float *d_sink, double *flop, void *stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char *mom_status_string(mom_status_t status);
 

@@ -23,7 +23,8 @@ STATUS_NAMES = ["MOM_OK", "MOM_ERR_NULL", "MOM_ERR_BAD_N", "MOM_ERR_BAD_DIM", "M
 
 EXPORTS = ["mom_chain_plan", "mom_plan_from_splits", "mom_plan_destroy", "mom_plan_cost_mults",
            "mom_plan_num_products", "mom_plan_result", "mom_plan_string", "mom_plan_splits",
-           "mom_plan_workspace_bytes", "mom_chain_eval", "mom_chain_eval_batched", "mom_status_string"]
+           "mom_plan_workspace_bytes", "mom_chain_eval", "mom_chain_eval_batched", "mom_probe_mfma_peak",
+           "mom_status_string"]
 
 
 class MomError(RuntimeError):
@@ -70,6 +71,8 @@ _lib.mom_chain_eval.argtypes = [ctypes.c_void_p, _vpp, _i64p, ctypes.c_void_p, c
 _lib.mom_chain_eval_batched.restype = ctypes.c_int
 _lib.mom_chain_eval_batched.argtypes = [ctypes.c_void_p, _vpp, _i64p, ctypes.c_void_p, ctypes.c_int64,
                                         ctypes.c_int32, ctypes.c_void_p]
+_lib.mom_probe_mfma_peak.restype = ctypes.c_int
+_lib.mom_probe_mfma_peak.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
 _lib.mom_status_string.restype = ctypes.c_char_p
 _lib.mom_status_string.argtypes = [ctypes.c_int]
 
@@ -310,3 +313,15 @@ def mom_chain_eval_batched(plan: Plan, factors: Sequence[Optional[torch.Tensor]]
                            out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     """One call of the C entry point: marshal (bind_chain_eval_batched) and enqueue."""
     return bind_chain_eval_batched(plan, factors, out)(stream)
+
+
+def mom_probe_mfma_peak(iters: int, sink: torch.Tensor, stream=None) -> float:
+    """Enqueue one launch of the register-only MFMA loop; returns its floating-point operations.
+    `sink`: a CUDA tensor of at least 1024 bytes.  The caller times the launch."""
+    if not sink.is_cuda or sink.numel() * sink.element_size() < 1024:
+        raise ValueError("sink must be a GPU tensor of at least 1024 bytes")
+    flop = ctypes.c_double(0.0)
+    st = _lib.mom_probe_mfma_peak(int(iters), ctypes.c_void_p(sink.data_ptr()), ctypes.byref(flop), _stream_handle(stream))
+    if st != MOM_OK:
+        raise MomError(st, "mom_probe_mfma_peak")
+    return flop.value

@@ -38,6 +38,31 @@ hipError_t launch_product(const ProductBatch &batch, hipStream_t stream)
     return hipGetLastError();
 }
 
+// Register-only MFMA loop: 4 independent accumulator blocks per wavefront keep the pipe full.
+constexpr int kProbeWorkgroups = 2 * kComputeUnits, kProbeBlocks = 4, kProbeUnroll = 8;
+
+__global__ __launch_bounds__(256) void probe_mfma_kernel(float *sink, int iters, float a0, float b0)
+{
+    f32x16 acc[kProbeBlocks];
+#pragma unroll
+    for (int i = 0; i < kProbeBlocks; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
+    const float a = a0 + threadIdx.x, b = b0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int r = 0; r < kProbeUnroll; ++r)
+#pragma unroll
+            for (int i = 0; i < kProbeBlocks; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[i], 0, 0, 0);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < kProbeBlocks; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s += acc[i][v];
+    if (s == 12345.0f) sink[threadIdx.x] = s;       // sums of products of 1.x and 2 never land here
+}
+
 inline bool aligned16(const void *ptr, int64_t ld) { return (reinterpret_cast<uintptr_t>(ptr) & 15) == 0 && (ld & 3) == 0; }
 
 inline int elementwise_grid(int64_t total) { return (int)std::min<int64_t>((total + 255) / 256, 4096); }
@@ -176,4 +201,16 @@ extern "C" mom_status_t mom_chain_eval_batched(const mom_plan_t *plan, const flo
     if (batch == 0) return MOM_OK;
     return launch_batched(plan, d_factor_bases, batch_strides, d_out, out_batch_stride, batch,
                           static_cast<hipStream_t>(stream_)) == hipSuccess ? MOM_OK : MOM_ERR_HIP;
+}
+
+extern "C" mom_status_t mom_probe_mfma_peak(int32_t iters, float *d_sink, double *flop, void *stream_)
+{
+    if (!d_sink || !flop) return MOM_ERR_NULL;
+    if (iters <= 0) return MOM_ERR_BAD_N;
+    hipLaunchKernelGGL(probe_mfma_kernel, dim3(kProbeWorkgroups), dim3(256), 0, static_cast<hipStream_t>(stream_), d_sink,
+                       iters, 1.0f, 2.0f);
+    if (hipGetLastError() != hipSuccess) return MOM_ERR_HIP;
+    // 32x32x2: 2 * 32 * 32 * 2 = 4096 floating-point operations per MFMA
+    *flop = (double)kProbeWorkgroups * 4 /* wavefronts */ * (double)iters * kProbeUnroll * kProbeBlocks * 4096.0;
+    return MOM_OK;
 }

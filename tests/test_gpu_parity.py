@@ -208,3 +208,13 @@ def test_bound_call_can_be_enqueued_again():
         for b in range(batch):
             w = oracle.eval_dense(bdims, bprops, [f[b].numpy() for f in bhost])
             assert rel_fro(got[b], w) <= TOL
+
+
+def test_mfma_probe_runs_and_counts_its_flop():
+    sink = torch.zeros(256, device="cuda")
+    flop = mom.mom_probe_mfma_peak(10, sink)
+    torch.cuda.synchronize()
+    assert flop == 512 * 4 * 10 * 32 * 4096.0       # workgroups x wavefronts x trips x MFMAs x 2*32*32*2
+    assert float(sink.abs().sum()) == 0.0           # the sink is never written
+    with pytest.raises(mom.MomError):
+        mom.mom_probe_mfma_peak(0, sink)
