@@ -32,13 +32,13 @@ HBM_PEAK_GBS = 8000.0
 # gave then, and any other digest turns the field into null.
 # (scale factors of that calibration: FETCH_SIZE x 1.9997, WRITE_SIZE x 1.0000; all launches of one step summed)
 MEASURED_TRAFFIC = {
-    "trmm4096": {"fetch_bytes": 449427665, "write_bytes": 67108864, "sources": "b67311fb9a136d6b"},
-    "general5": {"fetch_bytes": 123002959, "write_bytes": 80347136, "sources": "b67311fb9a136d6b"},
-    "mixed5": {"fetch_bytes": 3691833985, "write_bytes": 100663296, "sources": "b67311fb9a136d6b"},
-    "mixed5_tri_intermediate": {"fetch_bytes": 7894462748, "write_bytes": 201457664, "sources": "b67311fb9a136d6b"},
-    "mixed5_left_to_right": {"fetch_bytes": 15285528933, "write_bytes": 436338688, "sources": "b67311fb9a136d6b"},
-    "batched32": {"fetch_bytes": 50356366, "write_bytes": 16777216, "sources": "b67311fb9a136d6b"},
-    "copy8192": {"fetch_bytes": 268435456, "write_bytes": 268435456, "sources": "b67311fb9a136d6b"},
+    "trmm4096": {"fetch_bytes": 449938753, "write_bytes": 67108864, "sources": "660cfbbdd0954a82"},
+    "general5": {"fetch_bytes": 122962986, "write_bytes": 80347136, "sources": "660cfbbdd0954a82"},
+    "mixed5": {"fetch_bytes": 3697877577, "write_bytes": 100663296, "sources": "660cfbbdd0954a82"},
+    "mixed5_tri_intermediate": {"fetch_bytes": 7892763813, "write_bytes": 201457664, "sources": "660cfbbdd0954a82"},
+    "mixed5_left_to_right": {"fetch_bytes": 15288740743, "write_bytes": 436338688, "sources": "660cfbbdd0954a82"},
+    "batched32": {"fetch_bytes": 50368485, "write_bytes": 16777216, "sources": "660cfbbdd0954a82"},
+    "copy8192": {"fetch_bytes": 268435456, "write_bytes": 268435456, "sources": "660cfbbdd0954a82"},
 }
 
 # forced parenthesisations of the mixed-property chain (the planner's own tree never forms
