@@ -218,3 +218,35 @@ def test_mfma_probe_runs_and_counts_its_flop():
     assert float(sink.abs().sum()) == 0.0           # the sink is never written
     with pytest.raises(mom.MomError):
         mom.mom_probe_mfma_peak(0, sink)
+
+
+def test_evaluation_can_be_captured_in_a_graph_and_replayed():
+    """The library only enqueues kernels (no allocation, no memset, no synchronisation), so an
+    evaluation records into a HIP graph; every replay, with eager work in between, must
+    reproduce the eager result bit for bit (same kernels, same order of summation)."""
+    dims, props = [96, 1500, 80, 1200, 72], [G, G, G, G]          # fused level + split-K + slice sum
+    host = chain(dims, props, 830)
+    plan = mom.mom_plan_from_splits(dims, props, [1, 0, 2])
+    dev = upload(host, props)
+    call = mom.bind_chain_eval(plan, dev)
+    eager = call().clone()                                         # also the warm-up before capture
+    torch.cuda.synchronize()
+    want = oracle.eval_dense(dims, props, [f.numpy() for f in host])
+    assert rel_fro(eager.cpu().numpy(), want) <= TOL
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        call()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            call()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(4):
+        call.out.fill_(float("nan"))
+        other = (dev[0] @ dev[0].t()).sum()                        # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(call.out, eager), "replay %d differs" % rep
+        assert torch.isfinite(other)
