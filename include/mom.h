@@ -82,7 +82,7 @@ typedef struct mom_plan mom_plan_t;   /* opaque */
 mom_status_t mom_chain_plan(const int64_t *dims, const int32_t *props, int32_t n, mom_plan_t **out);
 
 /*
- * Plan with a forced parenthesisation, e.g. the "initial parenthesization" of Sec. 4.
+ * Plan with a forced parenthesisation, e.g. the left-to-right tree Sec. 4 starts from.
  *   preorder_splits [host]: one entry per binary product (survivors-1 entries; survivors =
  *   factors that are not Identity), in preorder: a node's split, then its left subtree's
  *   entries, then its right subtree's.  A split is the ORIGINAL index of the last factor of

@@ -48,7 +48,7 @@ static int structurally_nonzero(int prop, int64_t i, int64_t j)
 
 /* Number of scalar products X[i][t]*Y[t][j] in which neither operand is a
  * structural zero, counted one by one.  This is the planner's cost unit
- * ("number of scalar multiplications", Sec. 2 Transformations) written as
+ * (the multiplication count of Sec. 2, Transformations) written as
  * its definition; the closed forms below are checked against it.           */
 uint64_t oracle_count_mults(int64_t m, int64_t k, int64_t n, int32_t pX, int32_t pY)
 {
