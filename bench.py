@@ -32,12 +32,12 @@ HBM_PEAK_GBS = 8000.0
 # gave then, and any other digest turns the field into null.
 # (scale factors of that calibration: FETCH_SIZE x 1.9997, WRITE_SIZE x 1.0000; all launches of one step summed)
 MEASURED_TRAFFIC = {
-    "trmm4096": {"fetch_bytes": 449938753, "write_bytes": 67108864, "sources": "660cfbbdd0954a82"},
-    "general5": {"fetch_bytes": 122962986, "write_bytes": 80347136, "sources": "660cfbbdd0954a82"},
-    "mixed5": {"fetch_bytes": 3697877577, "write_bytes": 100663296, "sources": "660cfbbdd0954a82"},
-    "mixed5_tri_intermediate": {"fetch_bytes": 7892763813, "write_bytes": 201457664, "sources": "660cfbbdd0954a82"},
-    "mixed5_left_to_right": {"fetch_bytes": 15288740743, "write_bytes": 436338688, "sources": "660cfbbdd0954a82"},
-    "batched32": {"fetch_bytes": 50368485, "write_bytes": 16777216, "sources": "660cfbbdd0954a82"},
+    "trmm4096": {"fetch_bytes": 450008201, "write_bytes": 67108864, "sources": "660cfbbdd0954a82"},
+    "general5": {"fetch_bytes": 122960424, "write_bytes": 80347136, "sources": "660cfbbdd0954a82"},
+    "mixed5": {"fetch_bytes": 3694882991, "write_bytes": 100663296, "sources": "660cfbbdd0954a82"},
+    "mixed5_tri_intermediate": {"fetch_bytes": 7892135877, "write_bytes": 201457664, "sources": "660cfbbdd0954a82"},
+    "mixed5_left_to_right": {"fetch_bytes": 15287317696, "write_bytes": 436338688, "sources": "660cfbbdd0954a82"},
+    "batched32": {"fetch_bytes": 50368480, "write_bytes": 16777216, "sources": "660cfbbdd0954a82"},
     "copy8192": {"fetch_bytes": 268435456, "write_bytes": 268435456, "sources": "660cfbbdd0954a82"},
 }
 
@@ -70,11 +70,11 @@ def kernel_sources_digest():
 
 
 def measured_traffic(workload):
+    """(bytes per step, {fetch, write}) or (None, None) when the kernels have changed since."""
     m = MEASURED_TRAFFIC.get(workload)
     if not m or m["sources"] != kernel_sources_digest():
-        return None
-    return {"fetch_bytes": m["fetch_bytes"], "write_bytes": m["write_bytes"],
-            "bytes": m["fetch_bytes"] + m["write_bytes"]}
+        return None, None
+    return m["fetch_bytes"] + m["write_bytes"], {"fetch_bytes": m["fetch_bytes"], "write_bytes": m["write_bytes"]}
 
 
 def useful_flop(name, plan, cfg):
@@ -193,6 +193,7 @@ def main():
     per = sorted(s.elapsed_time(e) for s, e in events)
 
     value = flop / (ms_per_step * 1e-3) / 1e9
+    traffic, traffic_detail = measured_traffic(args.workload)
 
     # what the matrix pipes of this very GPU sustain with no memory traffic (register-only MFMA
     # loop of the library), best of five launches: reported beside the nominal peak
@@ -209,13 +210,13 @@ def main():
         byts = algorithmic_bytes(cfg)
         ach = byts / (avg_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": ach / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload),
+                    "frac": ach / HBM_PEAK_GBS, "traffic": traffic, "traffic_detail": traffic_detail,
                     "kernel": "batched_chain3_right_kernel" if cfg.batch else "copy_structure_kernel",
                     "algorithmic_bytes_per_launch": byts}
     else:
         ach = flop / (avg_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": ach, "peak": F32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": ach / F32_MFMA_PEAK_TFLOPS, "traffic": measured_traffic(args.workload),
+                    "frac": ach / F32_MFMA_PEAK_TFLOPS, "traffic": traffic, "traffic_detail": traffic_detail,
                     "kernel": "product_kernel", "launches_per_step": mom.mom_plan_num_products(plan),
                     "algorithmic_flop_per_step": flop, "measured_peak": probe_tflops,
                     "frac_of_measured_peak": ach / probe_tflops}
