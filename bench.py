@@ -32,13 +32,13 @@ HBM_PEAK_GBS = 8000.0
 # gave then, and any other digest turns the field into null.
 # (scale factors of that calibration: FETCH_SIZE x 1.9997, WRITE_SIZE x 1.0000; all launches of one step summed)
 MEASURED_TRAFFIC = {
-    "trmm4096": {"fetch_bytes": 450008201, "write_bytes": 67108864, "sources": "660cfbbdd0954a82"},
-    "general5": {"fetch_bytes": 122960424, "write_bytes": 80347136, "sources": "660cfbbdd0954a82"},
-    "mixed5": {"fetch_bytes": 3694882991, "write_bytes": 100663296, "sources": "660cfbbdd0954a82"},
-    "mixed5_tri_intermediate": {"fetch_bytes": 7892135877, "write_bytes": 201457664, "sources": "660cfbbdd0954a82"},
-    "mixed5_left_to_right": {"fetch_bytes": 15287317696, "write_bytes": 436338688, "sources": "660cfbbdd0954a82"},
-    "batched32": {"fetch_bytes": 50368480, "write_bytes": 16777216, "sources": "660cfbbdd0954a82"},
-    "copy8192": {"fetch_bytes": 268435456, "write_bytes": 268435456, "sources": "660cfbbdd0954a82"},
+    "trmm4096": {"fetch_bytes": 450087582, "write_bytes": 67108864, "sources": "d2ecf14ff39747cb"},
+    "general5": {"fetch_bytes": 122961840, "write_bytes": 80347136, "sources": "d2ecf14ff39747cb"},
+    "mixed5": {"fetch_bytes": 3694037165, "write_bytes": 100663296, "sources": "d2ecf14ff39747cb"},
+    "mixed5_tri_intermediate": {"fetch_bytes": 7892507115, "write_bytes": 201457664, "sources": "d2ecf14ff39747cb"},
+    "mixed5_left_to_right": {"fetch_bytes": 15278575356, "write_bytes": 436338688, "sources": "d2ecf14ff39747cb"},
+    "batched32": {"fetch_bytes": 50368476, "write_bytes": 16777216, "sources": "d2ecf14ff39747cb"},
+    "copy8192": {"fetch_bytes": 268435456, "write_bytes": 268435456, "sources": "d2ecf14ff39747cb"},
 }
 
 # forced parenthesisations of the mixed-property chain (the planner's own tree never forms

@@ -9,6 +9,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <vector>
 
 namespace {
@@ -20,18 +21,22 @@ using namespace mom;
 typedef TileConfig<128, 128, kChunk128, 2, 2, 2> Tile128;
 typedef TileConfig<64, 64, kChunk64, 2, 2, 4> Tile64;
 
+constexpr int kMaxDevices = 64;       // devices whose kernel attributes are remembered
+
 template <class T>
 hipError_t launch_product(const ProductBatch &batch, hipStream_t stream)
 {
-    static bool configured[64] = {};
+    // the tile's LDS footprint exceeds the default dynamic limit: raise it once per device (a
+    // second thread doing the same at the same moment is harmless)
+    static std::atomic<bool> configured[kMaxDevices];
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
-    if (dev >= 0 && dev < 64 && !configured[dev]) {
+    if (dev < 0 || dev >= kMaxDevices || !configured[dev].load(std::memory_order_acquire)) {
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(&product_kernel<T>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
         if (e != hipSuccess) return e;
-        configured[dev] = true;
+        if (dev >= 0 && dev < kMaxDevices) configured[dev].store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL(product_kernel<T>, dim3(batch.block_end[batch.count - 1]), dim3(T::NT), T::LDS_BYTES, stream,
                        batch);
