@@ -48,7 +48,7 @@ typedef enum {
     MOM_OK = 0,
     MOM_ERR_NULL,              /* a required pointer is NULL */
     MOM_ERR_BAD_N,             /* n <= 0 or above MOM_MAX_FACTORS, batch < 0 */
-    MOM_ERR_BAD_DIM,           /* a dimension is <= 0 or above 2^31-1 */
+    MOM_ERR_BAD_DIM,           /* a dimension is <= 0 or above MOM_MAX_DIM */
     MOM_ERR_BAD_PROP,          /* a property is not one of mom_prop_t */
     MOM_ERR_NOT_SQUARE,        /* a lowerTri / upperTri / Identity factor is not square */
     MOM_ERR_OVERFLOW,          /* a multiplication count does not fit in 64 bits */
@@ -61,6 +61,7 @@ typedef enum {
 } mom_status_t;
 
 #define MOM_MAX_FACTORS 1024
+#define MOM_MAX_DIM 2147483392          /* 2^31 - 256: tile arithmetic in the kernels stays in 32 bits */
 
 /* mom_chain_eval flag: also write zeros into the other half of a triangular RESULT, which
  * restores the fully materialised buffer of the paper's bufferization (Sec. 2).  Without it

@@ -49,7 +49,7 @@ mom_status_t validate(const int64_t *dims, const int32_t *props, int32_t n)
     if (!dims || !props) return MOM_ERR_NULL;
     if (n <= 0 || n > MOM_MAX_FACTORS) return MOM_ERR_BAD_N;
     for (int i = 0; i <= n; ++i)
-        if (dims[i] <= 0 || dims[i] > (int64_t)std::numeric_limits<int32_t>::max()) return MOM_ERR_BAD_DIM;
+        if (dims[i] <= 0 || dims[i] > (int64_t)MOM_MAX_DIM) return MOM_ERR_BAD_DIM;
     for (int i = 0; i < n; ++i) {
         if (props[i] < kGeneral || props[i] > kIdentity) return MOM_ERR_BAD_PROP;
         if (props[i] != kGeneral && dims[i] != dims[i + 1]) return MOM_ERR_NOT_SQUARE;
@@ -376,7 +376,7 @@ const char *mom_status_string(mom_status_t status)
     case MOM_OK: return "ok";
     case MOM_ERR_NULL: return "a required pointer is NULL";
     case MOM_ERR_BAD_N: return "number of factors (or batch) out of range";
-    case MOM_ERR_BAD_DIM: return "a dimension is not in 1..2^31-1";
+    case MOM_ERR_BAD_DIM: return "a dimension is not in 1..2^31-256";
     case MOM_ERR_BAD_PROP: return "unknown matrix property";
     case MOM_ERR_NOT_SQUARE: return "a triangular or Identity factor is not square";
     case MOM_ERR_OVERFLOW: return "multiplication count does not fit in 64 bits";

@@ -124,6 +124,8 @@ def test_error_paths():
     assert status_of(mom.mom_chain_plan, [4, 0], [G]) == code["MOM_ERR_BAD_DIM"]
     assert status_of(mom.mom_chain_plan, [4, -3], [G]) == code["MOM_ERR_BAD_DIM"]
     assert status_of(mom.mom_chain_plan, [4, 2 ** 31], [G]) == code["MOM_ERR_BAD_DIM"]
+    assert status_of(mom.mom_chain_plan, [4, 2 ** 31 - 255], [G]) == code["MOM_ERR_BAD_DIM"]
+    assert mom.mom_chain_plan([4, 2 ** 31 - 256], [G]).cost_mults == 0       # the largest dimension allowed
     assert status_of(mom.mom_chain_plan, [4, 4], [7]) == code["MOM_ERR_BAD_PROP"]
     for p in (L, U, I):
         assert status_of(mom.mom_chain_plan, [4, 5], [p]) == code["MOM_ERR_NOT_SQUARE"]
@@ -131,8 +133,8 @@ def test_error_paths():
     assert status_of(mom.mom_plan_from_splits, [4, 4, 4, 4], [G, G, G], [0, 0]) == code["MOM_ERR_BAD_SPLITS"]
     assert status_of(mom.mom_plan_from_splits, [4, 4, 4, 4], [G, I, G], [1]) == code["MOM_ERR_BAD_SPLITS"]
     assert status_of(mom.mom_plan_from_splits, [4, 4, 4, 4], [G, G, G], [0]) == code["MOM_ERR_BAD_SPLITS"]
-    # 2^31-1 cubed, three times over, does not fit in 64 bits
-    big = 2 ** 31 - 1
+    # the largest dimension cubed, three times over, does not fit in 64 bits
+    big = 2 ** 31 - 256
     assert status_of(mom.mom_chain_plan, [big] * 5, [G] * 4) == code["MOM_ERR_OVERFLOW"]
     lib = mom.library()
     assert lib.mom_chain_plan(None, None, 1, None) == code["MOM_ERR_NULL"]
