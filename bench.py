@@ -34,6 +34,7 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_TRAFFIC = {
     "trmm4096": {"fetch_bytes": 450087582, "write_bytes": 67108864, "sources": "ae1f6e39e3348a47"},
     "general5": {"fetch_bytes": 122961840, "write_bytes": 80347136, "sources": "ae1f6e39e3348a47"},
+    "general5_left_to_right": {"fetch_bytes": 1840669840, "write_bytes": 478150656, "sources": "ae1f6e39e3348a47"},
     "mixed5": {"fetch_bytes": 3694037165, "write_bytes": 100663296, "sources": "ae1f6e39e3348a47"},
     "mixed5_tri_intermediate": {"fetch_bytes": 7892507115, "write_bytes": 201457664, "sources": "ae1f6e39e3348a47"},
     "mixed5_left_to_right": {"fetch_bytes": 15278575356, "write_bytes": 436338688, "sources": "ae1f6e39e3348a47"},
