@@ -397,40 +397,14 @@ __device__ __forceinline__ void chunk_step(float *smem, const ProductParams &p, 
     const float *As = smem + s * T::A_STAGE, *Bs = smem + 2 * T::A_STAGE + s * T::B_STAGE;
     float *An = smem + (s ^ 1) * T::A_STAGE, *Bn = smem + 2 * T::A_STAGE + (s ^ 1) * T::B_STAGE;
 
-    read_fragments<T>(As, Bs, a_lane, b_lane, 1, pl.f1);
-    const bool staged = HOT ? true : pl.in_regs;
-    if (HOT) {
-        stage_to_lds<T>(An, Bn, tid, pl.ra, pl.rb);
-        const int64_t b_step = (int64_t)T::BK * p.ldb;
+    // The chunk on its way to LDS is staged, and the next loads are issued, in the group before
+    // the barrier rather than in the first one: the stores of a tile that has just ended (and
+    // that an in-order memory counter makes the staging wait for) then have the first groups'
+    // MFMAs to drain under.
+    constexpr int MOVE = NKG >= 2 ? NKG - 2 : 0;
+    bool staged = HOT;
 #pragma unroll
-        for (int q = 0; q < T::A_F4; ++q) { pl.ra[q] = *reinterpret_cast<const f32x4 *>(pl.a_src[q]); pl.a_src[q] += T::BK; }
-#pragma unroll
-        for (int q = 0; q < T::B_F4; ++q) { pl.rb[q] = *reinterpret_cast<const f32x4 *>(pl.b_src[q]); pl.b_src[q] += b_step; }
-    } else {
-        if (pl.in_regs) {
-            if (pl.reg_kind == kDiag) mask_registers<T>(p, pl.reg_r0, pl.reg_c0, pl.reg_kc, tid, pl.ra, pl.rb);
-            stage_to_lds<T>(An, Bn, tid, pl.ra, pl.rb);
-        }
-        fetch_chunk<T>(p, block, slice, tid, pl);
-    }
-    mfma_group<T>(pl.f0, acc);
-    if (HOT) {
-        __builtin_amdgcn_sched_group_barrier(kSchedLdsRead, NREAD, 0);
-#pragma unroll
-        for (int i = 0; i < NMOVE; ++i) {
-            __builtin_amdgcn_sched_group_barrier(kSchedMfma, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(kSchedLdsWrite, 1, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < NMOVE; ++i) {
-            __builtin_amdgcn_sched_group_barrier(kSchedMfma, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(kSchedVmemRead, 1, 0);
-        }
-    } else {
-        __builtin_amdgcn_sched_barrier(0);
-    }
-#pragma unroll
-    for (int kg = 1; kg < NKG; ++kg) {
+    for (int kg = 0; kg < NKG; ++kg) {
         Fragments<T> &now = (kg & 1) ? pl.f1 : pl.f0;
         Fragments<T> &next = (kg & 1) ? pl.f0 : pl.f1;
         if (kg + 1 < NKG) {
@@ -439,8 +413,39 @@ __device__ __forceinline__ void chunk_step(float *smem, const ProductParams &p, 
             __syncthreads();
             if (staged) read_fragments<T>(An, Bn, a_lane, b_lane, 0, next);
         }
+        if (kg == MOVE) {
+            if (HOT) {
+                stage_to_lds<T>(An, Bn, tid, pl.ra, pl.rb);
+                const int64_t b_step = (int64_t)T::BK * p.ldb;
+#pragma unroll
+                for (int q = 0; q < T::A_F4; ++q) { pl.ra[q] = *reinterpret_cast<const f32x4 *>(pl.a_src[q]); pl.a_src[q] += T::BK; }
+#pragma unroll
+                for (int q = 0; q < T::B_F4; ++q) { pl.rb[q] = *reinterpret_cast<const f32x4 *>(pl.b_src[q]); pl.b_src[q] += b_step; }
+            } else {
+                staged = pl.in_regs;
+                if (pl.in_regs) {
+                    if (pl.reg_kind == kDiag) mask_registers<T>(p, pl.reg_r0, pl.reg_c0, pl.reg_kc, tid, pl.ra, pl.rb);
+                    stage_to_lds<T>(An, Bn, tid, pl.ra, pl.rb);
+                }
+                fetch_chunk<T>(p, block, slice, tid, pl);
+            }
+        }
         mfma_group<T>(now, acc);
-        if (HOT) {
+        if (!HOT) {
+            __builtin_amdgcn_sched_barrier(0);
+        } else if (kg == MOVE) {
+            __builtin_amdgcn_sched_group_barrier(kSchedLdsRead, NREAD, 0);
+#pragma unroll
+            for (int i = 0; i < NMOVE; ++i) {
+                __builtin_amdgcn_sched_group_barrier(kSchedMfma, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(kSchedLdsWrite, 1, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < NMOVE; ++i) {
+                __builtin_amdgcn_sched_group_barrier(kSchedMfma, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(kSchedVmemRead, 1, 0);
+            }
+        } else {
             constexpr int PER = NMFMA / NREAD > 0 ? NMFMA / NREAD : 1;
 #pragma unroll
             for (int i = 0; i < NREAD; ++i) {
@@ -448,8 +453,6 @@ __device__ __forceinline__ void chunk_step(float *smem, const ProductParams &p, 
                 __builtin_amdgcn_sched_group_barrier(kSchedMfma, PER, 0);
             }
             if (NMFMA > PER * NREAD) __builtin_amdgcn_sched_group_barrier(kSchedMfma, NMFMA - PER * NREAD, 0);
-        } else {
-            __builtin_amdgcn_sched_barrier(0);
         }
     }
 }
