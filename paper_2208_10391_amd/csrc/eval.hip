@@ -164,6 +164,7 @@ extern "C" mom_status_t mom_chain_eval(const mom_plan_t *plan, const float *cons
                     r.slices = L.split_k; r.M = p.M; r.N = p.N;
                     reduce_quads = std::max<int64_t>(reduce_quads, (st.m * st.n + 3) / 4);
                 }
+                p.c_vec = aligned16(p.C, p.ldc);
                 const int64_t blocks = (int64_t)(batch.count ? batch.block_end[batch.count - 1] : 0) + (int64_t)L.grid * L.split_k;
                 if (blocks > 0x7fffffff) return MOM_ERR_UNSUPPORTED;
                 batch.block_end[batch.count++] = (int)blocks;

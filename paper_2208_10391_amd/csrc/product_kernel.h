@@ -10,8 +10,11 @@
 //
 // Data path: global -> registers (16-byte loads, two chunks ahead) -> LDS (two stages, one
 // barrier per chunk) -> MFMA operands (read one group of 8 k-values ahead).
-// v_mfma_f32_32x32x2_f32: lane l supplies A[i = l%32][k = l/32] and B[k = l/32][j = l%32];
-// accumulator register v of lane l holds C[8*(v/4) + 4*(l/32) + v%4][l%32].
+// v_mfma_f32_32x32x2_f32 computes D = X * Y + D with lane l supplying X[i = l%32][k = l/32] and
+// Y[k = l/32][j = l%32]; register v of lane l holds D[8*(v/4) + 4*(l/32) + v%4][l%32].  The kernel
+// feeds it the transposed problem, X = B^T and Y = A^T, so that D = C^T: a lane then owns one row
+// of the 32x32 block of C and four consecutive registers are four consecutive columns of it, which
+// go out as one 16-byte store.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -34,6 +37,7 @@ struct ProductParams {
     int tiles_m, tiles_n, num_tiles, order, paired;
     int grid;              // workgroups per k-slice
     int a_vec, b_vec;      // 16-byte loads are legal for A / B (base and row stride aligned)
+    int c_vec;             // 16-byte stores are legal for C
     int split_k;
 };
 
@@ -187,7 +191,8 @@ __device__ __forceinline__ void read_fragments(const float *As, const float *Bs,
 }
 
 // The 4 * FM * FN MFMAs of one group of 8 k-values: step e multiplies k = 4*half + e (the
-// order of summation over k is free).
+// order of summation over k is free).  The B operand goes first: the accumulators hold the
+// transposed block (see the head of this file).
 template <class T>
 __device__ __forceinline__ void mfma_group(const Fragments<T> &f, f32x16 (&acc)[T::FM][T::FN])
 {
@@ -197,7 +202,7 @@ __device__ __forceinline__ void mfma_group(const Fragments<T> &f, f32x16 (&acc)[
         for (int bi = 0; bi < T::FM; ++bi)
 #pragma unroll
             for (int bj = 0; bj < T::FN; ++bj)
-                acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[bi][e], f.b[bj][e], acc[bi][bj], 0, 0, 0);
+                acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.b[bj][e], f.a[bi][e], acc[bi][bj], 0, 0, 0);
 }
 
 // What one output tile needs: where it sits, its k-range in chunks, and which chunks are
@@ -526,8 +531,10 @@ __global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const Pro
             ++g;
         }
 
-        // store: full tiles of a general result (or tiles strictly inside the triangle) go out
-        // unchecked; edge and diagonal tiles element by element, the triangle only
+        // store: register v of lane (l32, half) is C[row l32][column 8*(v/4) + 4*half + v%4] of its
+        // 32x32 block.  Full tiles of a general result (or tiles strictly inside the triangle) go out
+        // unchecked, 16 bytes at a time when the result allows; edge and diagonal tiles element by
+        // element, the triangle only
         float *const C = p.C + (int64_t)slice * p.slice_stride;
         bool plain = w.r0 + T::BM <= p.M && w.c0 + T::BN <= p.N;
         if (p.pc == kLower) plain = plain && w.c0 + T::BN - 1 <= w.r0;
@@ -537,11 +544,18 @@ __global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const Pro
 #pragma unroll
             for (int bj = 0; bj < T::FN; ++bj)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int gi = w.r0 + wr0 + bi * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-                    const int gj = w.c0 + wc0 + bj * 32 + l32;
-                    if (plain || (gi < p.M && gj < p.N && in_structure(p.pc, gi, gj)))
-                        C[(int64_t)gi * p.ldc + gj] = acc[bi][bj][v];
+                for (int q = 0; q < 4; ++q) {
+                    const int gi = w.r0 + wr0 + bi * 32 + l32;
+                    const int gj = w.c0 + wc0 + bj * 32 + 8 * q + 4 * half;
+                    float *dst = C + (int64_t)gi * p.ldc + gj;
+                    if (plain && p.c_vec) {
+                        const f32x4 v = {acc[bi][bj][4 * q], acc[bi][bj][4 * q + 1], acc[bi][bj][4 * q + 2], acc[bi][bj][4 * q + 3]};
+                        *reinterpret_cast<f32x4 *>(dst) = v;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (plain || (gi < p.M && gj + e < p.N && in_structure(p.pc, gi, gj + e))) dst[e] = acc[bi][bj][4 * q + e];
+                    }
                 }
     }
 }
