@@ -32,14 +32,14 @@ HBM_PEAK_GBS = 8000.0
 # gave then, and any other digest turns the field into null.
 # (scale factors of that calibration: FETCH_SIZE x 1.9997, WRITE_SIZE x 1.0000; all launches of one step summed)
 MEASURED_TRAFFIC = {
-    "trmm4096": {"fetch_bytes": 450087582, "write_bytes": 67108864, "sources": "ae1f6e39e3348a47"},
-    "general5": {"fetch_bytes": 122961840, "write_bytes": 80347136, "sources": "ae1f6e39e3348a47"},
-    "general5_left_to_right": {"fetch_bytes": 1840669840, "write_bytes": 478150656, "sources": "ae1f6e39e3348a47"},
-    "mixed5": {"fetch_bytes": 3694037165, "write_bytes": 100663296, "sources": "ae1f6e39e3348a47"},
-    "mixed5_tri_intermediate": {"fetch_bytes": 7892507115, "write_bytes": 201457664, "sources": "ae1f6e39e3348a47"},
-    "mixed5_left_to_right": {"fetch_bytes": 15278575356, "write_bytes": 436338688, "sources": "ae1f6e39e3348a47"},
-    "batched32": {"fetch_bytes": 50368476, "write_bytes": 16777216, "sources": "ae1f6e39e3348a47"},
-    "copy8192": {"fetch_bytes": 268435456, "write_bytes": 268435456, "sources": "ae1f6e39e3348a47"},
+    "trmm4096": {"fetch_bytes": 450819942, "write_bytes": 67108951, "sources": "2fd7e2e931156b0d"},
+    "general5": {"fetch_bytes": 123418004, "write_bytes": 86186287, "sources": "2fd7e2e931156b0d"},
+    "general5_left_to_right": {"fetch_bytes": 1878765529, "write_bytes": 525719436, "sources": "2fd7e2e931156b0d"},
+    "mixed5": {"fetch_bytes": 3707730910, "write_bytes": 100898919, "sources": "2fd7e2e931156b0d"},
+    "mixed5_tri_intermediate": {"fetch_bytes": 7937225703, "write_bytes": 201610467, "sources": "2fd7e2e931156b0d"},
+    "mixed5_left_to_right": {"fetch_bytes": 15428785791, "write_bytes": 436576098, "sources": "2fd7e2e931156b0d"},
+    "batched32": {"fetch_bytes": 50368482, "write_bytes": 16777216, "sources": "2fd7e2e931156b0d"},
+    "copy8192": {"fetch_bytes": 268435456, "write_bytes": 268435456, "sources": "2fd7e2e931156b0d"},
 }
 
 # forced parenthesisations of the mixed-property chain (the planner's own tree never forms
