@@ -437,7 +437,7 @@ __device__ __forceinline__ void chunk_step(float *smem, const ProductParams &p, 
         }
         mfma_group<T>(now, acc);
         if (!HOT) {
-            __builtin_amdgcn_sched_barrier(0);
+            // the general body is left to the compiler's own scheduling
         } else if (kg == MOVE) {
             __builtin_amdgcn_sched_group_barrier(kSchedLdsRead, NREAD, 0);
 #pragma unroll
