@@ -32,14 +32,14 @@ HBM_PEAK_GBS = 8000.0
 # gave then, and any other digest turns the field into null.
 # (scale factors of that calibration: FETCH_SIZE x 1.9997, WRITE_SIZE x 1.0000; all launches of one step summed)
 MEASURED_TRAFFIC = {
-    "trmm4096": {"fetch_bytes": 450819942, "write_bytes": 67108951, "sources": "2fd7e2e931156b0d"},
-    "general5": {"fetch_bytes": 123418004, "write_bytes": 86186287, "sources": "2fd7e2e931156b0d"},
-    "general5_left_to_right": {"fetch_bytes": 1878765529, "write_bytes": 525719436, "sources": "2fd7e2e931156b0d"},
-    "mixed5": {"fetch_bytes": 3707730910, "write_bytes": 100898919, "sources": "2fd7e2e931156b0d"},
-    "mixed5_tri_intermediate": {"fetch_bytes": 7937225703, "write_bytes": 201610467, "sources": "2fd7e2e931156b0d"},
-    "mixed5_left_to_right": {"fetch_bytes": 15428785791, "write_bytes": 436576098, "sources": "2fd7e2e931156b0d"},
-    "batched32": {"fetch_bytes": 50368482, "write_bytes": 16777216, "sources": "2fd7e2e931156b0d"},
-    "copy8192": {"fetch_bytes": 268435456, "write_bytes": 268435456, "sources": "2fd7e2e931156b0d"},
+    "trmm4096": {"fetch_bytes": 449996754, "write_bytes": 67108884, "sources": "96752c54a085d577"},
+    "general5": {"fetch_bytes": 123315758, "write_bytes": 87158912, "sources": "96752c54a085d577"},
+    "general5_left_to_right": {"fetch_bytes": 1876441223, "write_bytes": 527158985, "sources": "96752c54a085d577"},
+    "mixed5": {"fetch_bytes": 3701566704, "write_bytes": 100968522, "sources": "96752c54a085d577"},
+    "mixed5_tri_intermediate": {"fetch_bytes": 7936007970, "write_bytes": 201653276, "sources": "96752c54a085d577"},
+    "mixed5_left_to_right": {"fetch_bytes": 15400234152, "write_bytes": 436568715, "sources": "96752c54a085d577"},
+    "batched32": {"fetch_bytes": 50368472, "write_bytes": 16777216, "sources": "96752c54a085d577"},
+    "copy8192": {"fetch_bytes": 268435456, "write_bytes": 268435456, "sources": "96752c54a085d577"},
 }
 
 # forced parenthesisations of the mixed-property chain (the planner's own tree never forms
