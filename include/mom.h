@@ -15,8 +15,10 @@
  *   - All matrices are dense, row-major f32 (the paper's memref materialisation, Sec. 2).
  *     Factor t has dims[t] rows and dims[t+1] columns.
  *   - lowerTri: entries above the diagonal are zero; upperTri: entries below it are zero; the
- *     diagonal is stored data.  The library never READS the zero half of a triangular factor:
- *     only the triangle defines the value.  Identity factors have no buffer.
+ *     diagonal is stored data.  Only the triangle of a triangular factor defines the value: the
+ *     other half of its (dense, fully allocated) buffer may be loaded but is masked before any
+ *     arithmetic, so whatever it holds, NaN included, never reaches a result.  Identity factors
+ *     have no buffer.
  *   - lowerTri, upperTri and Identity factors must be square.
  *   - Plans live in host memory, belong to the library until mom_plan_destroy, are immutable
  *     and may be evaluated concurrently on different streams with different workspaces.
