@@ -158,6 +158,29 @@ def test_random_chains_with_random_properties():
         assert (plan.cost_mults, plan.splits) == (want["cost"], want["splits"])
 
 
+def test_random_chains_larger_and_snapped_to_tiles():
+    """Larger random chains, half of them snapped to multiples of 32 / 64 / 128 (16-byte paths),
+    random forced trees, strided buffers."""
+    rng = np.random.default_rng(123)
+    for trial in range(40):
+        n = int(rng.integers(1, 5))
+        dims, props = random_chain(rng, n, int(rng.choice([96, 300, 700])))
+        if rng.integers(0, 2):
+            snap = int(rng.choice([32, 64, 128]))
+            dims = [max(snap, (d // snap) * snap) for d in dims]
+            for t, p in enumerate(props):
+                if p != G:
+                    dims[t + 1] = dims[t]
+        f = chain(dims, props, 5000 + trial)
+        surv = oracle.survivors(props)
+        splits = None
+        if len(surv) >= 3 and rng.integers(0, 2):
+            trees = list(all_preorder_trees(0, len(surv) - 1))
+            splits = [surv[x] for x in trees[int(rng.integers(0, len(trees)))]]
+        pad = int(rng.choice([0, 0, 4, 5]))
+        check_against_dense(dims, props, f, splits=splits, flags=int(rng.integers(0, 2)), pad_cols=pad, out_pad=pad)
+
+
 def test_triangular_temporaries_feed_masked_products():
     # (L1 L2) is a lowerTri temporary of which only the triangle is written; whatever the
     # workspace held before must not leak into ((L1 L2) U) G
