@@ -2,9 +2,8 @@
 
 Shared by the tests, the benchmark, the smoke check and the CPU oracle's callers.
 This module holds no arithmetic of the method: it only draws uniform[-1, 1) f32
-entries from a seed and writes the zeros (or the unit diagonal) that a factor's
-property prescribes, which is how the paper's Fill operation initialises an
-algebraic object "according to its properties" (Sec. 2, Table 1).
+entries from a seed and writes the zeros a factor's property prescribes, as the
+Fill operation of the paper does when it initialises an object (Sec. 2, Table 1).
 
 Properties: 0 general, 1 lowerTri (zeros above the diagonal), 2 upperTri (zeros below
 the diagonal), 3 Identity (no buffer at all).  The diagonal of a triangular factor is

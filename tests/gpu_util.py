@@ -71,6 +71,36 @@ def eval_chain(dims, props, factors, splits=None, flags=0, poison=True, pad_cols
     return plan, res[:, :cols]
 
 
+def assert_close_by_tiles(got: np.ndarray, want: np.ndarray, prop: int = G, tile: int = 128, tol: float = TOL):
+    """Whole-result comparison that localises a bad tile: the relative Frobenius error must hold
+    overall AND in every band of `tile` rows (the rows one tile-row of the product kernel
+    writes), both restricted to the structure of `prop`; on failure the worst tile x tile block
+    is named.  `want` is the f64 reference."""
+    rows, cols = want.shape
+    mask = structure_mask(prop, rows, cols)
+    diff = np.where(mask, got.astype(np.float64) - want, 0.0)
+    assert not np.any(np.isnan(diff)), "unwritten entries inside the result's structure"
+    ref = np.where(mask, want, 0.0)
+    d2, r2 = diff * diff, ref * ref
+    scale = np.sqrt(r2.sum() / max(int(mask.sum()), 1))          # rms magnitude of a result entry
+    worst = (0.0, -1)
+    for r0 in range(0, rows, tile):
+        num, den, cnt = d2[r0:r0 + tile].sum(), r2[r0:r0 + tile].sum(), int(mask[r0:r0 + tile].sum())
+        # a band of few or tiny entries is measured against the typical entry as well
+        err = np.sqrt(num) / max(np.sqrt(den), scale * np.sqrt(cnt) * 1e-3, 1e-300)
+        worst = max(worst, (float(err), r0 // tile))
+    if worst[0] > tol:
+        tr = worst[1]
+        band = d2[tr * tile:(tr + 1) * tile]
+        per_col = [float(np.sqrt(band[:, c0:c0 + tile].max())) for c0 in range(0, cols, tile)]
+        tc = int(np.argmax(per_col))
+        raise AssertionError("tile-row %d: relative error %.3e; worst tile (%d, %d), max abs error %.3e" %
+                             (tr, worst[0], tr, tc, per_col[tc]))
+    total = float(np.sqrt(d2.sum()) / max(np.sqrt(r2.sum()), 1e-300))
+    assert total <= tol, "relative Frobenius error %.3e" % total
+    return total, worst[0]
+
+
 def check_against_dense(dims, props, factors, splits=None, flags=0, **kw):
     plan, got = eval_chain(dims, props, factors, splits, flags, **kw)
     np_f = [None if f is None else f.numpy() for f in factors]
@@ -83,6 +113,7 @@ def check_against_dense(dims, props, factors, splits=None, flags=0, **kw):
     assert not np.any(np.isnan(got[mask])), "unwritten entries inside the result's structure"
     err = rel_fro(np.where(mask, got, 0.0), np.where(mask, want, 0.0))
     assert err <= TOL, "relative Frobenius error %.3e" % err
+    assert_close_by_tiles(got, want, prop)
     if prop in (L, U):
         other = got[~mask]
         if flags & mom.MOM_OUT_ZERO_FILL_TRIANGLE:

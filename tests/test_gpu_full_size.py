@@ -1,0 +1,129 @@
+"""GPU parity of WHOLE results at the sizes where the large-launch paths of the product kernel
+run: tiles paired longest-with-shortest, the persistent grid over equal tiles, and tile orders
+that take many rounds of resident workgroups.  Every entry of the result is compared with the
+f64 oracle, per band of 128 rows (one tile-row) and overall.
+
+References: `oracle.eval_dense` (the plain definition, no property logic) where a dense f64
+product is affordable, `oracle.eval_plan` along the same tree (pinned to the dense definition
+by the CPU tests) at n = 4096 / 8192, plus `oracle.eval_rows` (the definition again) on one
+row of every tile-row."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2208_10391_amd as mom
+import synthetic_chains as sc
+from gpu_util import G, I, L, TOL, U, assert_close_by_tiles, rel_fro, structure_mask, upload
+
+pytestmark = pytest.mark.gpu
+
+
+def one_row_per_tile_row(rows: int, seed: int, tile: int = 128):
+    """One row inside every band of `tile` rows, at an offset that varies from band to band."""
+    rng = np.random.default_rng(seed)
+    picks = [min(r0 + int(rng.integers(0, tile)), rows - 1) for r0 in range(0, rows, tile)]
+    return sorted(set(picks) | {0, rows - 1})
+
+
+def run_whole(dims, props, host, splits=None, flags=0, reference="plan", expect_plan=None, rows_seed=None):
+    plan = mom.mom_chain_plan(dims, props) if splits is None else mom.mom_plan_from_splits(dims, props, splits)
+    if expect_plan:
+        assert plan.string == expect_plan
+    if splits is None:
+        want_plan = oracle.plan_bruteforce(dims, props)
+        assert (plan.cost_mults, plan.splits) == (want_plan["cost"], want_plan["splits"])
+    else:
+        assert plan.cost_mults == oracle.tree_cost(dims, props, splits)[0]
+    dev = upload(host, props, poison=True)
+    rows, cols, prop = plan.result
+    out = torch.full((rows, cols), float("nan"), device="cuda", dtype=torch.float32)
+    ws = torch.full((max(plan.workspace_bytes, 4) // 4,), float("nan"), device="cuda", dtype=torch.float32)
+    mom.mom_chain_eval(plan, dev, out=out, workspace=ws, flags=flags)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    np_f = [None if f is None else f.numpy() for f in host]
+    if reference == "dense":
+        want = oracle.eval_dense(dims, props, np_f)
+    else:
+        want, want_prop = oracle.eval_plan(dims, props, np_f, plan.splits)
+        assert want_prop == prop
+    assert_close_by_tiles(got, want, prop)
+    mask = structure_mask(prop, rows, cols)
+    if prop in (L, U):
+        assert np.all(np.isnan(got[~mask])), "other half of a triangular result must stay untouched"
+    if rows_seed is not None:          # the property-free definition on one row of every tile-row
+        picks = one_row_per_tile_row(rows, rows_seed)
+        rows_want = oracle.eval_rows(dims, props, np_f, picks)
+        for r, w in zip(picks, rows_want):
+            keep = mask[r]
+            err = rel_fro(got[r][keep], w[keep])
+            assert err <= TOL, "row %d: relative error %.3e" % (r, err)
+    return plan
+
+
+# ---- one dense-checked product per large-launch path ---------------------------------------
+
+@pytest.mark.parametrize("pa,pb", [(L, G), (U, G), (G, L), (G, U)])
+def test_paired_tiles_whole_result(pa, pb):
+    # 23 x 23 = 529 tiles of 128: between 512 and 2047, so workgroup b takes tiles b and 528-b
+    n = 2944
+    dims, props = [n, n, n], [pa, pb]
+    run_whole(dims, props, sc.make_chain(dims, props, 71), reference="dense")
+
+
+def test_persistent_grid_whole_result():
+    # 24 x 24 = 576 equal tiles > 512 resident workgroups, k = 288 >= 256: every workgroup
+    # strides over the tiles, some take two
+    dims, props = [3072, 288, 3072], [G, G]
+    run_whole(dims, props, sc.make_chain(dims, props, 72), reference="dense")
+
+
+def test_persistent_grid_ragged_whole_result():
+    dims, props = [3000, 300, 3100], [G, G]
+    run_whole(dims, props, sc.make_chain(dims, props, 73), reference="dense")
+
+
+@pytest.mark.parametrize("pa,pb", [(L, L), (U, U), (L, U), (U, L)])
+def test_triangular_pairs_many_rounds_whole_result(pa, pb):
+    # 33 x 33 tiles: 561 (tri -> tri, paired) or 1089 (tri.tri -> general, paired) tiles, ragged edge
+    n = 4100
+    dims, props = [n, n, n], [pa, pb]
+    run_whole(dims, props, sc.make_chain(dims, props, 74), reference="plan", rows_seed=5)
+
+
+# ---- the workloads, every entry ------------------------------------------------------------
+
+def test_trmm4096_whole_result():
+    c = sc.CONFIGS["trmm4096"]
+    run_whole(c.dims, c.props, sc.make_config("trmm4096"), expect_plan="(0 1)", rows_seed=2)
+
+
+def test_general5_whole_result_both_trees():
+    c = sc.CONFIGS["general5"]
+    host = sc.make_config("general5")
+    run_whole(c.dims, c.props, host, expect_plan="((0 (1 2)) (3 4))", rows_seed=3)
+    run_whole(c.dims, c.props, host, splits=oracle.left_to_right_splits(c.props), expect_plan="((((0 1) 2) 3) 4)")
+
+
+@pytest.mark.parametrize("splits,text", [(None, "(0 (2 (3 4)))"), ([2, 0, 3], "((0 2) (3 4))"),
+                                         ([3, 2, 0], "(((0 2) 3) 4)")])
+def test_mixed5_whole_result(splits, text):
+    c = sc.CONFIGS["mixed5"]
+    run_whole(c.dims, c.props, sc.make_config("mixed5"), splits=splits, expect_plan=text,
+              rows_seed=4 if splits is None else None)
+
+
+def test_lower_times_lower_8192_whole_result():
+    # 2080 tiles, unpaired, longest diagonals first: more than four rounds of resident workgroups
+    n = 8192
+    dims, props = [n, n, n], [L, L]
+    plan = run_whole(dims, props, sc.make_chain(dims, props, 40), rows_seed=8)
+    assert plan.result == (n, n, L)
+
+
+def test_lower_times_upper_8192_whole_result():
+    # 4096 tiles in shells
+    n = 8192
+    dims, props = [n, n, n], [L, U]
+    run_whole(dims, props, sc.make_chain(dims, props, 44))
