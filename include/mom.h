@@ -25,7 +25,10 @@
  *   - The library never allocates, frees or synchronises device memory.  Inputs, output and
  *     workspace are the caller's; inputs are read-only and must not overlap the output or the
  *     workspace.  Evaluation calls only enqueue kernels on the given stream and return.
- *   - Every call reports failure through mom_status_t; nothing is enqueued on failure.
+ *   - Every call reports failure through mom_status_t and no C++ exception leaves the library.
+ *     Every check of an evaluation call comes before its first launch, so nothing is enqueued
+ *     on failure; the one exception is MOM_ERR_HIP (the runtime rejected a launch), after which
+ *     earlier launches of the same call may already be on the stream.
  *   - "host" / "device" below say where a pointer must point.
  */
 #ifndef MOM_H
@@ -58,8 +61,13 @@ typedef enum {
     MOM_ERR_WORKSPACE,         /* workspace NULL or smaller than mom_plan_workspace_bytes */
     MOM_ERR_BUFFER_TOO_SMALL,  /* caller's host buffer cannot hold the answer */
     MOM_ERR_BAD_STRIDE,        /* a row or batch stride is smaller than the matrix needs */
-    MOM_ERR_UNSUPPORTED,       /* the batched kernel does not cover this plan's shapes */
-    MOM_ERR_HIP                /* the HIP runtime rejected a launch */
+    MOM_ERR_UNSUPPORTED,       /* the batched kernel does not cover this plan's shapes, or a product
+                                  would need more workgroups than one launch can have */
+    MOM_ERR_HIP,               /* the HIP runtime rejected a call */
+    MOM_ERR_NOMEM,             /* host memory for a plan could not be allocated */
+    MOM_ERR_BAD_FLAGS,         /* flag bits that this version does not define */
+    MOM_ERR_NOT_READY          /* first evaluation on this device was attempted while its stream
+                                  is being captured: call mom_init (or evaluate once) before */
 } mom_status_t;
 
 #define MOM_MAX_FACTORS 1024
@@ -96,6 +104,10 @@ mom_status_t mom_plan_from_splits(const int64_t *dims, const int32_t *props, int
 
 void mom_plan_destroy(mom_plan_t *plan);                       /* NULL is allowed */
 
+/* The accessors below read what the transformations of Sec. 2 produced for the chain: the
+ * multiplication count that the chain reordering minimised, the binary products the variadic
+ * Mul was rewritten into, and the inferred type of the result. */
+
 /* Scalar multiplications of the plan's tree (0 for a NULL plan). */
 uint64_t mom_plan_cost_mults(const mom_plan_t *plan);
 
@@ -117,6 +129,15 @@ mom_status_t mom_plan_splits(const mom_plan_t *plan, int32_t *out, int32_t cap);
 size_t mom_plan_workspace_bytes(const mom_plan_t *plan);
 
 /*
+ * One-time set-up of the CURRENT device (kernel attributes), for callers that record
+ * evaluations into a HIP graph: the set-up is not allowed while a stream is being captured.
+ * Without this call the first evaluation on a device does the same, unless its stream is being
+ * captured, in which case it returns MOM_ERR_NOT_READY and enqueues nothing.  Idempotent and
+ * cheap after the first time; allocates no device memory.
+ */
+mom_status_t mom_init(void);
+
+/*
  * Enqueue the evaluation of the plan on `stream` (a hipStream_t passed as void*; NULL = the
  * default stream).  Asynchronous.  The products run level by level of the tree; small
  * independent products of one level share a kernel launch, a product cut along k is followed
@@ -129,7 +150,7 @@ size_t mom_plan_workspace_bytes(const mom_plan_t *plan);
  *   d_out     [device] rows x cols result, row stride ld_out elements (0 = packed).
  *   d_workspace [device] at least mom_plan_workspace_bytes bytes, 256-byte aligned; may be
  *             NULL when that is 0.  Contents are scratch.
- *   flags     0 or MOM_OUT_ZERO_FILL_TRIANGLE.
+ *   flags     0 or MOM_OUT_ZERO_FILL_TRIANGLE; any other bit is MOM_ERR_BAD_FLAGS.
  * A chain whose factors are all Identity writes the identity matrix; a chain with a single
  * surviving factor copies it (its triangle only, for a triangular factor).
  */
@@ -138,7 +159,9 @@ mom_status_t mom_chain_eval(const mom_plan_t *plan, const float *const *d_factor
                             uint32_t flags, void *stream);
 
 /*
- * Evaluate `batch` independent chains that share one plan in ONE kernel launch; each chain is
+ * The same variadic Mul (Sec. 2, "Operations") for many small chains at once: evaluate
+ * `batch` independent chains that share one plan (one shape, one property list, hence one
+ * parenthesisation by Sec. 2, "Transformations") in ONE kernel launch; each chain is
  * handled by one 64-lane wavefront and intermediates never leave the compute unit.
  *   d_factor_bases [host] n DEVICE pointers; chain b's factor t starts at
  *             d_factor_bases[t] + b * batch_strides[t] and is packed row-major.

@@ -19,11 +19,12 @@ MOM_MAX_FACTORS = 1024
 
 STATUS_NAMES = ["MOM_OK", "MOM_ERR_NULL", "MOM_ERR_BAD_N", "MOM_ERR_BAD_DIM", "MOM_ERR_BAD_PROP",
                 "MOM_ERR_NOT_SQUARE", "MOM_ERR_OVERFLOW", "MOM_ERR_BAD_SPLITS", "MOM_ERR_WORKSPACE",
-                "MOM_ERR_BUFFER_TOO_SMALL", "MOM_ERR_BAD_STRIDE", "MOM_ERR_UNSUPPORTED", "MOM_ERR_HIP"]
+                "MOM_ERR_BUFFER_TOO_SMALL", "MOM_ERR_BAD_STRIDE", "MOM_ERR_UNSUPPORTED", "MOM_ERR_HIP",
+                "MOM_ERR_NOMEM", "MOM_ERR_BAD_FLAGS", "MOM_ERR_NOT_READY"]
 
 EXPORTS = ["mom_chain_plan", "mom_plan_from_splits", "mom_plan_destroy", "mom_plan_cost_mults",
            "mom_plan_num_products", "mom_plan_result", "mom_plan_string", "mom_plan_splits",
-           "mom_plan_workspace_bytes", "mom_chain_eval", "mom_chain_eval_batched", "mom_probe_mfma_peak",
+           "mom_plan_workspace_bytes", "mom_init", "mom_chain_eval", "mom_chain_eval_batched", "mom_probe_mfma_peak",
            "mom_status_string"]
 
 
@@ -65,6 +66,8 @@ _lib.mom_plan_splits.restype = ctypes.c_int
 _lib.mom_plan_splits.argtypes = [ctypes.c_void_p, _i32p, ctypes.c_int32]
 _lib.mom_plan_workspace_bytes.restype = ctypes.c_size_t
 _lib.mom_plan_workspace_bytes.argtypes = [ctypes.c_void_p]
+_lib.mom_init.restype = ctypes.c_int
+_lib.mom_init.argtypes = []
 _lib.mom_chain_eval.restype = ctypes.c_int
 _lib.mom_chain_eval.argtypes = [ctypes.c_void_p, _vpp, _i64p, ctypes.c_void_p, ctypes.c_int64,
                                 ctypes.c_void_p, ctypes.c_size_t, ctypes.c_uint32, ctypes.c_void_p]
@@ -191,6 +194,13 @@ def mom_plan_splits(plan: Plan) -> List[int]:
 
 def mom_plan_workspace_bytes(plan: Plan) -> int:
     return int(_lib.mom_plan_workspace_bytes(plan.handle))
+
+
+def mom_init() -> None:
+    """One-time set-up of the current device (needed before a FIRST evaluation is captured)."""
+    st = _lib.mom_init()
+    if st != MOM_OK:
+        raise MomError(st, "mom_init")
 
 
 def _stream_handle(stream) -> ctypes.c_void_p:

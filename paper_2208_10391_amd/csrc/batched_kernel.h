@@ -14,7 +14,7 @@
 namespace mom {
 
 constexpr int kBatchedMaxDim = 32;
-constexpr int kBatchedMaxFactors = 8;
+constexpr int kBatchedMaxFactors = kBatchedSlots;
 constexpr int kSlotLd = 36;                       // LDS row stride of a 32x32 slot, floats
 constexpr int kSlotFloats = 32 * kSlotLd;
 
@@ -203,21 +203,11 @@ inline hipError_t launch_batched(const mom_plan *plan, const float *const *bases
         p.vec[i] = p.rows[i] == 32 && p.cols[i] == 32 && (reinterpret_cast<uintptr_t>(bases[f]) & 15) == 0 &&
                    (p.stride[i] & 3) == 0;
     }
-    // slot of every value: factor -> its position among the survivors; a product's result
-    // takes over the slot of its left operand
-    std::vector<int> temp_slot(plan->temps.size(), -1);
-    auto slot_of = [&](const Operand &o) {
-        if (o.where == Where::Temp) return temp_slot[o.index];
-        for (int i = 0; i < nl; ++i)
-            if (plan->survivors[i] == o.index) return i;
-        return -1;
-    };
+    // slots were assigned with the plan
     p.num_products = (int)plan->steps.size();
     for (int s = 0; s < p.num_products; ++s) {
-        const ProductStep &st = plan->steps[s];
-        p.a_slot[s] = slot_of(st.a);
-        p.b_slot[s] = slot_of(st.b);
-        if (st.c.where == Where::Temp) temp_slot[st.c.index] = p.a_slot[s];
+        p.a_slot[s] = plan->a_slot[s];
+        p.b_slot[s] = plan->b_slot[s];
     }
     p.result_slot = 0;
     p.out = d_out;

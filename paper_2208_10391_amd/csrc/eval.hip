@@ -10,7 +10,6 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
-#include <vector>
 
 namespace {
 
@@ -21,23 +20,44 @@ using namespace mom;
 typedef TileConfig<128, 128, kChunk128, 2, 2, 2> Tile128;
 typedef TileConfig<64, 64, kChunk64, 2, 2, 4> Tile64;
 
-constexpr int kMaxDevices = 64;       // devices whose kernel attributes are remembered
+constexpr int kMaxDevices = 64;       // devices whose one-time set-up is remembered
+
+// One-time set-up per device: the tiles' LDS footprint exceeds the default dynamic limit, so
+// the limit of each product kernel is raised once (hipFuncSetAttribute is not allowed while a
+// stream is being captured, which is why this is not left to the launch itself).
+std::atomic<bool> g_device_ready[kMaxDevices];
+
+hipError_t configure_kernels()
+{
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&product_kernel<Tile128>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, Tile128::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&product_kernel<Tile64>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, Tile64::LDS_BYTES);
+}
+
+// Make the current device ready for launches.  `stream` is the stream an evaluation is about
+// to use (nullptr from mom_init): a first use under capture is refused instead of breaking the
+// capture.  A second thread doing the same set-up at the same moment is harmless.
+mom_status_t ensure_device_ready(bool have_stream, hipStream_t stream)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return MOM_ERR_HIP;
+    const bool remembered = dev >= 0 && dev < kMaxDevices;
+    if (remembered && g_device_ready[dev].load(std::memory_order_acquire)) return MOM_OK;
+    if (have_stream) {
+        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(stream, &cs) != hipSuccess) return MOM_ERR_HIP;
+        if (cs != hipStreamCaptureStatusNone) return MOM_ERR_NOT_READY;
+    }
+    if (configure_kernels() != hipSuccess) return MOM_ERR_HIP;
+    if (remembered) g_device_ready[dev].store(true, std::memory_order_release);
+    return MOM_OK;
+}
 
 template <class T>
 hipError_t launch_product(const ProductBatch &batch, hipStream_t stream)
 {
-    // the tile's LDS footprint exceeds the default dynamic limit: raise it once per device (a
-    // second thread doing the same at the same moment is harmless)
-    static std::atomic<bool> configured[kMaxDevices];
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= kMaxDevices || !configured[dev].load(std::memory_order_acquire)) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&product_kernel<T>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        if (dev >= 0 && dev < kMaxDevices) configured[dev].store(true, std::memory_order_release);
-    }
     hipLaunchKernelGGL(product_kernel<T>, dim3(batch.block_end[batch.count - 1]), dim3(T::NT), T::LDS_BYTES, stream,
                        batch);
     return hipGetLastError();
@@ -74,26 +94,10 @@ inline int elementwise_grid(int64_t total) { return (int)std::min<int64_t>((tota
 
 struct Resolved { const float *ptr; int64_t ld; };
 
-}  // namespace
-
-extern "C" mom_status_t mom_chain_eval(const mom_plan_t *plan, const float *const *d_factors, const int64_t *lds,
-                                       float *d_out, int64_t ld_out, void *d_workspace, size_t workspace_bytes,
-                                       uint32_t flags, void *stream_)
+// The evaluation proper: every check that can fail comes before the first launch.
+mom_status_t eval_chain(const mom_plan_t *plan, const float *const *d_factors, const int64_t *lds, float *d_out,
+                        int64_t ld_out, char *ws, uint32_t flags, hipStream_t stream)
 {
-    if (!plan || !d_out) return MOM_ERR_NULL;
-    if (!d_factors && !plan->survivors.empty()) return MOM_ERR_NULL;
-    for (int32_t f : plan->survivors)
-        if (!d_factors[f]) return MOM_ERR_NULL;
-    if (lds)
-        for (int32_t f : plan->survivors)
-            if (lds[f] < plan->dims[f + 1]) return MOM_ERR_BAD_STRIDE;
-    if (ld_out == 0) ld_out = plan->cols;
-    if (ld_out < plan->cols) return MOM_ERR_BAD_STRIDE;
-    if (plan->workspace_bytes > 0 &&
-        (!d_workspace || workspace_bytes < plan->workspace_bytes || (reinterpret_cast<uintptr_t>(d_workspace) & 255)))
-        return MOM_ERR_WORKSPACE;
-    hipStream_t stream = static_cast<hipStream_t>(stream_);
-    char *const ws = static_cast<char *>(d_workspace);
     const bool zero_fill = (flags & MOM_OUT_ZERO_FILL_TRIANGLE) != 0;
     const int M = (int)plan->rows, N = (int)plan->cols;
 
@@ -112,73 +116,43 @@ extern "C" mom_status_t mom_chain_eval(const mom_plan_t *plan, const float *cons
         if (hipGetLastError() != hipSuccess) return MOM_ERR_HIP;
     }
 
-    // Level by level; the products of a level that share a tile shape go out in one launch
-    // (at most kMaxFused at a time), followed by one launch that sums their split-K slices.
     auto resolve = [&](const Operand &o, int64_t cols) {
         if (o.where == Where::Factor) return factor(o.index);
         if (o.where == Where::Temp)
             return Resolved{reinterpret_cast<const float *>(ws + plan->temps[o.index].offset), cols};
         return Resolved{d_out, ld_out};
     };
-    size_t next = 0;
-    while (next < plan->order.size()) {
-        const int level = plan->steps[plan->order[next]].level;
-        size_t level_end = next;
-        while (level_end < plan->order.size() && plan->steps[plan->order[level_end]].level == level) ++level_end;
-        std::vector<bool> done(level_end - next, false);
-        for (size_t first = next; first < level_end; ++first) {
-            if (done[first - next]) continue;
-            const int shape = choose_launch(plan->steps[plan->order[first]]).shape;
-            ProductBatch batch{};
-            ReduceBatch reduce{};
-            int64_t reduce_quads = 0;
-            bool batch_small = true;
-            for (size_t i = first; i < level_end && batch.count < kMaxFused; ++i) {
-                const ProductStep &st = plan->steps[plan->order[i]];
-                const Launch L = choose_launch(st);
-                if (done[i - next] || L.shape != shape) continue;
-                // only small products share a launch: a big one fills the chip by itself and
-                // keeps its longest-first tile order only when it is alone
-                const bool small_launch = (int64_t)L.grid * L.split_k <= 4 * kComputeUnits;
-                if (batch.count > 0 && (!small_launch || !batch_small)) continue;
-                batch_small = small_launch;
-                done[i - next] = true;
-                const Resolved a = resolve(st.a, st.k), b = resolve(st.b, st.n), c = resolve(st.c, st.n);
-                ProductParams &p = batch.prob[batch.count];
-                p.A = a.ptr; p.B = b.ptr; p.C = const_cast<float *>(c.ptr);
-                p.lda = a.ld; p.ldb = b.ld; p.ldc = c.ld;
-                p.M = (int)st.m; p.N = (int)st.n; p.K = (int)st.k;
-                p.pa = st.pa; p.pb = st.pb; p.pc = st.pc;
-                p.tiles_m = L.tiles_m; p.tiles_n = L.tiles_n; p.num_tiles = L.num_tiles;
-                p.order = L.order; p.paired = L.paired; p.grid = L.grid;
-                p.a_vec = aligned16(a.ptr, a.ld); p.b_vec = aligned16(b.ptr, b.ld);
-                p.split_k = L.split_k;
-                p.slice_stride = 0;
-                if (L.split_k > 1) {                       // partial sums go to the scratch region
-                    p.C = reinterpret_cast<float *>(ws + plan->scratch_offset + st.scratch_offset);
-                    p.ldc = st.n;
-                    p.slice_stride = st.m * st.n;
-                    ReduceParams &r = reduce.prob[reduce.count++];
-                    r.P = p.C; r.C = const_cast<float *>(c.ptr);
-                    r.slice_stride = p.slice_stride; r.ldc = c.ld;
-                    r.slices = L.split_k; r.M = p.M; r.N = p.N;
-                    reduce_quads = std::max<int64_t>(reduce_quads, (st.m * st.n + 3) / 4);
-                }
-                p.c_vec = aligned16(p.C, p.ldc);
-                const int64_t blocks = (int64_t)(batch.count ? batch.block_end[batch.count - 1] : 0) + (int64_t)L.grid * L.split_k;
-                if (blocks > 0x7fffffff) return MOM_ERR_UNSUPPORTED;
-                batch.block_end[batch.count++] = (int)blocks;
+    // The launches were laid out with the plan; only addresses are filled in here.
+    for (const PlannedLaunch &pl : plan->launches) {
+        ProductBatch batch = pl.batch;
+        for (int i = 0; i < batch.count; ++i) {
+            const ProductStep &st = plan->steps[pl.step[i]];
+            ProductParams &p = batch.prob[i];
+            const Resolved a = resolve(st.a, st.k), b = resolve(st.b, st.n), c = resolve(st.c, st.n);
+            p.A = a.ptr; p.B = b.ptr; p.C = const_cast<float *>(c.ptr);
+            p.lda = a.ld; p.ldb = b.ld; p.ldc = c.ld;
+            p.a_vec = aligned16(a.ptr, a.ld); p.b_vec = aligned16(b.ptr, b.ld);
+            if (p.split_k > 1) {                           // partial sums go to the scratch region
+                p.C = reinterpret_cast<float *>(ws + plan->scratch_offset + st.scratch_offset);
+                p.ldc = st.n;
             }
-            const hipError_t e = shape == kTile128 ? launch_product<Tile128>(batch, stream)
-                                                   : launch_product<Tile64>(batch, stream);
-            if (e != hipSuccess) return MOM_ERR_HIP;
-            if (reduce.count > 0) {
-                hipLaunchKernelGGL(reduce_slices_kernel, dim3((unsigned)std::min<int64_t>((reduce_quads + 31) / 32, 8192), reduce.count),
-                                   dim3(256), 0, stream, reduce);
-                if (hipGetLastError() != hipSuccess) return MOM_ERR_HIP;
-            }
+            p.c_vec = aligned16(p.C, p.ldc);
         }
-        next = level_end;
+        const hipError_t e = pl.shape == kTile128 ? launch_product<Tile128>(batch, stream)
+                                                  : launch_product<Tile64>(batch, stream);
+        if (e != hipSuccess) return MOM_ERR_HIP;
+        if (pl.reduce.count > 0) {
+            ReduceBatch reduce = pl.reduce;
+            for (int i = 0; i < reduce.count; ++i) {
+                const int slot = pl.reduce_of[i];
+                const Resolved c = resolve(plan->steps[pl.step[slot]].c, plan->steps[pl.step[slot]].n);
+                reduce.prob[i].P = batch.prob[slot].C;
+                reduce.prob[i].C = const_cast<float *>(c.ptr);
+                reduce.prob[i].ldc = c.ld;
+            }
+            hipLaunchKernelGGL(reduce_slices_kernel, dim3(pl.reduce_grid_x, reduce.count), dim3(256), 0, stream, reduce);
+            if (hipGetLastError() != hipSuccess) return MOM_ERR_HIP;
+        }
     }
 
     if (zero_fill && (plan->result_prop == kLower || plan->result_prop == kUpper)) {
@@ -187,6 +161,45 @@ extern "C" mom_status_t mom_chain_eval(const mom_plan_t *plan, const float *cons
         if (hipGetLastError() != hipSuccess) return MOM_ERR_HIP;
     }
     return MOM_OK;
+}
+
+// Argument checks shared by the evaluation entry points; ld_out is resolved (0 = packed).
+mom_status_t check_eval_arguments(const mom_plan_t *plan, const float *const *d_factors, const int64_t *lds,
+                                  const float *d_out, int64_t &ld_out, uint32_t flags)
+{
+    if (!plan || !d_out) return MOM_ERR_NULL;
+    if (!d_factors && !plan->survivors.empty()) return MOM_ERR_NULL;
+    for (int32_t f : plan->survivors)
+        if (!d_factors[f]) return MOM_ERR_NULL;
+    if (lds)
+        for (int32_t f : plan->survivors)
+            if (lds[f] < plan->dims[f + 1]) return MOM_ERR_BAD_STRIDE;
+    if (ld_out == 0) ld_out = plan->cols;
+    if (ld_out < plan->cols) return MOM_ERR_BAD_STRIDE;
+    if (flags & ~(uint32_t)MOM_OUT_ZERO_FILL_TRIANGLE) return MOM_ERR_BAD_FLAGS;
+    return MOM_OK;
+}
+
+}  // namespace
+
+extern "C" mom_status_t mom_init(void)
+{
+    return ensure_device_ready(false, nullptr);
+}
+
+extern "C" mom_status_t mom_chain_eval(const mom_plan_t *plan, const float *const *d_factors, const int64_t *lds,
+                                       float *d_out, int64_t ld_out, void *d_workspace, size_t workspace_bytes,
+                                       uint32_t flags, void *stream_)
+{
+    mom_status_t st = check_eval_arguments(plan, d_factors, lds, d_out, ld_out, flags);
+    if (st != MOM_OK) return st;
+    if (plan->workspace_bytes > 0 &&
+        (!d_workspace || workspace_bytes < plan->workspace_bytes || (reinterpret_cast<uintptr_t>(d_workspace) & 255)))
+        return MOM_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    st = ensure_device_ready(true, stream);
+    if (st != MOM_OK) return st;
+    return eval_chain(plan, d_factors, lds, d_out, ld_out, static_cast<char *>(d_workspace), flags, stream);
 }
 
 extern "C" mom_status_t mom_chain_eval_batched(const mom_plan_t *plan, const float *const *d_factor_bases,

@@ -1,0 +1,46 @@
+// Kernel argument blocks of the product and slice-sum kernels: plain data, filled by the
+// planner at plan time (shapes, tile geometry) and completed by the evaluator at launch time
+// (pointers, row strides, alignment flags).  No HIP types: the host-only planner includes this.
+#pragma once
+#include <stdint.h>
+
+namespace mom {
+
+constexpr int kMaxFused = 4;          // independent products one launch can carry
+
+struct ProductParams {
+    const float *A;
+    const float *B;
+    float *C;              // result, or split-K partial sums (slice s at C + s * slice_stride)
+    int64_t lda, ldb, ldc;
+    int64_t slice_stride;  // elements between split-K slices (0 when split_k == 1)
+    int M, N, K;
+    int pa, pb, pc;
+    int tiles_m, tiles_n, num_tiles, order, paired;
+    int grid;              // workgroups per k-slice
+    int a_vec, b_vec;      // 16-byte loads are legal for A / B (base and row stride aligned)
+    int c_vec;             // 16-byte stores are legal for C
+    int split_k;
+};
+
+// Several independent products in one launch: workgroups [block_end[i-1], block_end[i]) belong
+// to product i, slice-major (split_k slices of `grid` workgroups each).
+struct ProductBatch {
+    int count;
+    int block_end[kMaxFused];
+    ProductParams prob[kMaxFused];
+};
+
+// Sum of split-K slices: C[i][j] = sum_s P[s][i][j], for up to kMaxFused products at once.
+struct ReduceParams {
+    const float *P;
+    float *C;
+    int64_t slice_stride, ldc;
+    int slices, M, N;
+};
+struct ReduceBatch {
+    int count;
+    ReduceParams prob[kMaxFused];
+};
+
+}  // namespace mom

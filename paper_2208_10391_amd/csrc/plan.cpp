@@ -8,6 +8,7 @@
 
 #include <algorithm>
 #include <limits>
+#include <memory>
 #include <new>
 
 namespace {
@@ -166,6 +167,85 @@ void render(const mom_plan *plan, const std::vector<int32_t> &split_pos, size_t 
     out += ')';
 }
 
+// The evaluation as a list of launches.  Level by level; the products of a level that share a
+// tile shape go out in one launch (at most kMaxFused at a time), followed by one launch that
+// sums their split-K slices.  Only small products share a launch: a big one fills the chip by
+// itself and keeps its longest-first tile order only when it is alone.  Everything but the
+// operands' addresses is fixed here, so an evaluation call allocates and decides nothing.
+mom_status_t lay_out_launches(mom_plan *plan)
+{
+    using namespace mom;
+    const std::vector<int32_t> &order = plan->order;
+    size_t next = 0;
+    while (next < order.size()) {
+        const int level = plan->steps[order[next]].level;
+        size_t level_end = next;
+        while (level_end < order.size() && plan->steps[order[level_end]].level == level) ++level_end;
+        std::vector<char> done(level_end - next, 0);
+        for (size_t first = next; first < level_end; ++first) {
+            if (done[first - next]) continue;
+            PlannedLaunch pl{};
+            pl.shape = choose_launch(plan->steps[order[first]]).shape;
+            int64_t reduce_quads = 0;
+            bool batch_small = true;
+            for (size_t i = first; i < level_end && pl.batch.count < kMaxFused; ++i) {
+                const ProductStep &st = plan->steps[order[i]];
+                const Launch L = choose_launch(st);
+                if (done[i - next] || L.shape != pl.shape) continue;
+                const bool small_launch = (int64_t)L.grid * L.split_k <= 4 * kComputeUnits;
+                if (pl.batch.count > 0 && (!small_launch || !batch_small)) continue;
+                batch_small = small_launch;
+                done[i - next] = 1;
+                const int slot = pl.batch.count;
+                pl.step[slot] = order[i];
+                ProductParams &p = pl.batch.prob[slot];
+                p.M = (int)st.m; p.N = (int)st.n; p.K = (int)st.k;
+                p.pa = st.pa; p.pb = st.pb; p.pc = st.pc;
+                p.tiles_m = L.tiles_m; p.tiles_n = L.tiles_n; p.num_tiles = L.num_tiles;
+                p.order = L.order; p.paired = L.paired; p.grid = L.grid;
+                p.split_k = L.split_k;
+                p.slice_stride = L.split_k > 1 ? st.m * st.n : 0;
+                if (L.split_k > 1) {
+                    ReduceParams &r = pl.reduce.prob[pl.reduce.count];
+                    pl.reduce_of[pl.reduce.count++] = slot;
+                    r.slice_stride = p.slice_stride;
+                    r.slices = L.split_k; r.M = p.M; r.N = p.N;
+                    reduce_quads = std::max<int64_t>(reduce_quads, (st.m * st.n + 3) / 4);
+                }
+                const int64_t blocks = (int64_t)(slot ? pl.batch.block_end[slot - 1] : 0) + (int64_t)L.grid * L.split_k;
+                if (blocks > 0x7fffffff) return MOM_ERR_UNSUPPORTED;
+                pl.batch.block_end[pl.batch.count++] = (int)blocks;
+            }
+            pl.reduce_grid_x = (unsigned)std::min<int64_t>((reduce_quads + 31) / 32, 8192);
+            plan->launches.push_back(pl);
+        }
+        next = level_end;
+    }
+    return MOM_OK;
+}
+
+// Batched evaluation keeps every value of a chain in an LDS slot: a factor sits in the slot of
+// its position among the survivors, a product's result takes over the slot of its left operand.
+void assign_batched_slots(mom_plan *plan)
+{
+    using namespace mom;
+    const int nl = (int)plan->survivors.size();
+    if (nl > kBatchedSlots) return;
+    std::vector<int> temp_slot(plan->temps.size(), -1);
+    auto slot_of = [&](const Operand &o) {
+        if (o.where == Where::Temp) return temp_slot[o.index];
+        for (int i = 0; i < nl; ++i)
+            if (plan->survivors[i] == o.index) return i;
+        return -1;
+    };
+    for (size_t s = 0; s < plan->steps.size(); ++s) {
+        const ProductStep &st = plan->steps[s];
+        plan->a_slot[s] = slot_of(st.a);
+        plan->b_slot[s] = slot_of(st.b);
+        if (st.c.where == Where::Temp) temp_slot[st.c.index] = plan->a_slot[s];
+    }
+}
+
 // Build everything that follows from a chosen tree (given as positions in the survivors chain).
 mom_status_t finish(mom_plan *plan, const std::vector<int64_t> &d, const std::vector<int32_t> &p,
                     const std::vector<int32_t> &split_pos)
@@ -222,18 +302,19 @@ mom_status_t finish(mom_plan *plan, const std::vector<int64_t> &d, const std::ve
     plan->scratch_offset = (plan->temp_bytes + 255) & ~(size_t)255;
     plan->scratch_bytes = scratch;
     plan->workspace_bytes = scratch ? plan->scratch_offset + scratch : plan->temp_bytes;
+    mom_status_t st = lay_out_launches(plan);
+    if (st != MOM_OK) return st;
+    assign_batched_slots(plan);
     return MOM_OK;
 }
 
-mom_status_t start(const int64_t *dims, const int32_t *props, int32_t n, mom_plan **holder,
-                   std::vector<int64_t> &d, std::vector<int32_t> &p)
+// identity simplification: A*I -> A, I*A -> A, I*I = I.  d / p receive the survivors' chain.
+void start(mom_plan *plan, const int64_t *dims, const int32_t *props, int32_t n,
+           std::vector<int64_t> &d, std::vector<int32_t> &p)
 {
-    mom_plan *plan = new (std::nothrow) mom_plan();
-    if (!plan) return MOM_ERR_NULL;
     plan->n = n;
     plan->dims.assign(dims, dims + n + 1);
     plan->props.assign(props, props + n);
-    // identity simplification: A*I -> A, I*A -> A, I*I = I
     for (int i = 0; i < n; ++i) {
         if (props[i] == kIdentity) continue;
         plan->survivors.push_back(i);
@@ -241,8 +322,96 @@ mom_status_t start(const int64_t *dims, const int32_t *props, int32_t n, mom_pla
         p.push_back(props[i]);
     }
     d.push_back(dims[n]);
-    *holder = plan;
+}
+
+// The chain DP: fewest multiplications for every sub-chain of the survivors, smallest split on
+// ties; returns the chosen tree as preorder positions.
+mom_status_t optimal_splits(const std::vector<int64_t> &d, const std::vector<int32_t> &p, std::vector<int32_t> &split_pos)
+{
+    const int m = (int)p.size();
+    if (m <= 1) return MOM_OK;
+    // best[i][j]: fewest multiplications for survivors i..j; prop[i][j]: their product's
+    // property (independent of the parenthesisation); cut[i][j]: chosen split.
+    std::vector<u128> best((size_t)m * m, 0);
+    std::vector<int32_t> cut((size_t)m * m, -1);
+    std::vector<int8_t> prop((size_t)m * m, 0);
+    auto at = [m](int i, int j) { return (size_t)i * m + j; };
+    for (int i = 0; i < m; ++i) {
+        prop[at(i, i)] = (int8_t)p[i];
+        for (int j = i + 1; j < m; ++j) prop[at(i, j)] = (int8_t)join(prop[at(i, j - 1)], p[j]);
+    }
+    for (int len = 2; len <= m; ++len) {
+        for (int i = 0; i + len <= m; ++i) {
+            const int j = i + len - 1;
+            u128 lowest = 0;
+            int where = -1;
+            for (int k = i; k < j; ++k) {       // ascending; only a strictly smaller cost
+                const u128 c = best[at(i, k)] + best[at(k + 1, j)] +
+                               product_mults(d[i], d[k + 1], d[j + 1], prop[at(i, k)], prop[at(k + 1, j)]);
+                if (where < 0 || c < lowest) { lowest = c; where = k; }   // replaces: smallest split wins ties
+            }
+            best[at(i, j)] = lowest;
+            cut[at(i, j)] = where;
+        }
+    }
+    if (best[at(0, m - 1)] > kU64Max) return MOM_ERR_OVERFLOW;
+    // preorder read-out of the chosen tree
+    std::vector<std::pair<int, int>> todo{{0, m - 1}};
+    while (!todo.empty()) {
+        auto [lo, hi] = todo.back();
+        todo.pop_back();
+        if (lo == hi) continue;
+        const int s = cut[at(lo, hi)];
+        split_pos.push_back(s);
+        todo.emplace_back(s + 1, hi);
+        todo.emplace_back(lo, s);
+    }
     return MOM_OK;
+}
+
+// Plan with the DP's tree (forced == nullptr) or with a given one.  Exceptions (allocation
+// failures of the containers) are turned into a status by the callers.
+mom_status_t make_plan(const int64_t *dims, const int32_t *props, int32_t n, bool forced_tree,
+                       const int32_t *forced, mom_plan_t **out)
+{
+    mom_status_t st = validate(dims, props, n);
+    if (st != MOM_OK) return st;
+    std::unique_ptr<mom_plan> plan(new mom_plan());
+    std::vector<int64_t> d;
+    std::vector<int32_t> p;
+    start(plan.get(), dims, props, n, d, p);
+    const int m = (int)p.size();
+    std::vector<int32_t> split_pos;
+    if (!forced_tree) {
+        st = optimal_splits(d, p, split_pos);
+        if (st != MOM_OK) return st;
+    } else if (m > 1) {
+        if (!forced) return MOM_ERR_NULL;
+        std::vector<int32_t> position(n, -1);
+        for (int i = 0; i < m; ++i) position[plan->survivors[i]] = i;
+        for (int i = 0; i < m - 1; ++i) {
+            const int32_t s = forced[i];
+            if (s < 0 || s >= n || position[s] < 0) return MOM_ERR_BAD_SPLITS;
+            split_pos.push_back(position[s]);
+        }
+    }
+    st = finish(plan.get(), d, p, split_pos);
+    if (st != MOM_OK) return st;
+    *out = plan.release();
+    return MOM_OK;
+}
+
+// No exception leaves the library: allocation failures become MOM_ERR_NOMEM.
+template <class F>
+mom_status_t guarded(F &&body)
+{
+    try {
+        return body();
+    } catch (const std::bad_alloc &) {
+        return MOM_ERR_NOMEM;
+    } catch (...) {
+        return MOM_ERR_NOMEM;
+    }
 }
 
 }  // namespace
@@ -253,57 +422,7 @@ mom_status_t mom_chain_plan(const int64_t *dims, const int32_t *props, int32_t n
 {
     if (!out) return MOM_ERR_NULL;
     *out = nullptr;
-    mom_status_t st = validate(dims, props, n);
-    if (st != MOM_OK) return st;
-    mom_plan *plan = nullptr;
-    std::vector<int64_t> d;
-    std::vector<int32_t> p;
-    st = start(dims, props, n, &plan, d, p);
-    if (st != MOM_OK) return st;
-    const int m = (int)p.size();
-    std::vector<int32_t> split_pos;
-    if (m > 1) {
-        // best[i][j]: fewest multiplications for survivors i..j; prop[i][j]: their product's
-        // property (independent of the parenthesisation); cut[i][j]: chosen split.
-        std::vector<u128> best((size_t)m * m, 0);
-        std::vector<int32_t> cut((size_t)m * m, -1);
-        std::vector<int8_t> prop((size_t)m * m, 0);
-        auto at = [m](int i, int j) { return (size_t)i * m + j; };
-        for (int i = 0; i < m; ++i) {
-            prop[at(i, i)] = (int8_t)p[i];
-            for (int j = i + 1; j < m; ++j) prop[at(i, j)] = (int8_t)join(prop[at(i, j - 1)], p[j]);
-        }
-        for (int len = 2; len <= m; ++len) {
-            for (int i = 0; i + len <= m; ++i) {
-                const int j = i + len - 1;
-                u128 lowest = 0;
-                int where = -1;
-                for (int k = i; k < j; ++k) {       // ascending; only a strictly smaller cost
-                    const u128 c = best[at(i, k)] + best[at(k + 1, j)] +
-                                   product_mults(d[i], d[k + 1], d[j + 1], prop[at(i, k)], prop[at(k + 1, j)]);
-                    if (where < 0 || c < lowest) { lowest = c; where = k; }   // replaces: smallest split wins ties
-                }
-                best[at(i, j)] = lowest;
-                cut[at(i, j)] = where;
-            }
-        }
-        if (best[at(0, m - 1)] > kU64Max) { delete plan; return MOM_ERR_OVERFLOW; }
-        // preorder read-out of the chosen tree
-        std::vector<std::pair<int, int>> todo{{0, m - 1}};
-        while (!todo.empty()) {
-            auto [lo, hi] = todo.back();
-            todo.pop_back();
-            if (lo == hi) continue;
-            const int s = cut[at(lo, hi)];
-            split_pos.push_back(s);
-            todo.emplace_back(s + 1, hi);
-            todo.emplace_back(lo, s);
-        }
-    }
-    st = finish(plan, d, p, split_pos);
-    if (st != MOM_OK) { delete plan; return st; }
-    *out = plan;
-    return MOM_OK;
+    return guarded([&] { return make_plan(dims, props, n, false, nullptr, out); });
 }
 
 mom_status_t mom_plan_from_splits(const int64_t *dims, const int32_t *props, int32_t n,
@@ -311,29 +430,7 @@ mom_status_t mom_plan_from_splits(const int64_t *dims, const int32_t *props, int
 {
     if (!out) return MOM_ERR_NULL;
     *out = nullptr;
-    mom_status_t st = validate(dims, props, n);
-    if (st != MOM_OK) return st;
-    mom_plan *plan = nullptr;
-    std::vector<int64_t> d;
-    std::vector<int32_t> p;
-    st = start(dims, props, n, &plan, d, p);
-    if (st != MOM_OK) return st;
-    const int m = (int)p.size();
-    std::vector<int32_t> split_pos;
-    if (m > 1) {
-        if (!preorder_splits) { delete plan; return MOM_ERR_NULL; }
-        std::vector<int32_t> position(n, -1);
-        for (int i = 0; i < m; ++i) position[plan->survivors[i]] = i;
-        for (int i = 0; i < m - 1; ++i) {
-            const int32_t s = preorder_splits[i];
-            if (s < 0 || s >= n || position[s] < 0) { delete plan; return MOM_ERR_BAD_SPLITS; }
-            split_pos.push_back(position[s]);
-        }
-    }
-    st = finish(plan, d, p, split_pos);
-    if (st != MOM_OK) { delete plan; return st; }
-    *out = plan;
-    return MOM_OK;
+    return guarded([&] { return make_plan(dims, props, n, true, preorder_splits, out); });
 }
 
 void mom_plan_destroy(mom_plan_t *plan) { delete plan; }
@@ -384,8 +481,11 @@ const char *mom_status_string(mom_status_t status)
     case MOM_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case MOM_ERR_BUFFER_TOO_SMALL: return "host buffer too small";
     case MOM_ERR_BAD_STRIDE: return "stride smaller than the matrix needs";
-    case MOM_ERR_UNSUPPORTED: return "plan not covered by the batched kernel";
+    case MOM_ERR_UNSUPPORTED: return "plan not covered by the kernel (batched: a dimension above 32 or more than 8 factors)";
     case MOM_ERR_HIP: return "HIP runtime error";
+    case MOM_ERR_NOMEM: return "out of host memory";
+    case MOM_ERR_BAD_FLAGS: return "unknown flag bits";
+    case MOM_ERR_NOT_READY: return "first use on this device happened under stream capture: call mom_init before capturing";
     }
     return "unknown status";
 }

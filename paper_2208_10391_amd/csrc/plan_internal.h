@@ -5,6 +5,8 @@
 #include <string>
 #include <vector>
 
+#include "launch_params.h"
+
 namespace mom {
 
 enum : int { kGeneral = 0, kLower = 1, kUpper = 2, kIdentity = 3 };
@@ -34,6 +36,21 @@ struct Temp {
                                // stored dense and only its triangle is ever written or read)
 };
 
+// One kernel launch of the evaluation, laid out at plan time: the evaluator copies `batch`
+// (and `reduce`), fills in the pointers, row strides and alignment flags of its operands and
+// launches.  A launch carries up to kMaxFused independent products of one level; when some of
+// them are cut along k, one slice-sum launch follows.
+struct PlannedLaunch {
+    int shape;                       // TileShape of the product kernel
+    int step[kMaxFused];             // index into mom_plan::steps of batch.prob[i]
+    ProductBatch batch;              // geometry complete; A, B, C, ld*, *_vec patched per call
+    ReduceBatch reduce;              // count == 0: no product of this launch is split
+    int reduce_of[kMaxFused];        // reduce.prob[i] sums the slices of batch.prob[reduce_of[i]]
+    unsigned reduce_grid_x;
+};
+
+constexpr int kBatchedSlots = 8;     // surviving factors the batched kernels hold at once
+
 }  // namespace mom
 
 struct mom_plan {
@@ -53,7 +70,11 @@ struct mom_plan {
     size_t scratch_bytes = 0;
     size_t workspace_bytes = 0;
     std::string text;
-    // batched evaluation: largest dimension and operand-stack depth of the post-order walk
+    std::vector<mom::PlannedLaunch> launches;   // the evaluation, launch by launch
+    // batched evaluation: largest dimension and operand-stack depth of the post-order walk;
+    // product s multiplies LDS slot a_slot[s] by slot b_slot[s] and leaves the result in a_slot[s]
+    // (filled only when the plan has at most kBatchedSlots surviving factors)
     int64_t max_dim = 0;
     int32_t stack_depth = 0;
+    int32_t a_slot[mom::kBatchedSlots] = {}, b_slot[mom::kBatchedSlots] = {};
 };

@@ -19,35 +19,13 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "launch_params.h"
 #include "schedule.h"
 
 namespace mom {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-struct ProductParams {
-    const float *A;
-    const float *B;
-    float *C;              // result, or split-K partial sums (slice s at C + s * slice_stride)
-    int64_t lda, ldb, ldc;
-    int64_t slice_stride;  // elements between split-K slices (0 when split_k == 1)
-    int M, N, K;
-    int pa, pb, pc;
-    int tiles_m, tiles_n, num_tiles, order, paired;
-    int grid;              // workgroups per k-slice
-    int a_vec, b_vec;      // 16-byte loads are legal for A / B (base and row stride aligned)
-    int c_vec;             // 16-byte stores are legal for C
-    int split_k;
-};
-
-// Several independent products in one launch: workgroups [block_end[i-1], block_end[i]) belong
-// to product i, slice-major (split_k slices of `grid` workgroups each).
-struct ProductBatch {
-    int count;
-    int block_end[kMaxFused];
-    ProductParams prob[kMaxFused];
-};
 
 // Is (i, j) inside the structure of property p?  (p is never Identity here.)
 __device__ __forceinline__ bool in_structure(int p, int i, int j)
@@ -560,20 +538,8 @@ __global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const Pro
     }
 }
 
-// Sum of split-K slices: C[i][j] = sum_s P[s][i][j], for up to kMaxFused products at once
-// (blockIdx.y selects the product).  The order of summation is fixed, so results repeat bit
-// for bit from run to run.
-struct ReduceParams {
-    const float *P;
-    float *C;
-    int64_t slice_stride, ldc;
-    int slices, M, N;
-};
-struct ReduceBatch {
-    int count;
-    ReduceParams prob[kMaxFused];
-};
-
+// Sum of split-K slices (ReduceBatch; blockIdx.y selects the product).  The order of summation
+// is fixed, so results repeat bit for bit from run to run.
 // 256 threads = 32 groups of 4 consecutive floats x 8 lanes over the slices: lane g of a group
 // sums slices g, g+8, ... with all its loads in flight, the 8 partial sums meet in LDS.
 __global__ __launch_bounds__(256) void reduce_slices_kernel(const ReduceBatch batch)

@@ -4,6 +4,7 @@
 #pragma once
 #include <algorithm>
 
+#include "launch_params.h"
 #include "plan_internal.h"
 
 namespace mom {
@@ -12,7 +13,6 @@ constexpr int kComputeUnits = 256;
 constexpr int kMinChunksPerSlice = 8;
 constexpr int kSplitTargetWorkgroups = 384;
 constexpr int kMinChunksToSplit = 64;      // below this the second launch costs more than it saves
-constexpr int kMaxFused = 4;          // independent products one launch can carry
 constexpr int kChunk128 = 32, kChunk64 = 32;   // k-chunk (BK) of the 128x128 and of the 64x64 tile shape
 
 // Tile shapes the product kernel is instantiated for.

@@ -273,3 +273,55 @@ def test_evaluation_can_be_captured_in_a_graph_and_replayed():
         torch.cuda.synchronize()
         assert torch.equal(call.out, eager), "replay %d differs" % rep
         assert torch.isfinite(other)
+
+
+FIRST_USE_UNDER_CAPTURE = r"""
+import sys
+import torch
+sys.path.insert(0, %r)
+import paper_2208_10391_amd as mom
+from paper_2208_10391_amd import binding
+a = torch.rand(200, 200, device="cuda")
+b = torch.rand(200, 200, device="cuda")
+plan = mom.mom_chain_plan([200, 200, 200], [0, 0])
+call = mom.bind_chain_eval(plan, [a, b])
+side = torch.cuda.Stream()
+side.wait_stream(torch.cuda.current_stream())
+torch.cuda.synchronize()
+graph = torch.cuda.CUDAGraph()
+status = None
+with torch.cuda.stream(side):
+    with torch.cuda.graph(graph, stream=side):
+        try:
+            call()                      # the very first evaluation of this process: refused
+        except mom.MomError as e:
+            status = binding.STATUS_NAMES[e.status]
+assert status == "MOM_ERR_NOT_READY", status
+mom.mom_init()
+graph2 = torch.cuda.CUDAGraph()
+with torch.cuda.stream(side):
+    with torch.cuda.graph(graph2, stream=side):
+        call()                          # after mom_init the first evaluation may be captured
+torch.cuda.current_stream().wait_stream(side)
+call.out.fill_(float("nan"))
+torch.cuda.synchronize()
+graph2.replay()
+torch.cuda.synchronize()
+ref = (a.double() @ b.double())
+err = float(torch.linalg.norm(call.out.double() - ref) / torch.linalg.norm(ref))
+assert err <= 1e-4, err
+print("capture ok", status, err)
+"""
+
+
+def test_first_evaluation_under_capture_returns_a_status_and_mom_init_makes_it_legal():
+    """In a fresh process (the per-device set-up has not happened yet) a first evaluation on a
+    capturing stream must come back as MOM_ERR_NOT_READY with the capture intact; after
+    mom_init the same call records and replays."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", FIRST_USE_UNDER_CAPTURE % root], capture_output=True, text=True, timeout=240)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "capture ok MOM_ERR_NOT_READY" in r.stdout

@@ -159,6 +159,11 @@ def test_error_paths():
     assert lib.mom_chain_eval(p3.handle, fptr3, None, ctypes.c_void_p(1024), 0, None, 0, 0, None) == code["MOM_ERR_WORKSPACE"]
     assert lib.mom_chain_eval(p3.handle, fptr3, None, ctypes.c_void_p(1024), 0, ctypes.c_void_p(4096), 8, 0, None) == code["MOM_ERR_WORKSPACE"]
     assert lib.mom_chain_eval(p3.handle, fptr3, None, ctypes.c_void_p(1024), 0, ctypes.c_void_p(4100), 1 << 20, 0, None) == code["MOM_ERR_WORKSPACE"]
+    # unknown flag bits are refused, not ignored
+    assert lib.mom_chain_eval(p.handle, fptr, None, ctypes.c_void_p(1024), 0, None, 0, 2, None) == code["MOM_ERR_BAD_FLAGS"]
+    assert lib.mom_chain_eval(p.handle, fptr, None, ctypes.c_void_p(1024), 0, None, 0, 0x80000001, None) == code["MOM_ERR_BAD_FLAGS"]
+    for name in ("MOM_ERR_NOMEM", "MOM_ERR_BAD_FLAGS", "MOM_ERR_NOT_READY"):
+        assert mom.mom_status_string(code[name]) not in ("ok", "unknown status")
     pbig = mom.mom_chain_plan([33, 33, 33], [G, G])
     assert lib.mom_chain_eval_batched(pbig.handle, fptr, None, ctypes.c_void_p(1024), 0, 4, None) == code["MOM_ERR_UNSUPPORTED"]
     assert lib.mom_chain_eval_batched(p.handle, fptr, None, ctypes.c_void_p(1024), 0, -1, None) == code["MOM_ERR_BAD_N"]
