@@ -159,6 +159,24 @@ mom_status_t mom_chain_eval(const mom_plan_t *plan, const float *const *d_factor
                             uint32_t flags, void *stream);
 
 /*
+ * mom_chain_eval for callers that cannot hand over (or allocate) a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments and
+ * behaviour as mom_chain_eval, except that temporaries and k-slices live in an array that is
+ * part of the library's device code: MOM_STATIC_WORKSPACE_BYTES per GPU, held from the moment
+ * the library is loaded on a GPU until the process ends.  The call allocates and frees nothing.
+ *   - A plan with mom_plan_workspace_bytes above MOM_STATIC_WORKSPACE_BYTES is refused with
+ *     MOM_ERR_WORKSPACE and nothing is enqueued.
+ *   - Every call on a GPU shares that GPU's array: calls on ONE stream run in order and are
+ *     safe; calls that may overlap on one GPU (different streams, different threads) race.
+ *   - The array keeps the last call's contents; nothing in it needs to start at zero.
+ *   - The array's address is looked up at the device's one-time set-up (mom_init or the first
+ *     evaluation outside capture), so the capture rule of mom_init applies here as well.
+ */
+#define MOM_STATIC_WORKSPACE_BYTES (64u << 20)
+mom_status_t mom_chain_eval_static(const mom_plan_t *plan, const float *const *d_factors, const int64_t *lds,
+                                   float *d_out, int64_t ld_out, uint32_t flags, void *stream);
+
+/*
  * The same variadic Mul (Sec. 2, "Operations") for many small chains at once: evaluate
  * `batch` independent chains that share one plan (one shape, one property list, hence one
  * parenthesisation by Sec. 2, "Transformations") in ONE kernel launch; each chain is

@@ -16,6 +16,7 @@ MOM_GENERAL, MOM_LOWER_TRI, MOM_UPPER_TRI, MOM_IDENTITY = 0, 1, 2, 3
 MOM_OK = 0
 MOM_OUT_ZERO_FILL_TRIANGLE = 1
 MOM_MAX_FACTORS = 1024
+MOM_STATIC_WORKSPACE_BYTES = 64 << 20
 
 STATUS_NAMES = ["MOM_OK", "MOM_ERR_NULL", "MOM_ERR_BAD_N", "MOM_ERR_BAD_DIM", "MOM_ERR_BAD_PROP",
                 "MOM_ERR_NOT_SQUARE", "MOM_ERR_OVERFLOW", "MOM_ERR_BAD_SPLITS", "MOM_ERR_WORKSPACE",
@@ -24,7 +25,7 @@ STATUS_NAMES = ["MOM_OK", "MOM_ERR_NULL", "MOM_ERR_BAD_N", "MOM_ERR_BAD_DIM", "M
 
 EXPORTS = ["mom_chain_plan", "mom_plan_from_splits", "mom_plan_destroy", "mom_plan_cost_mults",
            "mom_plan_num_products", "mom_plan_result", "mom_plan_string", "mom_plan_splits",
-           "mom_plan_workspace_bytes", "mom_init", "mom_chain_eval", "mom_chain_eval_batched", "mom_probe_mfma_peak",
+           "mom_plan_workspace_bytes", "mom_init", "mom_chain_eval", "mom_chain_eval_static", "mom_chain_eval_batched", "mom_probe_mfma_peak",
            "mom_status_string"]
 
 
@@ -71,6 +72,9 @@ _lib.mom_init.argtypes = []
 _lib.mom_chain_eval.restype = ctypes.c_int
 _lib.mom_chain_eval.argtypes = [ctypes.c_void_p, _vpp, _i64p, ctypes.c_void_p, ctypes.c_int64,
                                 ctypes.c_void_p, ctypes.c_size_t, ctypes.c_uint32, ctypes.c_void_p]
+_lib.mom_chain_eval_static.restype = ctypes.c_int
+_lib.mom_chain_eval_static.argtypes = [ctypes.c_void_p, _vpp, _i64p, ctypes.c_void_p, ctypes.c_int64,
+                                       ctypes.c_uint32, ctypes.c_void_p]
 _lib.mom_chain_eval_batched.restype = ctypes.c_int
 _lib.mom_chain_eval_batched.argtypes = [ctypes.c_void_p, _vpp, _i64p, ctypes.c_void_p, ctypes.c_int64,
                                         ctypes.c_int32, ctypes.c_void_p]
@@ -232,12 +236,13 @@ class BoundEval:
 
 
 def bind_chain_eval(plan: Plan, factors: Sequence[Optional[torch.Tensor]], out: Optional[torch.Tensor] = None,
-                    workspace: Optional[torch.Tensor] = None, flags: int = 0) -> BoundEval:
+                    workspace: Optional[torch.Tensor] = None, flags: int = 0, static: bool = False) -> BoundEval:
     """Checks and marshals the arguments of mom_chain_eval; calling the result enqueues the plan
     on the (current) stream.  factors[t] is a 2-D f32 CUDA tensor with unit column stride (None
     for Identity factors); `out` and `workspace` are allocated with torch when not given (out is
     NOT cleared: a triangular result leaves its other half untouched unless flags has
-    MOM_OUT_ZERO_FILL_TRIANGLE)."""
+    MOM_OUT_ZERO_FILL_TRIANGLE).  With static=True the call is mom_chain_eval_static: no workspace
+    tensor at all, the library's own per-GPU array is used."""
     n = plan.n
     if len(factors) != n:
         raise ValueError("expected %d factors" % n)
@@ -260,12 +265,16 @@ def bind_chain_eval(plan: Plan, factors: Sequence[Optional[torch.Tensor]], out: 
     _check_factor(out, "out")
     if tuple(out.shape) != (rows, cols) or out.stride(1) != 1:
         raise ValueError("out must be %dx%d with unit column stride" % (rows, cols))
+    ld_out = out.stride(0) if rows > 1 else max(out.stride(0), cols)
+    if static:
+        head = (plan.handle, ctypes.cast(ptrs, _vpp), lds, ctypes.c_void_p(out.data_ptr()), ld_out, int(flags))
+        return BoundEval(_lib.mom_chain_eval_static, "mom_chain_eval_static", head, (), out,
+                         (plan, ptrs, lds, tuple(factors)))
     need = mom_plan_workspace_bytes(plan)
     if workspace is None and need > 0:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    ld_out = out.stride(0) if rows > 1 else max(out.stride(0), cols)
     head = (plan.handle, ctypes.cast(ptrs, _vpp), lds, ctypes.c_void_p(out.data_ptr()), ld_out,
             ctypes.c_void_p(ws_ptr), ws_bytes, int(flags))
     return BoundEval(_lib.mom_chain_eval, "mom_chain_eval", head, (), out,
@@ -317,6 +326,13 @@ def bind_chain_eval_batched(plan: Plan, factors: Sequence[Optional[torch.Tensor]
     head = (plan.handle, ctypes.cast(ptrs, _vpp), strides, ctypes.c_void_p(out.data_ptr()), out_stride, batch)
     return BoundEval(_lib.mom_chain_eval_batched, "mom_chain_eval_batched", head, (), out,
                      (plan, ptrs, strides, tuple(factors)))
+
+
+def mom_chain_eval_static(plan: Plan, factors: Sequence[Optional[torch.Tensor]], out: Optional[torch.Tensor] = None,
+                          flags: int = 0, stream=None) -> torch.Tensor:
+    """One call of the C entry point that uses the library's own per-GPU workspace (the output
+    tensor, when not given, is still allocated here, by torch, before the call)."""
+    return bind_chain_eval(plan, factors, out, None, flags, static=True)(stream)
 
 
 def mom_chain_eval_batched(plan: Plan, factors: Sequence[Optional[torch.Tensor]],

@@ -27,6 +27,17 @@ constexpr int kMaxDevices = 64;       // devices whose one-time set-up is rememb
 // stream is being captured, which is why this is not left to the launch itself).
 std::atomic<bool> g_device_ready[kMaxDevices];
 
+// Workspace of mom_chain_eval_static: one array per GPU, part of the loaded code object, held
+// until the process ends.  `scratch` is a host-side stand-in here; its device address on the
+// current GPU comes from hipGetSymbolAddress and is kept per device in g_scratch.
+static __device__ __align__(256) unsigned char scratch[MOM_STATIC_WORKSPACE_BYTES];
+char *g_scratch[kMaxDevices];
+
+hipError_t scratch_address(char **ptr)
+{
+    return hipGetSymbolAddress(reinterpret_cast<void **>(ptr), HIP_SYMBOL(scratch));
+}
+
 hipError_t configure_kernels()
 {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&product_kernel<Tile128>),
@@ -51,7 +62,12 @@ mom_status_t ensure_device_ready(bool have_stream, hipStream_t stream)
         if (cs != hipStreamCaptureStatusNone) return MOM_ERR_NOT_READY;
     }
     if (configure_kernels() != hipSuccess) return MOM_ERR_HIP;
-    if (remembered) g_device_ready[dev].store(true, std::memory_order_release);
+    if (remembered) {
+        char *ptr = nullptr;
+        if (scratch_address(&ptr) != hipSuccess || !ptr) return MOM_ERR_HIP;
+        g_scratch[dev] = ptr;                        // published by the release store below
+        g_device_ready[dev].store(true, std::memory_order_release);
+    }
     return MOM_OK;
 }
 
@@ -200,6 +216,29 @@ extern "C" mom_status_t mom_chain_eval(const mom_plan_t *plan, const float *cons
     st = ensure_device_ready(true, stream);
     if (st != MOM_OK) return st;
     return eval_chain(plan, d_factors, lds, d_out, ld_out, static_cast<char *>(d_workspace), flags, stream);
+}
+
+extern "C" mom_status_t mom_chain_eval_static(const mom_plan_t *plan, const float *const *d_factors, const int64_t *lds,
+                                              float *d_out, int64_t ld_out, uint32_t flags, void *stream_)
+{
+    mom_status_t st = check_eval_arguments(plan, d_factors, lds, d_out, ld_out, flags);
+    if (st != MOM_OK) return st;
+    if (plan->workspace_bytes > (size_t)MOM_STATIC_WORKSPACE_BYTES) return MOM_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    st = ensure_device_ready(true, stream);
+    if (st != MOM_OK) return st;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return MOM_ERR_HIP;
+    char *ws = nullptr;
+    if (dev >= 0 && dev < kMaxDevices) {
+        ws = g_scratch[dev];
+    } else if (scratch_address(&ws) != hipSuccess) {   // a device beyond the remembered ones: ask every time
+        return MOM_ERR_HIP;
+    }
+    if (!ws) return MOM_ERR_HIP;
+    // nothing in the workspace has to start at zero: temporaries are written before they are
+    // read and every k-slice of a split product writes its whole partial tile
+    return eval_chain(plan, d_factors, lds, d_out, ld_out, ws, flags, stream);
 }
 
 extern "C" mom_status_t mom_chain_eval_batched(const mom_plan_t *plan, const float *const *d_factor_bases,
