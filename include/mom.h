@@ -125,6 +125,18 @@ mom_status_t mom_plan_string(const mom_plan_t *plan, char *buf, size_t cap);
 /* Preorder splits (original indices) of the plan; cap entries available in out [host]. */
 mom_status_t mom_plan_splits(const mom_plan_t *plan, int32_t *out, int32_t cap);
 
+/* The i-th binary product (0 <= i < mom_plan_num_products) in evaluation order, i.e. level by
+ * level of the tree: shape[3] = rows, inner dimension, columns; props[3] = properties of the
+ * left operand, the right operand and the result; *mults = its scalar multiplications;
+ * *level = its height in the tree (products of one level are independent).  Any out pointer
+ * may be NULL.  MOM_ERR_BAD_N for an index out of range. */
+mom_status_t mom_plan_product(const mom_plan_t *plan, int32_t i, int64_t *shape, int32_t *props,
+                              uint64_t *mults, int32_t *level);
+
+/* Kernel launches one mom_chain_eval of this plan enqueues (products that share a launch count
+ * once, slice sums count, the optional zero-fill pass does not). */
+int32_t mom_plan_num_launches(const mom_plan_t *plan);
+
 /* Bytes of device workspace mom_chain_eval needs for temporaries and k-slices (may be 0). */
 size_t mom_plan_workspace_bytes(const mom_plan_t *plan);
 

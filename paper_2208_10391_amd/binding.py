@@ -25,7 +25,7 @@ STATUS_NAMES = ["MOM_OK", "MOM_ERR_NULL", "MOM_ERR_BAD_N", "MOM_ERR_BAD_DIM", "M
 
 EXPORTS = ["mom_chain_plan", "mom_plan_from_splits", "mom_plan_destroy", "mom_plan_cost_mults",
            "mom_plan_num_products", "mom_plan_result", "mom_plan_string", "mom_plan_splits",
-           "mom_plan_workspace_bytes", "mom_init", "mom_chain_eval", "mom_chain_eval_static", "mom_chain_eval_batched", "mom_probe_mfma_peak",
+           "mom_plan_product", "mom_plan_num_launches", "mom_plan_workspace_bytes", "mom_init", "mom_chain_eval", "mom_chain_eval_static", "mom_chain_eval_batched", "mom_probe_mfma_peak",
            "mom_status_string"]
 
 
@@ -65,6 +65,10 @@ _lib.mom_plan_string.restype = ctypes.c_int
 _lib.mom_plan_string.argtypes = [ctypes.c_void_p, ctypes.c_char_p, ctypes.c_size_t]
 _lib.mom_plan_splits.restype = ctypes.c_int
 _lib.mom_plan_splits.argtypes = [ctypes.c_void_p, _i32p, ctypes.c_int32]
+_lib.mom_plan_product.restype = ctypes.c_int
+_lib.mom_plan_product.argtypes = [ctypes.c_void_p, ctypes.c_int32, _i64p, _i32p, ctypes.POINTER(ctypes.c_uint64), _i32p]
+_lib.mom_plan_num_launches.restype = ctypes.c_int32
+_lib.mom_plan_num_launches.argtypes = [ctypes.c_void_p]
 _lib.mom_plan_workspace_bytes.restype = ctypes.c_size_t
 _lib.mom_plan_workspace_bytes.argtypes = [ctypes.c_void_p]
 _lib.mom_init.restype = ctypes.c_int
@@ -194,6 +198,22 @@ def mom_plan_splits(plan: Plan) -> List[int]:
     if st != MOM_OK:
         raise MomError(st, "mom_plan_splits")
     return [int(out[i]) for i in range(k)]
+
+
+def mom_plan_product(plan: Plan, i: int) -> dict:
+    """The i-th binary product in evaluation order: shape (m, k, n), props (left, right, result),
+    mults, level."""
+    shape, props = (ctypes.c_int64 * 3)(), (ctypes.c_int32 * 3)()
+    mults, level = ctypes.c_uint64(), ctypes.c_int32()
+    st = _lib.mom_plan_product(plan.handle, int(i), shape, props, ctypes.byref(mults), ctypes.byref(level))
+    if st != MOM_OK:
+        raise MomError(st, "mom_plan_product")
+    return {"shape": tuple(int(x) for x in shape), "props": tuple(int(x) for x in props),
+            "mults": int(mults.value), "level": int(level.value)}
+
+
+def mom_plan_num_launches(plan: Plan) -> int:
+    return int(_lib.mom_plan_num_launches(plan.handle))
 
 
 def mom_plan_workspace_bytes(plan: Plan) -> int:

@@ -465,6 +465,28 @@ mom_status_t mom_plan_splits(const mom_plan_t *plan, int32_t *out, int32_t cap)
     return MOM_OK;
 }
 
+mom_status_t mom_plan_product(const mom_plan_t *plan, int32_t i, int64_t *shape, int32_t *props,
+                              uint64_t *mults, int32_t *level)
+{
+    if (!plan) return MOM_ERR_NULL;
+    if (i < 0 || i >= (int32_t)plan->order.size()) return MOM_ERR_BAD_N;
+    const mom::ProductStep &st = plan->steps[plan->order[i]];
+    if (shape) { shape[0] = st.m; shape[1] = st.k; shape[2] = st.n; }
+    if (props) { props[0] = st.pa; props[1] = st.pb; props[2] = st.pc; }
+    if (mults) *mults = st.mults;
+    if (level) *level = st.level;
+    return MOM_OK;
+}
+
+int32_t mom_plan_num_launches(const mom_plan_t *plan)
+{
+    if (!plan) return 0;
+    if (plan->steps.empty()) return 1;                    // identity write or copy
+    int32_t n = 0;
+    for (const mom::PlannedLaunch &pl : plan->launches) n += 1 + (pl.reduce.count > 0 ? 1 : 0);
+    return n;
+}
+
 size_t mom_plan_workspace_bytes(const mom_plan_t *plan) { return plan ? plan->workspace_bytes : 0; }
 
 const char *mom_status_string(mom_status_t status)
