@@ -34,12 +34,14 @@ _lib.oracle_plan_bruteforce.argtypes = [ctypes.c_int32, _i64p, _i32p, ctypes.c_i
 _lib.oracle_tree_cost.restype = ctypes.c_int
 _lib.oracle_tree_cost.argtypes = [ctypes.c_int32, _i64p, _i32p, _i32p,
                                   ctypes.POINTER(ctypes.c_uint64), _i32p]
-_lib.oracle_eval_dense.restype = ctypes.c_int
-_lib.oracle_eval_dense.argtypes = [ctypes.c_int32, _i64p, _i32p, _fpp, _f64p]
-_lib.oracle_eval_rows.restype = ctypes.c_int
-_lib.oracle_eval_rows.argtypes = [ctypes.c_int32, _i64p, _i32p, _fpp, ctypes.c_int32, _i64p, _f64p]
-_lib.oracle_eval_plan.restype = ctypes.c_int
-_lib.oracle_eval_plan.argtypes = [ctypes.c_int32, _i64p, _i32p, _fpp, _i32p, _f64p, _i32p]
+_lib.oracle_eval_dense_t.restype = ctypes.c_int
+_lib.oracle_eval_dense_t.argtypes = [ctypes.c_int32, _i64p, _i32p, _i32p, _fpp, _f64p]
+_lib.oracle_eval_rows_t.restype = ctypes.c_int
+_lib.oracle_eval_rows_t.argtypes = [ctypes.c_int32, _i64p, _i32p, _i32p, _fpp, ctypes.c_int32, _i64p, _f64p]
+_lib.oracle_eval_plan_t.restype = ctypes.c_int
+_lib.oracle_eval_plan_t.argtypes = [ctypes.c_int32, _i64p, _i32p, _i32p, _fpp, _i32p, _f64p, _i32p]
+_lib.oracle_transposed_property.restype = ctypes.c_int32
+_lib.oracle_transposed_property.argtypes = [ctypes.c_int32]
 _lib.oracle_max_threads.restype = ctypes.c_int
 
 
@@ -51,8 +53,31 @@ def _props(props) -> np.ndarray:
     return np.ascontiguousarray(np.asarray(props, dtype=np.int32))
 
 
-def _factor_ptrs(dims: np.ndarray, props: np.ndarray, factors: Sequence[Optional[np.ndarray]]):
-    """Host f32 row-major buffers -> array of pointers (Identity entries may be None)."""
+def _trans(trans, n: int):
+    """None -> NULL pointer (no factor transposed), else n flags."""
+    if trans is None:
+        return None, None
+    t = np.ascontiguousarray(np.asarray([1 if x else 0 for x in trans], dtype=np.int32))
+    assert len(t) == n
+    return t.ctypes.data_as(_i32p), t
+
+
+def transposed_property(prop: int) -> int:
+    """Property of the transpose: lowerTri(A) -> upperTri(A^T) and back (the inference rule of
+    Sec. 2, Transformations); general and Identity are unchanged."""
+    return int(_lib.oracle_transposed_property(int(prop)))
+
+
+def chain_props(props, trans=None) -> List[int]:
+    """Properties the factors have inside the chain: a transposed factor's stored property mirrored."""
+    if trans is None:
+        return [int(p) for p in props]
+    return [transposed_property(p) if t else int(p) for p, t in zip(props, trans)]
+
+
+def _factor_ptrs(dims: np.ndarray, props: np.ndarray, factors: Sequence[Optional[np.ndarray]], trans=None):
+    """Host f32 row-major buffers -> array of pointers (Identity entries may be None).  The buffer
+    of a transposed factor holds the dims[t+1] x dims[t] matrix whose transpose enters the chain."""
     keep = []
     ptrs = (ctypes.c_void_p * len(props))()
     for t, p in enumerate(props):
@@ -63,8 +88,9 @@ def _factor_ptrs(dims: np.ndarray, props: np.ndarray, factors: Sequence[Optional
             ptrs[t] = None
             continue
         a = np.ascontiguousarray(np.asarray(f, dtype=np.float32))
-        if a.shape != (dims[t], dims[t + 1]):
-            raise ValueError("factor %d has shape %s, expected %s" % (t, a.shape, (dims[t], dims[t + 1])))
+        want = (dims[t + 1], dims[t]) if (trans is not None and trans[t]) else (dims[t], dims[t + 1])
+        if a.shape != want:
+            raise ValueError("factor %d has shape %s, expected %s" % (t, a.shape, want))
         keep.append(a)
         ptrs[t] = a.ctypes.data
     return ptrs, keep
@@ -80,14 +106,16 @@ def count_mults(m: int, k: int, n: int, pX: int, pY: int) -> int:
     return int(_lib.oracle_count_mults(m, k, n, pX, pY))
 
 
-def plan_bruteforce(dims, props, elide: bool = True) -> dict:
+def plan_bruteforce(dims, props, elide: bool = True, trans=None) -> dict:
     """Minimum-multiplication parenthesisation by enumerating every binary tree
     (Sec. 2: variadic Mul -> binary products with an optimal parenthesisation; matrix-chain
     reordering generalised to properties; identity simplification).
 
     Returns cost, n_eff, splits (preorder, original factor indices), result_prop, num_trees.
-    Ties go to the lexicographically smallest preorder split list."""
-    d, p = _dims(dims), _props(props)
+    Ties go to the lexicographically smallest preorder split list.  With `trans`, props are the
+    stored properties and the search runs on the properties the factors have inside the chain
+    (Table 1 Transpose; Sec. 2 Transformations: lowerTri(A) -> upperTri(A^T))."""
+    d, p = _dims(dims), _props(chain_props(props, trans))
     n = len(p)
     assert len(d) == n + 1
     cost = ctypes.c_uint64()
@@ -106,9 +134,9 @@ def plan_bruteforce(dims, props, elide: bool = True) -> dict:
             "result_prop": int(rprop.value), "num_trees": int(ntrees.value)}
 
 
-def tree_cost(dims, props, splits) -> Tuple[int, int]:
+def tree_cost(dims, props, splits, trans=None) -> Tuple[int, int]:
     """(cost in scalar multiplications, result property) of one given tree."""
-    d, p = _dims(dims), _props(props)
+    d, p = _dims(dims), _props(chain_props(props, trans))
     s = np.ascontiguousarray(np.asarray(list(splits) + [0], dtype=np.int32))
     cost = ctypes.c_uint64()
     rprop = ctypes.c_int32()
@@ -148,46 +176,51 @@ def left_to_right_splits(props) -> List[int]:
     return [surv[i] for i in range(len(surv) - 2, -1, -1)]
 
 
-def eval_dense(dims, props, factors) -> np.ndarray:
+def eval_dense(dims, props, factors, trans=None) -> np.ndarray:
     """The chain product by its plain definition: dense f64 triple loops, left to right,
-    Identity materialised as eye, no property logic (Sec. 2, bufferization and Types)."""
+    Identity materialised as eye, no property logic (Sec. 2, bufferization and Types).
+    trans[t] true: factors[t] is the dims[t+1] x dims[t] buffer whose transpose is factor t
+    (Table 1, Transpose)."""
     d, p = _dims(dims), _props(props)
-    ptrs, keep = _factor_ptrs(d, p, factors)
+    ptrs, keep = _factor_ptrs(d, p, factors, trans)
+    tp, tkeep = _trans(trans, len(p))
     out = np.zeros((d[0], d[-1]), dtype=np.float64)
-    rc = _lib.oracle_eval_dense(len(p), d.ctypes.data_as(_i64p), p.ctypes.data_as(_i32p),
-                                ctypes.cast(ptrs, _fpp), out.ctypes.data_as(_f64p))
+    rc = _lib.oracle_eval_dense_t(len(p), d.ctypes.data_as(_i64p), p.ctypes.data_as(_i32p), tp,
+                                  ctypes.cast(ptrs, _fpp), out.ctypes.data_as(_f64p))
     if rc != 0:
         raise ValueError("oracle_eval_dense failed: %d" % rc)
     del keep
     return out
 
 
-def eval_rows(dims, props, factors, rows) -> np.ndarray:
+def eval_rows(dims, props, factors, rows, trans=None) -> np.ndarray:
     """Selected rows of the dense chain product: A_0[r,:] pushed through the other factors."""
     d, p = _dims(dims), _props(props)
-    ptrs, keep = _factor_ptrs(d, p, factors)
+    ptrs, keep = _factor_ptrs(d, p, factors, trans)
+    tp, tkeep = _trans(trans, len(p))
     r = np.ascontiguousarray(np.asarray(rows, dtype=np.int64))
     out = np.zeros((len(r), d[-1]), dtype=np.float64)
-    rc = _lib.oracle_eval_rows(len(p), d.ctypes.data_as(_i64p), p.ctypes.data_as(_i32p),
-                               ctypes.cast(ptrs, _fpp), len(r), r.ctypes.data_as(_i64p),
-                               out.ctypes.data_as(_f64p))
+    rc = _lib.oracle_eval_rows_t(len(p), d.ctypes.data_as(_i64p), p.ctypes.data_as(_i32p), tp,
+                                 ctypes.cast(ptrs, _fpp), len(r), r.ctypes.data_as(_i64p),
+                                 out.ctypes.data_as(_f64p))
     if rc != 0:
         raise ValueError("oracle_eval_rows failed: %d" % rc)
     del keep
     return out
 
 
-def eval_plan(dims, props, factors, splits) -> Tuple[np.ndarray, int]:
+def eval_plan(dims, props, factors, splits, trans=None) -> Tuple[np.ndarray, int]:
     """Evaluate along a given tree with loops restricted by the operand properties, f64.
-    Returns (dense result, result property)."""
+    Returns (dense result, result property).  With `trans`, props describe the stored matrices."""
     d, p = _dims(dims), _props(props)
-    ptrs, keep = _factor_ptrs(d, p, factors)
+    ptrs, keep = _factor_ptrs(d, p, factors, trans)
+    tp, tkeep = _trans(trans, len(p))
     s = np.ascontiguousarray(np.asarray(list(splits) + [0], dtype=np.int32))
     out = np.zeros((d[0], d[-1]), dtype=np.float64)
     rprop = ctypes.c_int32()
-    rc = _lib.oracle_eval_plan(len(p), d.ctypes.data_as(_i64p), p.ctypes.data_as(_i32p),
-                               ctypes.cast(ptrs, _fpp), s.ctypes.data_as(_i32p),
-                               out.ctypes.data_as(_f64p), ctypes.byref(rprop))
+    rc = _lib.oracle_eval_plan_t(len(p), d.ctypes.data_as(_i64p), p.ctypes.data_as(_i32p), tp,
+                                 ctypes.cast(ptrs, _fpp), s.ctypes.data_as(_i32p),
+                                 out.ctypes.data_as(_f64p), ctypes.byref(rprop))
     if rc != 0:
         raise ValueError("malformed split list")
     del keep

@@ -13,6 +13,9 @@
  *   - memory of a triangular matrix is a plain dense row-major buffer whose
  *     other half holds zeros; the diagonal is stored             [Sec. 2, bufferization]
  *   - Identity is square with ones on the diagonal, A*I = A, I*I = I  [Sec. 2, Types]
+ *   - a factor may enter the chain transposed; the transpose of a lowerTri
+ *     matrix is upperTri and vice versa     [Table 1 "Transpose"; Sec. 2,
+ *     "Transformations", the inference rule printed there]
  *   - the variadic product is rewritten into binary products whose
  *     parenthesisation minimises the number of scalar multiplications, taking
  *     the properties of operands and intermediates into account
@@ -24,7 +27,9 @@
  * fill value 1 (closed form i-j+1), the Sec. 4 chain 800x1100x900x1200x100 and its
  * two parenthesisations, numpy.matmul in f64 on general chains, counted
  * multiplications against the closed-form costs, identity rules bit-exactly,
- * structure invariants, agreement of every parenthesisation on tiny inputs.
+ * structure invariants, agreement of every parenthesisation on tiny inputs;
+ * transposed factors: (A*B)^T = B^T * A^T and explicit .T chains against numpy,
+ * lowerTri^T is upperTri, costs and plans equal those of the mirrored chain.
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -70,6 +75,17 @@ static int product_property(int pX, int pY)
     if (pY == P_IDENTITY) return pX;
     if (pX == pY && (pX == P_LOWER || pX == P_UPPER)) return pX;
     return P_GENERAL;
+}
+
+/* Property of the transpose of a matrix with property p: the mirror image of
+ * its structure, lowerTri(A) -> upperTri(A^T) and back; general, Identity
+ * stay what they are.  [Sec. 2, Transformations: the inference rule printed
+ * there; Table 1, Transpose]                                               */
+int32_t oracle_transposed_property(int32_t p)
+{
+    if (p == P_LOWER) return P_UPPER;
+    if (p == P_UPPER) return P_LOWER;
+    return p;
 }
 
 typedef unsigned __int128 u128;
@@ -264,10 +280,14 @@ done:
 
 /* Entry (i,j) of factor t, promoted to double.  An Identity factor has no   */
 /* buffer: it is the matrix with ones on the diagonal [Sec. 2, Types].       */
+/* With trans[t] != 0 the chain holds the TRANSPOSE of the stored matrix      */
+/* [Table 1, Transpose]: the buffer is the dims[t+1] x dims[t] matrix S,     */
+/* row-major, and entry (i,j) of the factor is S[j][i].                      */
 static double factor_entry(const float *const *factors, const int64_t *dims, const int32_t *props,
-                           int t, int64_t i, int64_t j)
+                           const int32_t *trans, int t, int64_t i, int64_t j)
 {
     if (props[t] == P_IDENTITY) return i == j ? 1.0 : 0.0;
+    if (trans && trans[t]) return (double)factors[t][j * dims[t] + i];
     return (double)factors[t][i * dims[t + 1] + j];
 }
 
@@ -278,21 +298,21 @@ static double factor_entry(const float *const *factors, const int64_t *dims, con
  * right with the textbook triple loop  C[i][j] = sum_k A[i][k] * B[k][j].
  * No property logic.  out: dims[0] x dims[n] doubles, row-major.
  */
-int oracle_eval_dense(int32_t n, const int64_t *dims, const int32_t *props,
-                      const float *const *factors, double *out)
+int oracle_eval_dense_t(int32_t n, const int64_t *dims, const int32_t *props, const int32_t *trans,
+                        const float *const *factors, double *out)
 {
     if (n <= 0) return 1;
     int64_t rows = dims[0], cols = dims[1];
     double *acc = (double *)malloc(sizeof(double) * rows * cols);
     for (int64_t i = 0; i < rows; ++i)
         for (int64_t j = 0; j < cols; ++j)
-            acc[i * cols + j] = factor_entry(factors, dims, props, 0, i, j);
+            acc[i * cols + j] = factor_entry(factors, dims, props, trans, 0, i, j);
     for (int t = 1; t < n; ++t) {
         int64_t k = dims[t], nc = dims[t + 1];
         double *b = (double *)malloc(sizeof(double) * k * nc);
         for (int64_t i = 0; i < k; ++i)
             for (int64_t j = 0; j < nc; ++j)
-                b[i * nc + j] = factor_entry(factors, dims, props, t, i, j);
+                b[i * nc + j] = factor_entry(factors, dims, props, trans, t, i, j);
         double *c = (double *)calloc((size_t)(rows * nc), sizeof(double));
         #pragma omp parallel for schedule(static)
         for (int64_t i = 0; i < rows; ++i)
@@ -309,6 +329,12 @@ int oracle_eval_dense(int32_t n, const int64_t *dims, const int32_t *props,
     return 0;
 }
 
+int oracle_eval_dense(int32_t n, const int64_t *dims, const int32_t *props,
+                      const float *const *factors, double *out)
+{
+    return oracle_eval_dense_t(n, dims, props, NULL, factors, out);
+}
+
 /*
  * Selected rows of the chain product, for sizes where the whole product is
  * out of reach on a CPU: row r of A_0*A_1*...*A_{n-1} is the row vector
@@ -316,8 +342,8 @@ int oracle_eval_dense(int32_t n, const int64_t *dims, const int32_t *props,
  * w[j] = sum_k v[k] * A_t[k][j].  Same plain definition, no property logic.
  * out: nrows x dims[n] doubles.
  */
-int oracle_eval_rows(int32_t n, const int64_t *dims, const int32_t *props,
-                     const float *const *factors, int32_t nrows, const int64_t *row_idx, double *out)
+int oracle_eval_rows_t(int32_t n, const int64_t *dims, const int32_t *props, const int32_t *trans,
+                       const float *const *factors, int32_t nrows, const int64_t *row_idx, double *out)
 {
     if (n <= 0) return 1;
     int64_t widest = 0;
@@ -327,14 +353,14 @@ int oracle_eval_rows(int32_t n, const int64_t *dims, const int32_t *props,
         double *v = (double *)malloc(sizeof(double) * widest);
         double *w = (double *)malloc(sizeof(double) * widest);
         for (int64_t j = 0; j < dims[1]; ++j)
-            v[j] = factor_entry(factors, dims, props, 0, row_idx[r], j);
+            v[j] = factor_entry(factors, dims, props, trans, 0, row_idx[r], j);
         for (int t = 1; t < n; ++t) {
             int64_t k = dims[t], nc = dims[t + 1];
             for (int64_t j = 0; j < nc; ++j) w[j] = 0.0;
             for (int64_t kk = 0; kk < k; ++kk) {
                 double a = v[kk];
                 for (int64_t j = 0; j < nc; ++j)
-                    w[j] += a * factor_entry(factors, dims, props, t, kk, j);
+                    w[j] += a * factor_entry(factors, dims, props, trans, t, kk, j);
             }
             double *tmp = v; v = w; w = tmp;
         }
@@ -342,6 +368,12 @@ int oracle_eval_rows(int32_t n, const int64_t *dims, const int32_t *props,
         free(v); free(w);
     }
     return 0;
+}
+
+int oracle_eval_rows(int32_t n, const int64_t *dims, const int32_t *props,
+                     const float *const *factors, int32_t nrows, const int64_t *row_idx, double *out)
+{
+    return oracle_eval_rows_t(n, dims, props, NULL, factors, nrows, row_idx, out);
 }
 
 /* ------------------------------------------------------------------------ */
@@ -364,7 +396,10 @@ static void j_range(int prop, int64_t t, int64_t n, int64_t *lo, int64_t *hi)   
     if (prop == P_UPPER) *lo = t;
 }
 
-static dmat_t eval_tree(const int64_t *d, const int32_t *p, const float *const *f,
+/* p holds the properties the factors have INSIDE the chain (a transposed     */
+/* factor's property already mirrored); tr says which buffers hold the       */
+/* transpose of their factor.                                                */
+static dmat_t eval_tree(const int64_t *d, const int32_t *p, const int32_t *tr, const float *const *f,
                         int lo, int hi, const int32_t *splits, int *pos)
 {
     dmat_t r;
@@ -374,12 +409,13 @@ static dmat_t eval_tree(const int64_t *d, const int32_t *p, const float *const *
         for (int64_t i = 0; i < r.rows; ++i)
             for (int64_t j = 0; j < r.cols; ++j)
                 if (structurally_nonzero(r.prop, i, j))
-                    r.a[i * r.cols + j] = (double)f[lo][i * r.cols + j];
+                    r.a[i * r.cols + j] = tr[lo] ? (double)f[lo][j * r.rows + i]
+                                                 : (double)f[lo][i * r.cols + j];
         return r;
     }
     int s = splits[(*pos)++];
-    dmat_t X = eval_tree(d, p, f, lo, s, splits, pos);
-    dmat_t Y = eval_tree(d, p, f, s + 1, hi, splits, pos);
+    dmat_t X = eval_tree(d, p, tr, f, lo, s, splits, pos);
+    dmat_t Y = eval_tree(d, p, tr, f, s + 1, hi, splits, pos);
     r.rows = X.rows; r.cols = Y.cols; r.prop = product_property(X.prop, Y.prop);
     r.a = (double *)calloc((size_t)(r.rows * r.cols), sizeof(double));
     int64_t K = X.cols, N = Y.cols;
@@ -401,28 +437,35 @@ static dmat_t eval_tree(const int64_t *d, const int32_t *p, const float *const *
 
 /*
  * Evaluate the chain along the tree `splits` (preorder, ORIGINAL factor
- * indices, over the chain with Identity factors removed).  out receives the
+ * indices, over the chain with Identity factors removed).  trans (may be
+ * NULL): which factors enter the chain transposed [Table 1, Transpose].  out receives the
  * dense dims[0] x dims[n] result (zeros outside the triangle of a triangular
  * result; the identity matrix when every factor is an Identity).
  * Returns 0, or 2 for a malformed split list.
  */
-int oracle_eval_plan(int32_t n, const int64_t *dims, const int32_t *props,
-                     const float *const *factors, const int32_t *splits,
-                     double *out, int32_t *result_prop)
+int oracle_eval_plan_t(int32_t n, const int64_t *dims, const int32_t *props, const int32_t *trans,
+                       const float *const *factors, const int32_t *splits,
+                       double *out, int32_t *result_prop)
 {
+    /* props describe the STORED matrices; inside the chain a transposed factor
+     * carries the mirrored property [Sec. 2, Transformations]                */
+    int32_t *eff = (int32_t *)malloc(sizeof(int32_t) * (n > 0 ? n : 1));
+    for (int i = 0; i < n; ++i)
+        eff[i] = (trans && trans[i]) ? oracle_transposed_property(props[i]) : props[i];
     uint64_t cost; int32_t rp;
-    int rc = oracle_tree_cost(n, dims, props, splits, &cost, &rp);
-    if (rc == 2) return 2;
+    int rc = oracle_tree_cost(n, dims, eff, splits, &cost, &rp);
+    if (rc == 2) { free(eff); return 2; }
     *result_prop = rp;
     int64_t *d = (int64_t *)malloc(sizeof(int64_t) * (n + 1));
     int32_t *p = (int32_t *)malloc(sizeof(int32_t) * n);
+    int32_t *tr = (int32_t *)malloc(sizeof(int32_t) * n);
     const float **f = (const float **)malloc(sizeof(float *) * n);
     int32_t *where = (int32_t *)malloc(sizeof(int32_t) * n);
     int m = 0;
     for (int i = 0; i < n; ++i) {
         where[i] = -1;
         if (props[i] == P_IDENTITY) continue;
-        d[m] = dims[i]; p[m] = props[i]; f[m] = factors[i]; where[i] = m; ++m;
+        d[m] = dims[i]; p[m] = eff[i]; tr[m] = (trans && trans[i]) ? 1 : 0; f[m] = factors[i]; where[i] = m; ++m;
     }
     d[m] = dims[n];
     if (m == 0) {
@@ -433,12 +476,19 @@ int oracle_eval_plan(int32_t n, const int64_t *dims, const int32_t *props,
         int32_t *s = (int32_t *)malloc(sizeof(int32_t) * m);
         for (int i = 0; i + 1 < m; ++i) s[i] = where[splits[i]];
         int pos = 0;
-        dmat_t r = eval_tree(d, p, f, 0, m - 1, s, &pos);
+        dmat_t r = eval_tree(d, p, tr, f, 0, m - 1, s, &pos);
         memcpy(out, r.a, sizeof(double) * r.rows * r.cols);
         free(r.a); free(s);
     }
-    free(d); free(p); free((void *)f); free(where);
+    free(d); free(p); free(tr); free((void *)f); free(where); free(eff);
     return 0;
+}
+
+int oracle_eval_plan(int32_t n, const int64_t *dims, const int32_t *props,
+                     const float *const *factors, const int32_t *splits,
+                     double *out, int32_t *result_prop)
+{
+    return oracle_eval_plan_t(n, dims, props, NULL, factors, splits, out, result_prop);
 }
 
 int oracle_max_threads(void)

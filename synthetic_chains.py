@@ -66,11 +66,17 @@ def make_factor(rows: int, cols: int, prop: int, seed: int, batch: int = 0) -> O
 
 
 def make_chain(dims: Sequence[int], props: Sequence[int], seed_family: int,
-               batch: int = 0) -> List[Optional[torch.Tensor]]:
-    """All factors of one chain; factor t is drawn from seed 1000*seed_family + t."""
+               batch: int = 0, trans: Optional[Sequence[int]] = None) -> List[Optional[torch.Tensor]]:
+    """All factors of one chain; factor t is drawn from seed 1000*seed_family + t.  Where
+    trans[t] is set the chain holds the transpose of what is stored (Table 1, Transpose): the
+    buffer drawn is the dims[t+1] x dims[t] matrix, and props[t] is the property of that
+    stored matrix."""
     assert len(dims) == len(props) + 1
-    return [make_factor(dims[t], dims[t + 1], props[t], factor_seed(seed_family, t), batch)
-            for t in range(len(props))]
+    out = []
+    for t in range(len(props)):
+        r, c = (dims[t + 1], dims[t]) if (trans is not None and trans[t]) else (dims[t], dims[t + 1])
+        out.append(make_factor(r, c, props[t], factor_seed(seed_family, t), batch))
+    return out
 
 
 def make_config(name: str) -> List[Optional[torch.Tensor]]:
