@@ -35,6 +35,7 @@ WORKLOADS = {
     "mixed5_tri_intermediate": ("mixed5", [2, 0, 3]),       # forms L1*L2 as a lowerTri temporary
     "mixed5_left_to_right": ("mixed5", [3, 2, 0]),
     "trmm4096": ("trmm4096", None),
+    "trmm4096_transposed": ("trmm4096_transposed", None),   # both operands read from transposed buffers
     "general5": ("general5", None),
     "general5_left_to_right": ("general5", [3, 2, 1, 0]),   # the tree Sec. 4 would start from
     "batched32": ("batched32", None),
@@ -42,7 +43,7 @@ WORKLOADS = {
     # that the HBM counters are calibrated against
     "copy8192": ("copy8192", None),
 }
-SIDE_WORKLOADS = ["trmm4096", "general5", "general5_left_to_right", "mixed5_tri_intermediate",
+SIDE_WORKLOADS = ["trmm4096", "trmm4096_transposed", "general5", "general5_left_to_right", "mixed5_tri_intermediate",
                   "mixed5_left_to_right", "batched32"]
 
 sc.CONFIGS["copy8192"] = sc.ChainConfig("copy8192", 9, (8192, 8192), (sc.GENERAL,))
@@ -52,7 +53,8 @@ def kernel_sources_digest():
     import hashlib
     h = hashlib.sha256()
     # what decides the kernels and their launch geometry; the planner's host code is left out
-    names = ("batched_kernel.h", "eval.hip", "launch_params.h", "product_kernel.h", "schedule.h")
+    names = ("batched_kernel.h", "eval.hip", "launch_params.h", "product_kernel.h", "product_variant.h",
+             "schedule.h", "small_kernels.h")
     for path in (os.path.join(ROOT, "paper_2208_10391_amd", "csrc", n) for n in names):
         with open(path, "rb") as f:
             h.update(os.path.basename(path).encode() + b"\0" + f.read())
@@ -88,7 +90,7 @@ def algorithmic_bytes(cfg, result_prop):
     total = 0
     for t, p in enumerate(cfg.props):
         if p != sc.IDENTITY:
-            total += structural_bytes(cfg.dims[t], cfg.dims[t + 1], p)
+            total += structural_bytes(cfg.dims[t], cfg.dims[t + 1], p)      # (a transpose has as many)
     total += structural_bytes(cfg.dims[0], cfg.dims[-1], result_prop)
     return total * max(cfg.batch, 1)
 
@@ -140,8 +142,9 @@ def measure(mom, workload, steps, warmup, want_cpu_baseline):
     cfg_name, splits = WORKLOADS[workload]
     cfg = sc.CONFIGS[cfg_name]
     host = sc.make_config(cfg_name)
-    best = mom.mom_chain_plan(cfg.dims, cfg.props)                 # the planner's tree
-    plan = best if splits is None else mom.mom_plan_from_splits(cfg.dims, cfg.props, splits)
+    trans = list(cfg.trans) if cfg.trans else None
+    best = mom.mom_chain_plan(cfg.dims, cfg.props, trans=trans)    # the planner's tree
+    plan = best if splits is None else mom.mom_plan_from_splits(cfg.dims, cfg.props, splits, trans=trans)
     dev = [None if f is None else f.cuda() for f in host]
     rows, cols, rprop = plan.result
     # arguments are marshalled once; a step is one call of the C entry point
@@ -157,7 +160,7 @@ def measure(mom, workload, steps, warmup, want_cpu_baseline):
     # non-zero half of 2*n^3, as its workload definition says); tree_flop: what THIS tree
     # executes usefully, which is more for a forced tree
     batch = max(cfg.batch, 1)
-    useful = float(cfg.dims[0]) ** 3 if workload == "trmm4096" else 2.0 * best.cost_mults * batch
+    useful = float(cfg.dims[0]) ** 3 if cfg_name.startswith("trmm4096") else 2.0 * best.cost_mults * batch
     tree_flop = useful if splits is None else 2.0 * plan.cost_mults * batch
 
     settle_ms, settle_windows, _ = settle(step)
@@ -214,11 +217,11 @@ def measure(mom, workload, steps, warmup, want_cpu_baseline):
         if splits is not None:                    # against the work the planner's tree would need
             rec["roofline"]["frac_vs_planned_tree"] = useful / (dev_ms * 1e-3) / 1e12 / F32_MFMA_PEAK_TFLOPS
     if want_cpu_baseline:
-        rec["cpu_baseline"] = cpu_baseline(cfg, host, plan.splits, tree_flop)
+        rec["cpu_baseline"] = cpu_baseline(cfg, host, plan.splits, tree_flop, trans)
     return rec, cfg, plan
 
 
-def cpu_baseline(cfg, host, splits, flop):
+def cpu_baseline(cfg, host, splits, flop, trans=None):
     """The oracle as it stands, timed on the host cores along the same tree (f64, loops
     restricted by the properties).  For the batched workload a bounded number of chains."""
     import numpy as np
@@ -228,7 +231,7 @@ def cpu_baseline(cfg, host, splits, flop):
         chains = min(cfg.batch, 512)
         t0 = time.perf_counter()
         for b in range(chains):
-            oracle.eval_plan(cfg.dims, cfg.props, [None if f is None else f[b] for f in np_f], splits)
+            oracle.eval_plan(cfg.dims, cfg.props, [None if f is None else f[b] for f in np_f], splits, trans=trans)
         dt = time.perf_counter() - t0
         done = flop * chains / cfg.batch
         sample = "%d of %d chains, same tree" % (chains, cfg.batch)
@@ -236,7 +239,7 @@ def cpu_baseline(cfg, host, splits, flop):
         # bound the work to roughly 250 GFLOP by narrowing the last factor to a column panel
         full_cols = cfg.dims[-1]
         cols = full_cols
-        while flop * cols / full_cols > 2.5e11 and cols > 64 and cfg.props[-1] == sc.GENERAL:
+        while flop * cols / full_cols > 2.5e11 and cols > 64 and cfg.props[-1] == sc.GENERAL and not trans:
             cols //= 2
         dims = list(cfg.dims[:-1]) + [cols]
         if cols != full_cols:
@@ -248,7 +251,7 @@ def cpu_baseline(cfg, host, splits, flop):
             done = flop
             sample = "the whole workload, same tree, one run"
         t0 = time.perf_counter()
-        oracle.eval_plan(dims, cfg.props, np_f, splits)
+        oracle.eval_plan(dims, cfg.props, np_f, splits, trans=trans)
         dt = time.perf_counter() - t0
     return {"value": done / dt / 1e9, "unit": "GFLOP/s", "cores": oracle.max_threads(), "kind": "oracle",
             "sample": sample, "seconds": dt}

@@ -66,8 +66,9 @@ typedef enum {
     MOM_ERR_HIP,               /* the HIP runtime rejected a call */
     MOM_ERR_NOMEM,             /* host memory for a plan could not be allocated */
     MOM_ERR_BAD_FLAGS,         /* flag bits that this version does not define */
-    MOM_ERR_NOT_READY          /* first evaluation on this device was attempted while its stream
+    MOM_ERR_NOT_READY,         /* first evaluation on this device was attempted while its stream
                                   is being captured: call mom_init (or evaluate once) before */
+    MOM_ERR_BAD_TRANS          /* a transposition flag is neither 0 nor 1 */
 } mom_status_t;
 
 #define MOM_MAX_FACTORS 1024
@@ -101,6 +102,26 @@ mom_status_t mom_chain_plan(const int64_t *dims, const int32_t *props, int32_t n
  */
 mom_status_t mom_plan_from_splits(const int64_t *dims, const int32_t *props, int32_t n,
                                   const int32_t *preorder_splits, mom_plan_t **out);
+
+/* What the parenthesisation minimises. */
+#define MOM_PLAN_MIN_MULTS 0            /* scalar multiplications (Sec. 2, "Transformations") */
+
+/*
+ * The general planning call: mom_chain_plan / mom_plan_from_splits plus transposed factors
+ * (Table 1, "Transpose").
+ *   trans [host] n flags or NULL (= none).  trans[t] = 1: factor t of the chain is the
+ *         TRANSPOSE of the matrix in its buffer.  dims still describe the chain (factor t is
+ *         dims[t] x dims[t+1]), so the buffer holds a dims[t+1] x dims[t] matrix, row-major;
+ *         props[t] is the property of that STORED matrix, and inside the chain the factor
+ *         carries the mirrored one: lowerTri(A) -> upperTri(A^T) (Sec. 2, "Transformations",
+ *         the inference rule printed there); general and Identity are their own mirror image.
+ *         Nothing is transposed in memory: the product kernels read the buffer as it is.
+ *   objective        MOM_PLAN_MIN_MULTS.
+ *   preorder_splits  [host] NULL: the optimal tree; else a forced tree as in mom_plan_from_splits.
+ * Costs, the tree and the result's property follow from the properties inside the chain.
+ */
+mom_status_t mom_chain_plan_ex(const int64_t *dims, const int32_t *props, const int32_t *trans, int32_t n,
+                               int32_t objective, const int32_t *preorder_splits, mom_plan_t **out);
 
 void mom_plan_destroy(mom_plan_t *plan);                       /* NULL is allowed */
 
@@ -156,9 +177,11 @@ mom_status_t mom_init(void);
  * by a launch that adds its slices, and a zero-fill pass runs last when asked for.  The
  * library allocates nothing and never synchronises; calls on one stream run in order, calls
  * that share a workspace or an output on different streams race.
- *   d_factors [host] array of n DEVICE pointers, entry t -> dims[t] x dims[t+1] f32;
- *             entries of Identity factors are ignored and may be NULL.
- *   lds       [host] n row strides in elements (>= dims[t+1]), or NULL for packed rows.
+ *   d_factors [host] array of n DEVICE pointers, entry t -> dims[t] x dims[t+1] f32 (for a
+ *             factor planned as transposed: the dims[t+1] x dims[t] matrix whose transpose it
+ *             is); entries of Identity factors are ignored and may be NULL.
+ *   lds       [host] n row strides in elements (>= the columns of the stored matrix), or NULL
+ *             for packed rows.
  *   d_out     [device] rows x cols result, row stride ld_out elements (0 = packed).
  *   d_workspace [device] at least mom_plan_workspace_bytes bytes, 256-byte aligned; may be
  *             NULL when that is 0.  Contents are scratch.
@@ -194,7 +217,8 @@ mom_status_t mom_chain_eval_static(const mom_plan_t *plan, const float *const *d
  * parenthesisation by Sec. 2, "Transformations") in ONE kernel launch; each chain is
  * handled by one 64-lane wavefront and intermediates never leave the compute unit.
  *   d_factor_bases [host] n DEVICE pointers; chain b's factor t starts at
- *             d_factor_bases[t] + b * batch_strides[t] and is packed row-major.
+ *             d_factor_bases[t] + b * batch_strides[t] and is packed row-major (the stored
+ *             matrix, for a factor planned as transposed).
  *   batch_strides [host] n strides in elements, or NULL for dims[t]*dims[t+1].
  *   d_out [device], chain b's result at d_out + b * out_batch_stride (0 = rows*cols), packed.
  * Covers plans whose dimensions are all <= 32 and that have at most 8 surviving factors

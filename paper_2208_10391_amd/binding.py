@@ -21,9 +21,11 @@ MOM_STATIC_WORKSPACE_BYTES = 64 << 20
 STATUS_NAMES = ["MOM_OK", "MOM_ERR_NULL", "MOM_ERR_BAD_N", "MOM_ERR_BAD_DIM", "MOM_ERR_BAD_PROP",
                 "MOM_ERR_NOT_SQUARE", "MOM_ERR_OVERFLOW", "MOM_ERR_BAD_SPLITS", "MOM_ERR_WORKSPACE",
                 "MOM_ERR_BUFFER_TOO_SMALL", "MOM_ERR_BAD_STRIDE", "MOM_ERR_UNSUPPORTED", "MOM_ERR_HIP",
-                "MOM_ERR_NOMEM", "MOM_ERR_BAD_FLAGS", "MOM_ERR_NOT_READY"]
+                "MOM_ERR_NOMEM", "MOM_ERR_BAD_FLAGS", "MOM_ERR_NOT_READY", "MOM_ERR_BAD_TRANS"]
 
-EXPORTS = ["mom_chain_plan", "mom_plan_from_splits", "mom_plan_destroy", "mom_plan_cost_mults",
+MOM_PLAN_MIN_MULTS = 0
+
+EXPORTS = ["mom_chain_plan", "mom_plan_from_splits", "mom_chain_plan_ex", "mom_plan_destroy", "mom_plan_cost_mults",
            "mom_plan_num_products", "mom_plan_result", "mom_plan_string", "mom_plan_splits",
            "mom_plan_product", "mom_plan_num_launches", "mom_plan_workspace_bytes", "mom_init", "mom_chain_eval", "mom_chain_eval_static", "mom_chain_eval_batched", "mom_probe_mfma_peak",
            "mom_status_string"]
@@ -53,6 +55,8 @@ _lib.mom_chain_plan.restype = ctypes.c_int
 _lib.mom_chain_plan.argtypes = [_i64p, _i32p, ctypes.c_int32, _vpp]
 _lib.mom_plan_from_splits.restype = ctypes.c_int
 _lib.mom_plan_from_splits.argtypes = [_i64p, _i32p, ctypes.c_int32, _i32p, _vpp]
+_lib.mom_chain_plan_ex.restype = ctypes.c_int
+_lib.mom_chain_plan_ex.argtypes = [_i64p, _i32p, _i32p, ctypes.c_int32, ctypes.c_int32, _i32p, _vpp]
 _lib.mom_plan_destroy.restype = None
 _lib.mom_plan_destroy.argtypes = [ctypes.c_void_p]
 _lib.mom_plan_cost_mults.restype = ctypes.c_uint64
@@ -99,10 +103,16 @@ def mom_status_string(status: int) -> str:
 class Plan:
     """Owner of a mom_plan_t handle."""
 
-    def __init__(self, handle: int, dims: Sequence[int], props: Sequence[int]):
+    def __init__(self, handle: int, dims: Sequence[int], props: Sequence[int], trans: Optional[Sequence[int]] = None):
         self.handle = ctypes.c_void_p(handle)
         self.dims = [int(d) for d in dims]
         self.props = [int(p) for p in props]
+        self.trans = [0] * len(self.props) if trans is None else [1 if t else 0 for t in trans]
+
+    def stored_shape(self, t: int):
+        """Shape of factor t's buffer: the transpose's shape when the factor enters transposed."""
+        r, c = self.dims[t], self.dims[t + 1]
+        return (c, r) if self.trans[t] else (r, c)
 
     def __del__(self):
         if getattr(self, "handle", None):
@@ -142,7 +152,30 @@ def _i32(values) -> ctypes.Array:
     return (ctypes.c_int32 * max(len(values), 1))(*[int(v) for v in values])
 
 
-def mom_chain_plan(dims: Sequence[int], props: Sequence[int]) -> Plan:
+def mom_chain_plan_ex(dims: Sequence[int], props: Sequence[int], trans: Optional[Sequence[int]] = None,
+                      objective: int = MOM_PLAN_MIN_MULTS, preorder_splits: Optional[Sequence[int]] = None) -> Plan:
+    """The general planning call: transposed factors (props are those of the STORED matrices),
+    the objective, and optionally a forced tree."""
+    n = len(props)
+    if len(dims) != n + 1:
+        raise ValueError("dims must have len(props)+1 entries")
+    if trans is not None and len(trans) != n:
+        raise ValueError("trans must have len(props) entries")
+    if preorder_splits is not None:
+        survivors = sum(1 for p in props if p != MOM_IDENTITY)
+        if len(preorder_splits) != max(survivors - 1, 0):
+            raise MomError(7, "mom_chain_plan_ex")
+    out = ctypes.c_void_p()
+    st = _lib.mom_chain_plan_ex(_i64(dims), _i32(props), None if trans is None else _i32(trans), n, int(objective),
+                                None if preorder_splits is None else _i32(preorder_splits), ctypes.byref(out))
+    if st != MOM_OK:
+        raise MomError(st, "mom_chain_plan_ex")
+    return Plan(out.value, dims, props, trans)
+
+
+def mom_chain_plan(dims: Sequence[int], props: Sequence[int], trans: Optional[Sequence[int]] = None) -> Plan:
+    if trans is not None:
+        return mom_chain_plan_ex(dims, props, trans)
     n = len(props)
     if len(dims) != n + 1:
         raise ValueError("dims must have len(props)+1 entries")
@@ -153,7 +186,10 @@ def mom_chain_plan(dims: Sequence[int], props: Sequence[int]) -> Plan:
     return Plan(out.value, dims, props)
 
 
-def mom_plan_from_splits(dims: Sequence[int], props: Sequence[int], preorder_splits: Sequence[int]) -> Plan:
+def mom_plan_from_splits(dims: Sequence[int], props: Sequence[int], preorder_splits: Sequence[int],
+                         trans: Optional[Sequence[int]] = None) -> Plan:
+    if trans is not None:
+        return mom_chain_plan_ex(dims, props, trans, preorder_splits=preorder_splits)
     n = len(props)
     if len(dims) != n + 1:
         raise ValueError("dims must have len(props)+1 entries")
@@ -271,11 +307,11 @@ def bind_chain_eval(plan: Plan, factors: Sequence[Optional[torch.Tensor]], out: 
     for t, f in enumerate(factors):
         if f is None:
             ptrs[t] = None
-            lds[t] = plan.dims[t + 1]
+            lds[t] = plan.stored_shape(t)[1]
             continue
         _check_factor(f, "factor %d" % t)
-        if f.dim() != 2 or tuple(f.shape) != (plan.dims[t], plan.dims[t + 1]) or f.stride(1) != 1:
-            raise ValueError("factor %d must be %dx%d with unit column stride" % (t, plan.dims[t], plan.dims[t + 1]))
+        if f.dim() != 2 or tuple(f.shape) != plan.stored_shape(t) or f.stride(1) != 1:
+            raise ValueError("factor %d must be %dx%d with unit column stride" % ((t,) + plan.stored_shape(t)))
         ptrs[t] = f.data_ptr()
         lds[t] = f.stride(0) if f.shape[0] > 1 else max(f.stride(0), f.shape[1])
     rows, cols, _ = mom_plan_result(plan)
@@ -326,7 +362,7 @@ def bind_chain_eval_batched(plan: Plan, factors: Sequence[Optional[torch.Tensor]
             strides[t] = plan.dims[t] * plan.dims[t + 1]
             continue
         _check_factor(f, "factor %d" % t)
-        r, c = plan.dims[t], plan.dims[t + 1]
+        r, c = plan.stored_shape(t)
         if f.dim() != 3 or tuple(f.shape[1:]) != (r, c) or f.shape[0] != batch:
             raise ValueError("factor %d must be [batch, %d, %d]" % (t, r, c))
         if f.stride(2) != 1 or (r > 1 and f.stride(1) != c):

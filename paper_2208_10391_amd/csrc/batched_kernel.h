@@ -23,6 +23,8 @@ struct BatchedParams {
     int64_t stride[kBatchedMaxFactors];           // elements between consecutive chains
     int rows[kBatchedMaxFactors], cols[kBatchedMaxFactors], prop[kBatchedMaxFactors];
     int vec[kBatchedMaxFactors];                  // factor is a full 32x32, 16-byte aligned
+    int trans[kBatchedMaxFactors];                // the buffer holds the factor's transpose (rows, cols:
+                                                  // of the STORED matrix; prop: of the factor in the chain)
     int num_products;
     int a_slot[kBatchedMaxFactors], b_slot[kBatchedMaxFactors];   // product s: slot[a] = slot[a] * slot[b]
     float *out;
@@ -66,16 +68,23 @@ __global__ __launch_bounds__(64) void batched_chain_kernel(const BatchedParams p
                 }
         }
     }
-    // 2. registers -> LDS slot f, keeping only the factor's structure
+    // 2. registers -> LDS slot f, keeping only the factor's structure; a factor whose buffer
+    //    holds its transpose is mirrored on the way (stored entry (i, j) is entry (j, i) of the chain)
 #pragma unroll
     for (int f = 0; f < NL; ++f)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int i = (lane + 64 * q) / 8, j0 = ((lane + 64 * q) % 8) * 4;
             f32x4 v = reg[f][q];
+            if (p.trans[f]) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = in_structure(p.prop[f], i, j0 + e) ? v[e] : 0.0f;
-            *reinterpret_cast<f32x4 *>(&slots[f * kSlotFloats + i * kSlotLd + j0]) = v;
+                for (int e = 0; e < 4; ++e)
+                    slots[f * kSlotFloats + (j0 + e) * kSlotLd + i] = in_structure(p.prop[f], j0 + e, i) ? v[e] : 0.0f;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = in_structure(p.prop[f], i, j0 + e) ? v[e] : 0.0f;
+                *reinterpret_cast<f32x4 *>(&slots[f * kSlotFloats + i * kSlotLd + j0]) = v;
+            }
         }
     __syncthreads();
 
@@ -196,9 +205,10 @@ inline hipError_t launch_batched(const mom_plan *plan, const float *const *bases
     for (int i = 0; i < nl; ++i) {
         const int f = plan->survivors[i];
         p.base[i] = bases[f];
-        p.rows[i] = (int)plan->dims[f];
-        p.cols[i] = (int)plan->dims[f + 1];
-        p.prop[i] = plan->props[f];
+        p.trans[i] = plan->trans[f];
+        p.rows[i] = (int)plan->dims[p.trans[i] ? f + 1 : f];
+        p.cols[i] = (int)plan->dims[p.trans[i] ? f : f + 1];
+        p.prop[i] = plan->chain_props[f];
         p.stride[i] = strides ? strides[f] : plan->dims[f] * plan->dims[f + 1];
         p.vec[i] = p.rows[i] == 32 && p.cols[i] == 32 && (reinterpret_cast<uintptr_t>(bases[f]) & 15) == 0 &&
                    (p.stride[i] & 3) == 0;
@@ -216,7 +226,7 @@ inline hipError_t launch_batched(const mom_plan *plan, const float *const *bases
     p.out_cols = (int)plan->cols;
     p.batch = batch;
     // three full, aligned 32x32 factors multiplied as X0 * (X1 * X2): the register-only kernel
-    if (nl == 3 && p.vec[0] && p.vec[1] && p.vec[2] && p.num_products == 2 && p.a_slot[0] == 1 && p.b_slot[0] == 2 &&
+    if (nl == 3 && p.vec[0] && p.vec[1] && p.vec[2] && !p.trans[0] && !p.trans[1] && !p.trans[2] && p.num_products == 2 && p.a_slot[0] == 1 && p.b_slot[0] == 2 &&
         p.a_slot[1] == 0 && p.b_slot[1] == 1) {
         hipLaunchKernelGGL(chain3_kernel_for(p.prop[0], p.prop[1], p.prop[2]), dim3((batch + 3) / 4), dim3(256), 0, stream, p);
         return hipGetLastError();

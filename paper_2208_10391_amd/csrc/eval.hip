@@ -4,7 +4,9 @@
 #include "../../include/mom.h"
 #include "plan_internal.h"
 #include "product_kernel.h"
+#include "product_variant.h"
 #include "schedule.h"
+#include "small_kernels.h"
 #include "batched_kernel.h"
 
 #include <hip/hip_runtime.h>
@@ -14,11 +16,6 @@
 namespace {
 
 using namespace mom;
-
-// 128x128 tiles, 4 wavefronts of 64x64, two workgroups per compute unit: the workhorse.
-// 64x64 tiles, 4 wavefronts of 32x32, four or more per compute unit: products with a short side.
-typedef TileConfig<128, 128, kChunk128, 2, 2, 2> Tile128;
-typedef TileConfig<64, 64, kChunk64, 2, 2, 4> Tile64;
 
 constexpr int kMaxDevices = 64;       // devices whose one-time set-up is remembered
 
@@ -38,13 +35,17 @@ hipError_t scratch_address(char **ptr)
     return hipGetSymbolAddress(reinterpret_cast<void **>(ptr), HIP_SYMBOL(scratch));
 }
 
+const ProductLauncher kLaunchers[kNumVariants] = {launch_product_nn, launch_product_tn, launch_product_nt, launch_product_tt};
+const ProductConfigurer kConfigurers[kNumVariants] = {configure_product_nn, configure_product_tn, configure_product_nt,
+                                                      configure_product_tt};
+
 hipError_t configure_kernels()
 {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&product_kernel<Tile128>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, Tile128::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(&product_kernel<Tile64>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, Tile64::LDS_BYTES);
+    for (int v = 0; v < kNumVariants; ++v) {
+        const hipError_t e = kConfigurers[v]();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 // Make the current device ready for launches.  `stream` is the stream an evaluation is about
@@ -69,14 +70,6 @@ mom_status_t ensure_device_ready(bool have_stream, hipStream_t stream)
         g_device_ready[dev].store(true, std::memory_order_release);
     }
     return MOM_OK;
-}
-
-template <class T>
-hipError_t launch_product(const ProductBatch &batch, hipStream_t stream)
-{
-    hipLaunchKernelGGL(product_kernel<T>, dim3(batch.block_end[batch.count - 1]), dim3(T::NT), T::LDS_BYTES, stream,
-                       batch);
-    return hipGetLastError();
 }
 
 // Register-only MFMA loop: 4 independent accumulator blocks per wavefront keep the pipe full.
@@ -106,7 +99,14 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(float *sink, int iters,
 
 inline bool aligned16(const void *ptr, int64_t ld) { return (reinterpret_cast<uintptr_t>(ptr) & 15) == 0 && (ld & 3) == 0; }
 
-inline int elementwise_grid(int64_t total) { return (int)std::min<int64_t>((total + 255) / 256, 4096); }
+// Grid of the row-wise element-wise kernels: x over groups of four columns, y over rows.
+inline dim3 rowwise_grid(int rows, int cols, int rows_per_block)
+{
+    const int quads = (cols + 3) / 4;
+    const int gx = std::max(1, std::min((quads + 255) / 256, 16));
+    const int gy = std::max(1, std::min((rows + rows_per_block - 1) / rows_per_block, 16384));
+    return dim3(gx, gy);
+}
 
 struct Resolved { const float *ptr; int64_t ld; };
 
@@ -118,17 +118,25 @@ mom_status_t eval_chain(const mom_plan_t *plan, const float *const *d_factors, c
     const int M = (int)plan->rows, N = (int)plan->cols;
 
     if (plan->survivors.empty()) {                         // I * I * ... = I
-        hipLaunchKernelGGL(write_identity_kernel, dim3(elementwise_grid((int64_t)M * M)), dim3(256), 0, stream,
-                           d_out, ld_out, M);
+        hipLaunchKernelGGL(write_identity_kernel, rowwise_grid(M, M, 1), dim3(256), 0, stream, d_out, ld_out, M,
+                           (int)aligned16(d_out, ld_out));
         return hipGetLastError() == hipSuccess ? MOM_OK : MOM_ERR_HIP;
     }
-    auto factor = [&](int32_t f) { return Resolved{d_factors[f], lds ? lds[f] : plan->dims[f + 1]}; };
+    auto factor = [&](int32_t f) {                         // packed rows of the STORED matrix by default
+        return Resolved{d_factors[f], lds ? lds[f] : (plan->trans[f] ? plan->dims[f] : plan->dims[f + 1])};
+    };
 
     if (plan->steps.empty()) {                             // one survivor: A * I -> A
         const int32_t f = plan->survivors[0];
         const Resolved a = factor(f);
-        hipLaunchKernelGGL(copy_structure_kernel, dim3(elementwise_grid((int64_t)M * N)), dim3(256), 0, stream,
-                           a.ptr, a.ld, d_out, ld_out, M, N, plan->props[f]);
+        if (plan->trans[f]) {
+            const int64_t blocks = (int64_t)((M + 31) / 32) * ((N + 31) / 32);
+            hipLaunchKernelGGL(copy_transposed_kernel, dim3((unsigned)std::min<int64_t>(blocks, 1 << 20)), dim3(256), 0, stream,
+                               a.ptr, a.ld, d_out, ld_out, M, N, plan->chain_props[f]);
+        } else {
+            hipLaunchKernelGGL(copy_structure_kernel, rowwise_grid(M, N, kRowUnroll), dim3(256), 0, stream, a.ptr, a.ld,
+                               d_out, ld_out, M, N, plan->props[f], (int)(aligned16(a.ptr, a.ld) && aligned16(d_out, ld_out)));
+        }
         if (hipGetLastError() != hipSuccess) return MOM_ERR_HIP;
     }
 
@@ -144,6 +152,7 @@ mom_status_t eval_chain(const mom_plan_t *plan, const float *const *d_factors, c
         for (int i = 0; i < batch.count; ++i) {
             const ProductStep &st = plan->steps[pl.step[i]];
             ProductParams &p = batch.prob[i];
+            // (the column count only matters for temporaries, which are never stored transposed)
             const Resolved a = resolve(st.a, st.k), b = resolve(st.b, st.n), c = resolve(st.c, st.n);
             p.A = a.ptr; p.B = b.ptr; p.C = const_cast<float *>(c.ptr);
             p.lda = a.ld; p.ldb = b.ld; p.ldc = c.ld;
@@ -154,9 +163,7 @@ mom_status_t eval_chain(const mom_plan_t *plan, const float *const *d_factors, c
             }
             p.c_vec = aligned16(p.C, p.ldc);
         }
-        const hipError_t e = pl.shape == kTile128 ? launch_product<Tile128>(batch, stream)
-                                                  : launch_product<Tile64>(batch, stream);
-        if (e != hipSuccess) return MOM_ERR_HIP;
+        if (kLaunchers[pl.variant](pl.shape, batch, stream) != hipSuccess) return MOM_ERR_HIP;
         if (pl.reduce.count > 0) {
             ReduceBatch reduce = pl.reduce;
             for (int i = 0; i < reduce.count; ++i) {
@@ -172,8 +179,8 @@ mom_status_t eval_chain(const mom_plan_t *plan, const float *const *d_factors, c
     }
 
     if (zero_fill && (plan->result_prop == kLower || plan->result_prop == kUpper)) {
-        hipLaunchKernelGGL(zero_other_half_kernel, dim3(elementwise_grid((int64_t)M * M)), dim3(256), 0, stream,
-                           d_out, ld_out, M, plan->result_prop);
+        hipLaunchKernelGGL(zero_other_half_kernel, rowwise_grid(M, M, 1), dim3(256), 0, stream, d_out, ld_out, M,
+                           plan->result_prop, (int)aligned16(d_out, ld_out));
         if (hipGetLastError() != hipSuccess) return MOM_ERR_HIP;
     }
     return MOM_OK;
@@ -189,7 +196,7 @@ mom_status_t check_eval_arguments(const mom_plan_t *plan, const float *const *d_
         if (!d_factors[f]) return MOM_ERR_NULL;
     if (lds)
         for (int32_t f : plan->survivors)
-            if (lds[f] < plan->dims[f + 1]) return MOM_ERR_BAD_STRIDE;
+            if (lds[f] < (plan->trans[f] ? plan->dims[f] : plan->dims[f + 1])) return MOM_ERR_BAD_STRIDE;
     if (ld_out == 0) ld_out = plan->cols;
     if (ld_out < plan->cols) return MOM_ERR_BAD_STRIDE;
     if (flags & ~(uint32_t)MOM_OUT_ZERO_FILL_TRIANGLE) return MOM_ERR_BAD_FLAGS;

@@ -45,7 +45,11 @@ u128 product_mults(int64_t m, int64_t k, int64_t n, int px, int py)
     return N * (N + 1) * (2 * N + 1) / 6;                               // sum over i,j of min(i,j)+1
 }
 
-mom_status_t validate(const int64_t *dims, const int32_t *props, int32_t n)
+// Property of the transpose: the structure mirrored at the diagonal (Sec. 2, Transformations:
+// lowerTri(A) -> upperTri(A^T)).
+inline int mirrored(int p) { return p == kLower ? kUpper : (p == kUpper ? kLower : p); }
+
+mom_status_t validate(const int64_t *dims, const int32_t *props, const int32_t *trans, int32_t n)
 {
     if (!dims || !props) return MOM_ERR_NULL;
     if (n <= 0 || n > MOM_MAX_FACTORS) return MOM_ERR_BAD_N;
@@ -54,6 +58,7 @@ mom_status_t validate(const int64_t *dims, const int32_t *props, int32_t n)
     for (int i = 0; i < n; ++i) {
         if (props[i] < kGeneral || props[i] > kIdentity) return MOM_ERR_BAD_PROP;
         if (props[i] != kGeneral && dims[i] != dims[i + 1]) return MOM_ERR_NOT_SQUARE;
+        if (trans && trans[i] != 0 && trans[i] != 1) return MOM_ERR_BAD_TRANS;
     }
     return MOM_OK;
 }
@@ -134,6 +139,8 @@ struct Builder {
         st.a = a.op; st.b = b.op;
         st.m = a.rows; st.k = a.cols; st.n = b.cols;
         st.pa = a.prop; st.pb = b.prop; st.pc = join(a.prop, b.prop);
+        st.ta = a.op.where == mom::Where::Factor && plan->trans[a.op.index];
+        st.tb = b.op.where == mom::Where::Factor && plan->trans[b.op.index];
         const u128 c = product_mults(st.m, st.k, st.n, st.pa, st.pb);
         total += c;
         st.mults = c > kU64Max ? std::numeric_limits<uint64_t>::max() : (uint64_t)c;
@@ -186,12 +193,13 @@ mom_status_t lay_out_launches(mom_plan *plan)
             if (done[first - next]) continue;
             PlannedLaunch pl{};
             pl.shape = choose_launch(plan->steps[order[first]]).shape;
+            pl.variant = (plan->steps[order[first]].ta ? 1 : 0) + (plan->steps[order[first]].tb ? 2 : 0);
             int64_t reduce_quads = 0;
             bool batch_small = true;
             for (size_t i = first; i < level_end && pl.batch.count < kMaxFused; ++i) {
                 const ProductStep &st = plan->steps[order[i]];
                 const Launch L = choose_launch(st);
-                if (done[i - next] || L.shape != pl.shape) continue;
+                if (done[i - next] || L.shape != pl.shape || (st.ta ? 1 : 0) + (st.tb ? 2 : 0) != pl.variant) continue;
                 const bool small_launch = (int64_t)L.grid * L.split_k <= 4 * kComputeUnits;
                 if (pl.batch.count > 0 && (!small_launch || !batch_small)) continue;
                 batch_small = small_launch;
@@ -309,17 +317,23 @@ mom_status_t finish(mom_plan *plan, const std::vector<int64_t> &d, const std::ve
 }
 
 // identity simplification: A*I -> A, I*A -> A, I*I = I.  d / p receive the survivors' chain.
-void start(mom_plan *plan, const int64_t *dims, const int32_t *props, int32_t n,
+void start(mom_plan *plan, const int64_t *dims, const int32_t *props, const int32_t *trans, int32_t n,
            std::vector<int64_t> &d, std::vector<int32_t> &p)
 {
     plan->n = n;
     plan->dims.assign(dims, dims + n + 1);
     plan->props.assign(props, props + n);
+    plan->trans.assign(n, 0);
+    plan->chain_props.assign(props, props + n);
     for (int i = 0; i < n; ++i) {
+        if (trans && trans[i] && props[i] != kIdentity) {       // the transpose of I is I
+            plan->trans[i] = 1;
+            plan->chain_props[i] = mirrored(props[i]);
+        }
         if (props[i] == kIdentity) continue;
         plan->survivors.push_back(i);
         d.push_back(dims[i]);
-        p.push_back(props[i]);
+        p.push_back(plan->chain_props[i]);
     }
     d.push_back(dims[n]);
 }
@@ -371,15 +385,17 @@ mom_status_t optimal_splits(const std::vector<int64_t> &d, const std::vector<int
 
 // Plan with the DP's tree (forced == nullptr) or with a given one.  Exceptions (allocation
 // failures of the containers) are turned into a status by the callers.
-mom_status_t make_plan(const int64_t *dims, const int32_t *props, int32_t n, bool forced_tree,
-                       const int32_t *forced, mom_plan_t **out)
+mom_status_t make_plan(const int64_t *dims, const int32_t *props, const int32_t *trans, int32_t n,
+                       int32_t objective, bool forced_tree, const int32_t *forced, mom_plan_t **out)
 {
-    mom_status_t st = validate(dims, props, n);
+    mom_status_t st = validate(dims, props, trans, n);
     if (st != MOM_OK) return st;
+    if (objective != MOM_PLAN_MIN_MULTS) return MOM_ERR_BAD_FLAGS;
     std::unique_ptr<mom_plan> plan(new mom_plan());
+    plan->objective = objective;
     std::vector<int64_t> d;
     std::vector<int32_t> p;
-    start(plan.get(), dims, props, n, d, p);
+    start(plan.get(), dims, props, trans, n, d, p);
     const int m = (int)p.size();
     std::vector<int32_t> split_pos;
     if (!forced_tree) {
@@ -422,7 +438,7 @@ mom_status_t mom_chain_plan(const int64_t *dims, const int32_t *props, int32_t n
 {
     if (!out) return MOM_ERR_NULL;
     *out = nullptr;
-    return guarded([&] { return make_plan(dims, props, n, false, nullptr, out); });
+    return guarded([&] { return make_plan(dims, props, nullptr, n, MOM_PLAN_MIN_MULTS, false, nullptr, out); });
 }
 
 mom_status_t mom_plan_from_splits(const int64_t *dims, const int32_t *props, int32_t n,
@@ -430,7 +446,17 @@ mom_status_t mom_plan_from_splits(const int64_t *dims, const int32_t *props, int
 {
     if (!out) return MOM_ERR_NULL;
     *out = nullptr;
-    return guarded([&] { return make_plan(dims, props, n, true, preorder_splits, out); });
+    return guarded([&] { return make_plan(dims, props, nullptr, n, MOM_PLAN_MIN_MULTS, true, preorder_splits, out); });
+}
+
+mom_status_t mom_chain_plan_ex(const int64_t *dims, const int32_t *props, const int32_t *trans, int32_t n,
+                               int32_t objective, const int32_t *preorder_splits, mom_plan_t **out)
+{
+    if (!out) return MOM_ERR_NULL;
+    *out = nullptr;
+    return guarded([&] {
+        return make_plan(dims, props, trans, n, objective, preorder_splits != nullptr, preorder_splits, out);
+    });
 }
 
 void mom_plan_destroy(mom_plan_t *plan) { delete plan; }
@@ -505,6 +531,7 @@ const char *mom_status_string(mom_status_t status)
     case MOM_ERR_BAD_STRIDE: return "stride smaller than the matrix needs";
     case MOM_ERR_UNSUPPORTED: return "plan not covered by the kernel (batched: a dimension above 32 or more than 8 factors)";
     case MOM_ERR_HIP: return "HIP runtime error";
+    case MOM_ERR_BAD_TRANS: return "a transposition flag is neither 0 nor 1";
     case MOM_ERR_NOMEM: return "out of host memory";
     case MOM_ERR_BAD_FLAGS: return "unknown flag bits";
     case MOM_ERR_NOT_READY: return "first use on this device happened under stream capture: call mom_init before capturing";

@@ -23,7 +23,8 @@ struct Operand {
 struct ProductStep {
     Operand a, b, c;
     int64_t m, k, n;
-    int pa, pb, pc;            // properties of A, B and of the result
+    int pa, pb, pc;            // properties of A, B (as the product reads them) and of the result
+    int ta, tb;                // the buffer of A / B holds its transpose (factors only)
     uint64_t mults;            // scalar multiplications with no structurally-zero operand
     int level;                 // 1 + the highest level among the products it consumes (factors: 0);
                                // products of one level are independent of each other
@@ -42,6 +43,7 @@ struct Temp {
 // them are cut along k, one slice-sum launch follows.
 struct PlannedLaunch {
     int shape;                       // TileShape of the product kernel
+    int variant;                     // which operands are stored transposed (ProductVariant)
     int step[kMaxFused];             // index into mom_plan::steps of batch.prob[i]
     ProductBatch batch;              // geometry complete; A, B, C, ld*, *_vec patched per call
     ReduceBatch reduce;              // count == 0: no product of this launch is split
@@ -56,7 +58,10 @@ constexpr int kBatchedSlots = 8;     // surviving factors the batched kernels ho
 struct mom_plan {
     int32_t n = 0;
     std::vector<int64_t> dims;       // n + 1
-    std::vector<int32_t> props;      // n
+    std::vector<int32_t> props;      // n: properties of the STORED matrices
+    std::vector<int32_t> trans;      // n: factor t enters the chain as the transpose of its buffer
+    std::vector<int32_t> chain_props;   // n: properties inside the chain (a transposed triangle mirrored)
+    int32_t objective = 0;           // what the tree minimises (MOM_PLAN_MIN_MULTS / MOM_PLAN_MIN_TIME)
     std::vector<int32_t> survivors;  // original indices of the non-Identity factors
     std::vector<int32_t> splits;     // preorder, original indices, survivors-1 entries
     uint64_t cost = 0;

@@ -70,23 +70,41 @@ __device__ __forceinline__ void tile_coords(int order, int t, int tm, int tn, in
     }
 }
 
-template <int BM_, int BN_, int BK_, int WM_, int WN_, int MIN_BLOCKS_>
+// TA / TB: the operand's buffer holds the TRANSPOSE of what the product needs (paper Table 1,
+// Transpose): A is stored as the K x M matrix S with A[i][k] = S[k][i], B as the N x K matrix
+// with B[k][j] = S[j][k].  Nothing is transposed in memory: a transposed A tile is simply
+// fetched and staged the way a plain B tile is ([k][i], contiguous along i, read from LDS
+// with one 4-byte read per k), a transposed B tile the way a plain A tile is ([j][k + pad],
+// read with one 16-byte read per lane).
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int MIN_BLOCKS_, bool TA_ = false, bool TB_ = false>
 struct TileConfig {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
     static constexpr int MIN_BLOCKS = MIN_BLOCKS_;
+    static constexpr bool TA = TA_, TB = TB_;
     static constexpr int NT = WM * WN * 64;           // threads per workgroup
     static constexpr int WTM = BM / WM, WTN = BN / WN;   // tile of one wavefront
     static constexpr int FM = WTM / 32, FN = WTN / 32;   // 32x32 MFMA blocks per wavefront
-    static constexpr int LDA = BK + 4;                // LDS row stride of the A tile [BM][BK]:
-                                                      // 16-byte rows reads hit distinct banks
-    static constexpr int LDB = BN;                    // LDS row stride of the B tile [BK][BN]
-    static constexpr int A_STAGE = BM * LDA, B_STAGE = BK * LDB;
+    static constexpr int LDA = TA ? BM : BK + 4;      // LDS row stride of the A tile: [BM][BK + 4]
+                                                      // (16-byte row reads hit distinct banks), or
+                                                      // [BK][BM] when A is stored transposed
+    static constexpr int LDB = TB ? BK + 4 : BN;      // LDS row stride of the B tile: [BK][BN], or
+                                                      // [BN][BK + 4] when B is stored transposed
+    static constexpr int A_STAGE = (TA ? BK : BM) * LDA, B_STAGE = (TB ? BN : BK) * LDB;
     static constexpr int LDS_BYTES = 2 * (A_STAGE + B_STAGE) * 4;
     static constexpr int A_F4 = BM * BK / 4 / NT;     // 16-byte loads per thread and chunk
     static constexpr int B_F4 = BK * BN / 4 / NT;
     static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BK % 8 == 0, "tile shape");
     static_assert(BM % BK == 0 && BN % BK == 0, "diagonals must fall on chunk boundaries");
     static_assert((BM * BK / 4) % NT == 0 && (BK * BN / 4) % NT == 0, "load decomposition");
+
+    // Where the idx-th group of four consecutive stored elements of a chunk sits: row / column
+    // of the product (i or j), k inside the chunk, and which of the two runs along the four.
+    // A plain: idx -> (i = idx / (BK/4), k = 4 * (idx % (BK/4)) .. +3)
+    // A transposed: idx -> (k = idx / (BM/4), i = 4 * (idx % (BM/4)) .. +3)
+    static __device__ __forceinline__ int a_row(int idx) { return TA ? (idx % (BM / 4)) * 4 : idx / (BK / 4); }
+    static __device__ __forceinline__ int a_k(int idx) { return TA ? idx / (BM / 4) : (idx % (BK / 4)) * 4; }
+    static __device__ __forceinline__ int b_col(int idx) { return TB ? idx / (BK / 4) : (idx % (BN / 4)) * 4; }
+    static __device__ __forceinline__ int b_k(int idx) { return TB ? (idx % (BK / 4)) * 4 : idx / (BN / 4); }
 };
 
 // Element-wise loads of one k-chunk for the edges of a matrix and for rows that are not
@@ -100,11 +118,12 @@ __device__ __forceinline__ void load_a_checked(const ProductParams &p, int r0, i
 #pragma unroll
     for (int q = 0; q < T::A_F4; ++q) {
         const int idx = tid + q * T::NT;
-        const int gi = r0 + idx / (T::BK / 4), gk = kc + (idx % (T::BK / 4)) * 4;
+        const int gi = r0 + T::a_row(idx), gk = kc + T::a_k(idx);
         f32x4 v;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const bool ok = gi < p.M && gk + e < p.K && in_structure(p.pa, gi, gk + e);
+            const int i = T::TA ? gi + e : gi, k = T::TA ? gk : gk + e;
+            const bool ok = i < p.M && k < p.K && in_structure(p.pa, i, k);
             v[e] = ok ? src[q][e] : 0.0f;
         }
         ra[q] = v;
@@ -118,11 +137,12 @@ __device__ __forceinline__ void load_b_checked(const ProductParams &p, int c0, i
 #pragma unroll
     for (int q = 0; q < T::B_F4; ++q) {
         const int idx = tid + q * T::NT;
-        const int gk = kc + idx / (T::BN / 4), gj = c0 + (idx % (T::BN / 4)) * 4;
+        const int gk = kc + T::b_k(idx), gj = c0 + T::b_col(idx);
         f32x4 v;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const bool ok = gk < p.K && gj + e < p.N && in_structure(p.pb, gk, gj + e);
+            const int k = T::TB ? gk + e : gk, j = T::TB ? gj : gj + e;
+            const bool ok = k < p.K && j < p.N && in_structure(p.pb, k, j);
             v[e] = ok ? src[q][e] : 0.0f;
         }
         rb[q] = v;
@@ -136,19 +156,21 @@ __device__ __forceinline__ void stage_to_lds(float *As, float *Bs, int tid,
 #pragma unroll
     for (int q = 0; q < T::A_F4; ++q) {
         const int idx = tid + q * T::NT;
-        *reinterpret_cast<f32x4 *>(As + (idx / (T::BK / 4)) * T::LDA + (idx % (T::BK / 4)) * 4) = ra[q];
+        *reinterpret_cast<f32x4 *>(As + (T::TA ? T::a_k(idx) * T::LDA + T::a_row(idx)
+                                                 : T::a_row(idx) * T::LDA + T::a_k(idx))) = ra[q];
     }
 #pragma unroll
     for (int q = 0; q < T::B_F4; ++q) {
         const int idx = tid + q * T::NT;
-        *reinterpret_cast<f32x4 *>(Bs + (idx / (T::BN / 4)) * T::LDB + (idx % (T::BN / 4)) * 4) = rb[q];
+        *reinterpret_cast<f32x4 *>(Bs + (T::TB ? T::b_col(idx) * T::LDB + T::b_k(idx)
+                                                 : T::b_k(idx) * T::LDB + T::b_col(idx))) = rb[q];
     }
 }
 
 // MFMA operands of one group of 8 k-values: lane (l32, half) takes A[row l32][k = 4*half + e]
 // for e = 0..3 with one 16-byte LDS read per 32-row block, and B[k = 4*half + e][col l32].
 // a_lane / b_lane are the lane's own offsets inside a stage: (wr0 + l32) * LDA + 4 * half and
-// 4 * half * LDB + wc0 + l32.
+// 4 * half * LDB + wc0 + l32; an operand stored transposed swaps the two patterns.
 template <class T>
 struct Fragments {
     f32x4 a[T::FM];
@@ -160,12 +182,25 @@ __device__ __forceinline__ void read_fragments(const float *As, const float *Bs,
                                                Fragments<T> &f)
 {
 #pragma unroll
-    for (int bi = 0; bi < T::FM; ++bi)
-        f.a[bi] = *reinterpret_cast<const f32x4 *>(As + a_lane + bi * 32 * T::LDA + kg * 8);
+    for (int bi = 0; bi < T::FM; ++bi) {
+        if (T::TA) {
 #pragma unroll
-    for (int bj = 0; bj < T::FN; ++bj)
+            for (int e = 0; e < 4; ++e) f.a[bi][e] = As[a_lane + (kg * 8 + e) * T::LDA + bi * 32];
+        } else {
+            f.a[bi] = *reinterpret_cast<const f32x4 *>(As + a_lane + bi * 32 * T::LDA + kg * 8);
+        }
+    }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) f.b[bj][e] = Bs[b_lane + (kg * 8 + e) * T::LDB + bj * 32];
+    for (int bj = 0; bj < T::FN; ++bj) {
+        if (T::TB) {
+            const f32x4 v = *reinterpret_cast<const f32x4 *>(Bs + b_lane + bj * 32 * T::LDB + kg * 8);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) f.b[bj][e] = v[e];
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) f.b[bj][e] = Bs[b_lane + (kg * 8 + e) * T::LDB + bj * 32];
+        }
+    }
 }
 
 // The 4 * FM * FN MFMAs of one group of 8 k-values: step e multiplies k = 4*half + e (the
@@ -261,18 +296,20 @@ __device__ __forceinline__ void mask_registers(const ProductParams &p, int r0, i
 #pragma unroll
         for (int q = 0; q < T::A_F4; ++q) {
             const int idx = tid + q * T::NT;
-            const int gi = r0 + idx / (T::BK / 4), gk = kc + (idx % (T::BK / 4)) * 4;
+            const int gi = r0 + T::a_row(idx), gk = kc + T::a_k(idx);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) ra[q][e] = in_structure(p.pa, gi, gk + e) ? ra[q][e] : 0.0f;
+            for (int e = 0; e < 4; ++e)
+                ra[q][e] = in_structure(p.pa, T::TA ? gi + e : gi, T::TA ? gk : gk + e) ? ra[q][e] : 0.0f;
         }
     }
     if (p.pb != kGeneral) {
 #pragma unroll
         for (int q = 0; q < T::B_F4; ++q) {
             const int idx = tid + q * T::NT;
-            const int gk = kc + idx / (T::BN / 4), gj = c0 + (idx % (T::BN / 4)) * 4;
+            const int gk = kc + T::b_k(idx), gj = c0 + T::b_col(idx);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) rb[q][e] = in_structure(p.pb, gk, gj + e) ? rb[q][e] : 0.0f;
+            for (int e = 0; e < 4; ++e)
+                rb[q][e] = in_structure(p.pb, T::TB ? gk + e : gk, T::TB ? gj : gj + e) ? rb[q][e] : 0.0f;
         }
     }
 }
@@ -324,12 +361,14 @@ __device__ __forceinline__ void next_fetch_tile(const ProductParams &p, int bloc
 #pragma unroll
     for (int q = 0; q < T::A_F4; ++q) {
         const int idx = tid + q * T::NT;
-        pl.a_src[q] = p.A + (int64_t)(pl.fw.r0 + idx / (T::BK / 4)) * p.lda + pl.fw.klo + (idx % (T::BK / 4)) * 4;
+        const int i = pl.fw.r0 + T::a_row(idx), k = pl.fw.klo + T::a_k(idx);
+        pl.a_src[q] = T::TA ? p.A + (int64_t)k * p.lda + i : p.A + (int64_t)i * p.lda + k;
     }
 #pragma unroll
     for (int q = 0; q < T::B_F4; ++q) {
         const int idx = tid + q * T::NT;
-        pl.b_src[q] = p.B + (int64_t)(pl.fw.klo + idx / (T::BN / 4)) * p.ldb + pl.fw.c0 + (idx % (T::BN / 4)) * 4;
+        const int k = pl.fw.klo + T::b_k(idx), j = pl.fw.c0 + T::b_col(idx);
+        pl.b_src[q] = T::TB ? p.B + (int64_t)j * p.ldb + k : p.B + (int64_t)k * p.ldb + j;
     }
 }
 
@@ -349,9 +388,10 @@ __device__ __forceinline__ void fetch_chunk(const ProductParams &p, int block, i
 #pragma unroll
         for (int q = 0; q < T::B_F4; ++q) pl.rb[q] = *reinterpret_cast<const f32x4 *>(pl.b_src[q]);
     }
-    const int64_t b_step = (int64_t)T::BK * p.ldb;
+    const int64_t a_step = T::TA ? (int64_t)T::BK * p.lda : T::BK;     // one chunk further along k
+    const int64_t b_step = T::TB ? T::BK : (int64_t)T::BK * p.ldb;
 #pragma unroll
-    for (int q = 0; q < T::A_F4; ++q) pl.a_src[q] += T::BK;
+    for (int q = 0; q < T::A_F4; ++q) pl.a_src[q] += a_step;
 #pragma unroll
     for (int q = 0; q < T::B_F4; ++q) pl.b_src[q] += b_step;
     pl.reg_kind = kind; pl.reg_r0 = pl.fw.r0; pl.reg_c0 = pl.fw.c0; pl.reg_kc = kc;
@@ -375,7 +415,10 @@ __device__ __forceinline__ void chunk_step(float *smem, const ProductParams &p, 
 {
     constexpr int NKG = T::BK / 8;
     static_assert(NKG % 2 == 0, "the operand double buffer returns to f0 after an even number of groups");
-    constexpr int NMFMA = 4 * T::FM * T::FN, NREAD = T::FM + 2 * T::FN, NMOVE = T::A_F4 + T::B_F4;
+    constexpr int NMFMA = 4 * T::FM * T::FN, NMOVE = T::A_F4 + T::B_F4;
+    // LDS read instructions per k-group: one 16-byte read per block of an operand laid out
+    // [row][k], two paired 4-byte reads per block of one laid out [k][row]
+    constexpr int NREAD = (T::TA ? 2 : 1) * T::FM + (T::TB ? 1 : 2) * T::FN;
     const int s = HOT ? S : s_;
     const float *As = smem + s * T::A_STAGE, *Bs = smem + 2 * T::A_STAGE + s * T::B_STAGE;
     float *An = smem + (s ^ 1) * T::A_STAGE, *Bn = smem + 2 * T::A_STAGE + (s ^ 1) * T::B_STAGE;
@@ -399,9 +442,10 @@ __device__ __forceinline__ void chunk_step(float *smem, const ProductParams &p, 
         if (kg == MOVE) {
             if (HOT) {
                 stage_to_lds<T>(An, Bn, tid, pl.ra, pl.rb);
-                const int64_t b_step = (int64_t)T::BK * p.ldb;
+                const int64_t a_step = T::TA ? (int64_t)T::BK * p.lda : T::BK;
+                const int64_t b_step = T::TB ? T::BK : (int64_t)T::BK * p.ldb;
 #pragma unroll
-                for (int q = 0; q < T::A_F4; ++q) { pl.ra[q] = *reinterpret_cast<const f32x4 *>(pl.a_src[q]); pl.a_src[q] += T::BK; }
+                for (int q = 0; q < T::A_F4; ++q) { pl.ra[q] = *reinterpret_cast<const f32x4 *>(pl.a_src[q]); pl.a_src[q] += a_step; }
 #pragma unroll
                 for (int q = 0; q < T::B_F4; ++q) { pl.rb[q] = *reinterpret_cast<const f32x4 *>(pl.b_src[q]); pl.b_src[q] += b_step; }
             } else {
@@ -454,7 +498,8 @@ __global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const Pro
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
     const int wr0 = (wave / T::WN) * T::WTM, wc0 = (wave % T::WN) * T::WTN;
-    const int a_lane = (wr0 + l32) * T::LDA + 4 * half, b_lane = 4 * half * T::LDB + wc0 + l32;
+    const int a_lane = T::TA ? 4 * half * T::LDA + wr0 + l32 : (wr0 + l32) * T::LDA + 4 * half;
+    const int b_lane = T::TB ? (wc0 + l32) * T::LDB + 4 * half : 4 * half * T::LDB + wc0 + l32;
 
     // prologue of the whole workgroup: flat chunk 0 into stage 0, flat chunk 1 into the registers
     Pipeline<T> pl;
@@ -535,77 +580,6 @@ __global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const Pro
                             if (plain || (gi < p.M && gj + e < p.N && in_structure(p.pc, gi, gj + e))) dst[e] = acc[bi][bj][4 * q + e];
                     }
                 }
-    }
-}
-
-// Sum of split-K slices (ReduceBatch; blockIdx.y selects the product).  The order of summation
-// is fixed, so results repeat bit for bit from run to run.
-// 256 threads = 32 groups of 4 consecutive floats x 8 lanes over the slices: lane g of a group
-// sums slices g, g+8, ... with all its loads in flight, the 8 partial sums meet in LDS.
-__global__ __launch_bounds__(256) void reduce_slices_kernel(const ReduceBatch batch)
-{
-    __shared__ f32x4 part[8][32];
-    const ReduceParams &r = batch.prob[blockIdx.y];
-    const int64_t total = (int64_t)r.M * r.N;              // scratch slices are packed: M*N floats each
-    const int64_t quads = (total + 3) / 4;
-    const bool vec = (total % 4) == 0 && (r.N % 4) == 0 && (r.ldc % 4) == 0 && (reinterpret_cast<uintptr_t>(r.C) & 15) == 0;
-    const int q_in_block = threadIdx.x % 32, g = threadIdx.x / 32;
-    for (int64_t q0 = (int64_t)blockIdx.x * 32; q0 < quads; q0 += (int64_t)gridDim.x * 32) {
-        const int64_t q = q0 + q_in_block, e = q * 4;
-        f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f};
-        if (q < quads) {
-            if (vec) {
-#pragma unroll 8
-                for (int k = g; k < r.slices; k += 8) s += *reinterpret_cast<const f32x4 *>(r.P + k * r.slice_stride + e);
-            } else {
-                for (int k = g; k < r.slices; k += 8)
-                    for (int c = 0; c < 4; ++c)
-                        if (e + c < total) s[c] += r.P[k * r.slice_stride + e + c];
-            }
-        }
-        part[g][q_in_block] = s;
-        __syncthreads();
-        if (g == 0 && q < quads) {
-#pragma unroll
-            for (int k = 1; k < 8; ++k) s += part[k][q_in_block];
-            if (vec) {
-                *reinterpret_cast<f32x4 *>(r.C + (e / r.N) * r.ldc + (e % r.N)) = s;
-            } else {
-                for (int c = 0; c < 4; ++c)
-                    if (e + c < total) r.C[((e + c) / r.N) * r.ldc + ((e + c) % r.N)] = s[c];
-            }
-        }
-        __syncthreads();
-    }
-}
-
-// out = A restricted to its structure (single surviving factor: A*I -> A)
-__global__ void copy_structure_kernel(const float *A, int64_t lda, float *C, int64_t ldc, int M, int N, int prop)
-{
-    const int64_t total = (int64_t)M * N;
-    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
-        const int i = (int)(e / N), j = (int)(e % N);
-        if (in_structure(prop, i, j)) C[(int64_t)i * ldc + j] = A[(int64_t)i * lda + j];
-    }
-}
-
-// out = I (every factor was an Identity: I*I = I)
-__global__ void write_identity_kernel(float *C, int64_t ldc, int M)
-{
-    const int64_t total = (int64_t)M * M;
-    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
-        const int i = (int)(e / M), j = (int)(e % M);
-        C[(int64_t)i * ldc + j] = i == j ? 1.0f : 0.0f;
-    }
-}
-
-// zeros into the half of a triangular result that the product kernel leaves untouched
-__global__ void zero_other_half_kernel(float *C, int64_t ldc, int M, int prop)
-{
-    const int64_t total = (int64_t)M * M;
-    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
-        const int i = (int)(e / M), j = (int)(e % M);
-        if (!in_structure(prop, i, j)) C[(int64_t)i * ldc + j] = 0.0f;
     }
 }
 

@@ -1,0 +1,166 @@
+// The small kernels around the product kernel: sum of split-K slices, copy of a single
+// surviving factor, identity write, zero fill of the other half of a triangular result.
+// Included by the evaluator only (these are ordinary, non-template kernels).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "product_kernel.h"
+
+namespace mom {
+
+// Sum of split-K slices (ReduceBatch; blockIdx.y selects the product).  The order of summation
+// is fixed, so results repeat bit for bit from run to run.
+// 256 threads = 32 groups of 4 consecutive floats x 8 lanes over the slices: lane g of a group
+// sums slices g, g+8, ... with all its loads in flight, the 8 partial sums meet in LDS.
+__global__ __launch_bounds__(256) void reduce_slices_kernel(const ReduceBatch batch)
+{
+    __shared__ f32x4 part[8][32];
+    const ReduceParams &r = batch.prob[blockIdx.y];
+    const int64_t total = (int64_t)r.M * r.N;              // scratch slices are packed: M*N floats each
+    const int64_t quads = (total + 3) / 4;
+    const bool vec = (total % 4) == 0 && (r.N % 4) == 0 && (r.ldc % 4) == 0 && (reinterpret_cast<uintptr_t>(r.C) & 15) == 0;
+    const int q_in_block = threadIdx.x % 32, g = threadIdx.x / 32;
+    for (int64_t q0 = (int64_t)blockIdx.x * 32; q0 < quads; q0 += (int64_t)gridDim.x * 32) {
+        const int64_t q = q0 + q_in_block, e = q * 4;
+        f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (q < quads) {
+            if (vec) {
+#pragma unroll 8
+                for (int k = g; k < r.slices; k += 8) s += *reinterpret_cast<const f32x4 *>(r.P + k * r.slice_stride + e);
+            } else {
+                for (int k = g; k < r.slices; k += 8)
+                    for (int c = 0; c < 4; ++c)
+                        if (e + c < total) s[c] += r.P[k * r.slice_stride + e + c];
+            }
+        }
+        part[g][q_in_block] = s;
+        __syncthreads();
+        if (g == 0 && q < quads) {
+#pragma unroll
+            for (int k = 1; k < 8; ++k) s += part[k][q_in_block];
+            if (vec) {
+                *reinterpret_cast<f32x4 *>(r.C + (e / r.N) * r.ldc + (e % r.N)) = s;
+            } else {
+                for (int c = 0; c < 4; ++c)
+                    if (e + c < total) r.C[((e + c) / r.N) * r.ldc + ((e + c) % r.N)] = s[c];
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// The three element-wise kernels below walk a matrix row by row: blockIdx.y strides over the
+// rows, the threads of a workgroup over groups of four consecutive columns (one 16-byte access
+// when base and row stride allow, element-wise otherwise); no division per element.
+constexpr int kRowUnroll = 4;          // rows a thread has in flight at once
+
+// Columns [lo, hi) of row i that lie inside the structure of property p (N columns in all).
+__device__ __forceinline__ void structure_span(int p, int i, int N, int &lo, int &hi)
+{
+    lo = p == kUpper ? min(i, N) : 0;
+    hi = p == kLower ? min(i + 1, N) : N;
+}
+
+// out = A restricted to its structure (single surviving factor: A*I -> A)
+__global__ __launch_bounds__(256) void copy_structure_kernel(const float *A, int64_t lda, float *C, int64_t ldc, int M, int N,
+                                                             int prop, int vec)
+{
+    const int quads = (N + 3) / 4;
+    for (int i0 = blockIdx.y * kRowUnroll; i0 < M; i0 += gridDim.y * kRowUnroll) {
+        for (int q = blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += gridDim.x * blockDim.x) {
+            const int j = 4 * q;
+            f32x4 v[kRowUnroll];
+            bool whole[kRowUnroll], some[kRowUnroll];
+#pragma unroll
+            for (int r = 0; r < kRowUnroll; ++r) {          // all loads first
+                const int i = i0 + r;
+                int lo, hi;
+                structure_span(prop, i, N, lo, hi);
+                some[r] = i < M && j < hi && j + 4 > lo;
+                whole[r] = some[r] && vec && j >= lo && j + 4 <= hi;
+                if (whole[r]) {
+                    v[r] = *reinterpret_cast<const f32x4 *>(A + (int64_t)i * lda + j);
+                } else if (some[r]) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[r][e] = (j + e >= lo && j + e < hi) ? A[(int64_t)i * lda + j + e] : 0.0f;
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < kRowUnroll; ++r) {
+                const int i = i0 + r;
+                if (whole[r]) {
+                    *reinterpret_cast<f32x4 *>(C + (int64_t)i * ldc + j) = v[r];
+                } else if (some[r]) {
+                    int lo, hi;
+                    structure_span(prop, i, N, lo, hi);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (j + e >= lo && j + e < hi) C[(int64_t)i * ldc + j + e] = v[r][e];
+                }
+            }
+        }
+    }
+}
+
+// out = S^T restricted to the structure `prop` of the result (single surviving factor that
+// enters the chain transposed): 32x32 blocks through LDS, reads and writes both along rows.
+__global__ __launch_bounds__(256) void copy_transposed_kernel(const float *S, int64_t lds_, float *C, int64_t ldc, int M, int N,
+                                                              int prop)
+{
+    __shared__ float tile[32][33];
+    const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;      // 32 x 8 threads
+    const int bj = (N + 31) / 32, blocks = ((M + 31) / 32) * bj;
+    for (int b = blockIdx.x; b < blocks; b += gridDim.x) {
+        const int i0 = (b / bj) * 32, j0 = (b % bj) * 32;        // block of the result
+        for (int r = ty; r < 32; r += 8) {                       // S is N x M: rows j0.., columns i0..
+            const int j = j0 + r, i = i0 + tx;
+            tile[r][tx] = (j < N && i < M && in_structure(prop, i, j)) ? S[(int64_t)j * lds_ + i] : 0.0f;
+        }
+        __syncthreads();
+        for (int r = ty; r < 32; r += 8) {
+            const int i = i0 + r, j = j0 + tx;
+            if (i < M && j < N && in_structure(prop, i, j)) C[(int64_t)i * ldc + j] = tile[tx][r];
+        }
+        __syncthreads();
+    }
+}
+
+// out = I (every factor was an Identity: I*I = I)
+__global__ __launch_bounds__(256) void write_identity_kernel(float *C, int64_t ldc, int M, int vec)
+{
+    const int quads = (M + 3) / 4;
+    for (int i = blockIdx.y; i < M; i += gridDim.y)
+        for (int q = blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += gridDim.x * blockDim.x) {
+            const int j = 4 * q;
+            if (vec && j + 4 <= M) {
+                const f32x4 v = {j == i ? 1.0f : 0.0f, j + 1 == i ? 1.0f : 0.0f, j + 2 == i ? 1.0f : 0.0f, j + 3 == i ? 1.0f : 0.0f};
+                *reinterpret_cast<f32x4 *>(C + (int64_t)i * ldc + j) = v;
+            } else {
+                for (int e = 0; e < 4 && j + e < M; ++e) C[(int64_t)i * ldc + j + e] = (j + e == i) ? 1.0f : 0.0f;
+            }
+        }
+}
+
+// zeros into the half of a triangular result that the product kernel leaves untouched
+__global__ __launch_bounds__(256) void zero_other_half_kernel(float *C, int64_t ldc, int M, int prop, int vec)
+{
+    const int quads = (M + 3) / 4;
+    for (int i = blockIdx.y; i < M; i += gridDim.y) {
+        // the other half of row i: columns (i, M) of a lowerTri result, [0, i) of an upperTri one
+        const int lo = prop == kLower ? i + 1 : 0, hi = prop == kLower ? M : i;
+        for (int q = blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += gridDim.x * blockDim.x) {
+            const int j = 4 * q;
+            if (j + 4 <= lo || j >= hi) continue;
+            if (vec && j >= lo && j + 4 <= hi) {
+                const f32x4 z = {0.0f, 0.0f, 0.0f, 0.0f};
+                *reinterpret_cast<f32x4 *>(C + (int64_t)i * ldc + j) = z;
+            } else {
+                for (int e = 0; e < 4; ++e)
+                    if (j + e >= lo && j + e < hi) C[(int64_t)i * ldc + j + e] = 0.0f;
+            }
+        }
+    }
+}
+
+}  // namespace mom

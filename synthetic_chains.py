@@ -25,6 +25,7 @@ class ChainConfig:
     dims: Sequence[int]
     props: Sequence[int]
     batch: int = 0              # 0 = a single chain; >0 = that many independent chains
+    trans: Sequence[int] = ()   # which factors enter transposed (props: of the stored matrices); () = none
 
 
 CONFIGS = {
@@ -32,6 +33,8 @@ CONFIGS = {
     "tiny": ChainConfig("tiny", 1, (64, 64, 32, 128), (LOWER_TRI, GENERAL, GENERAL)),
     # one triangular-times-general product, n = 4096
     "trmm4096": ChainConfig("trmm4096", 2, (4096, 4096, 4096), (LOWER_TRI, GENERAL)),
+    # the same product with both buffers holding transposes: (stored upperTri)^T * (stored G)^T
+    "trmm4096_transposed": ChainConfig("trmm4096_transposed", 2, (4096, 4096, 4096), (UPPER_TRI, GENERAL), trans=(1, 1)),
     # order-sensitive chain of five general factors
     "general5": ChainConfig("general5", 3, (8192, 512, 8192, 64, 4096, 2048), (GENERAL,) * 5),
     # L1 * I * L2 * U * G
@@ -81,4 +84,4 @@ def make_chain(dims: Sequence[int], props: Sequence[int], seed_family: int,
 
 def make_config(name: str) -> List[Optional[torch.Tensor]]:
     c = CONFIGS[name]
-    return make_chain(c.dims, c.props, c.number, c.batch)
+    return make_chain(c.dims, c.props, c.number, c.batch, list(c.trans) if c.trans else None)

@@ -56,9 +56,11 @@ def upload(factors, props, poison=True, pad_cols=0):
     return dev
 
 
-def eval_chain(dims, props, factors, splits=None, flags=0, poison=True, pad_cols=0, out_pad=0):
-    """Returns (plan, result as numpy with NaN sentinel where nothing was written)."""
-    plan = mom.mom_chain_plan(dims, props) if splits is None else mom.mom_plan_from_splits(dims, props, splits)
+def eval_chain(dims, props, factors, splits=None, flags=0, poison=True, pad_cols=0, out_pad=0, trans=None):
+    """Returns (plan, result as numpy with NaN sentinel where nothing was written).  With `trans`
+    the factors are the stored matrices (props theirs) and enter the chain transposed where flagged."""
+    plan = mom.mom_chain_plan(dims, props, trans=trans) if splits is None else \
+        mom.mom_plan_from_splits(dims, props, splits, trans=trans)
     dev = upload(factors, props, poison, pad_cols)
     rows, cols, _ = plan.result
     out_full = torch.full((rows, cols + out_pad), float("nan"), device="cuda", dtype=torch.float32)
@@ -104,7 +106,7 @@ def assert_close_by_tiles(got: np.ndarray, want: np.ndarray, prop: int = G, tile
 def check_against_dense(dims, props, factors, splits=None, flags=0, **kw):
     plan, got = eval_chain(dims, props, factors, splits, flags, **kw)
     np_f = [None if f is None else f.numpy() for f in factors]
-    want = oracle.eval_dense(dims, props, np_f)
+    want = oracle.eval_dense(dims, props, np_f, trans=kw.get("trans"))
     rows, cols, prop = plan.result
     mask = structure_mask(prop, rows, cols)
     if prop == I:

@@ -169,3 +169,34 @@ def test_error_paths():
     assert lib.mom_chain_eval_batched(p.handle, fptr, None, ctypes.c_void_p(1024), 0, -1, None) == code["MOM_ERR_BAD_N"]
     assert lib.mom_chain_eval_batched(p.handle, fptr, (ctypes.c_int64 * 2)(15, 16), ctypes.c_void_p(1024), 0, 4, None) == code["MOM_ERR_BAD_STRIDE"]
     assert mom.mom_status_string(0) == "ok" and "square" in mom.mom_status_string(code["MOM_ERR_NOT_SQUARE"])
+
+
+def test_plans_with_transposed_factors_equal_bruteforce():
+    # Table 1 Transpose; Sec. 2 Transformations: a transposed lowerTri factor plans as upperTri
+    rng = np.random.default_rng(77)
+    for trial in range(3000):
+        n = int(rng.integers(1, 9))
+        dims, props = random_chain(rng, n, 40)
+        trans = [int(x) for x in rng.integers(0, 2, size=n)]
+        want = oracle.plan_bruteforce(dims, props, trans=trans)
+        plan = mom.mom_chain_plan(dims, props, trans=trans)
+        assert (plan.cost_mults, plan.splits, plan.result[2]) == (want["cost"], want["splits"], want["result_prop"])
+        assert plan.string == oracle.plan_string(props, want["splits"])
+    p = mom.mom_chain_plan([5, 5, 5], [L, U], trans=[1, 0])
+    assert p.result == (5, 5, U) and p.cost_mults == 35          # upper * upper
+    p = mom.mom_chain_plan([5, 5, 5], [L, L], trans=[1, 0])
+    assert p.result == (5, 5, G) and p.cost_mults == 55          # upper * lower: sum of squares
+    p = mom.mom_chain_plan([4, 4, 4], [I, G], trans=[1, 1])
+    assert p.result == (4, 4, G) and p.cost_mults == 0
+    # forced tree through the general call
+    p = mom.mom_chain_plan_ex([3, 4, 5, 6], [G, G, G], [1, 0, 1], preorder_splits=[0, 1])
+    assert p.string == "(0 (1 2))"
+    assert status_of(mom.mom_chain_plan, [4, 4, 4], [G, G], [0, 2]) == mom.binding.STATUS_NAMES.index("MOM_ERR_BAD_TRANS")
+    assert status_of(mom.mom_chain_plan_ex, [4, 4, 4], [G, G], None, 9) == mom.binding.STATUS_NAMES.index("MOM_ERR_BAD_FLAGS")
+    # strides are those of the STORED matrix: a transposed 3x7 factor is a 7x3 buffer
+    lib = mom.library()
+    p = mom.mom_chain_plan([3, 7, 2], [G, G], trans=[1, 0])
+    fake = (ctypes.c_void_p * 2)(256, 512)
+    fptr = ctypes.cast(fake, ctypes.POINTER(ctypes.c_void_p))
+    bad = mom.binding.STATUS_NAMES.index("MOM_ERR_BAD_STRIDE")
+    assert lib.mom_chain_eval(p.handle, fptr, (ctypes.c_int64 * 2)(2, 2), ctypes.c_void_p(1024), 0, None, 0, 0, None) == bad
