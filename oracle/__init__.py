@@ -42,6 +42,13 @@ _lib.oracle_eval_plan_t.restype = ctypes.c_int
 _lib.oracle_eval_plan_t.argtypes = [ctypes.c_int32, _i64p, _i32p, _i32p, _fpp, _i32p, _f64p, _i32p]
 _lib.oracle_transposed_property.restype = ctypes.c_int32
 _lib.oracle_transposed_property.argtypes = [ctypes.c_int32]
+_lib.oracle_product_time_ps.restype = ctypes.c_uint64
+_lib.oracle_product_time_ps.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32]
+_lib.oracle_plan_bruteforce_time.restype = ctypes.c_int
+_lib.oracle_plan_bruteforce_time.argtypes = [ctypes.c_int32, _i64p, _i32p, ctypes.POINTER(ctypes.c_uint64),
+                                             ctypes.POINTER(ctypes.c_uint64), _i32p, _i32p]
+_lib.oracle_tree_time.restype = ctypes.c_int
+_lib.oracle_tree_time.argtypes = [ctypes.c_int32, _i64p, _i32p, _i32p, ctypes.POINTER(ctypes.c_uint64)]
 _lib.oracle_max_threads.restype = ctypes.c_int
 
 
@@ -132,6 +139,42 @@ def plan_bruteforce(dims, props, elide: bool = True, trans=None) -> dict:
     k = max(neff.value - 1, 0)
     return {"cost": int(cost.value), "n_eff": int(neff.value), "splits": [int(x) for x in splits[:k]],
             "result_prop": int(rprop.value), "num_trees": int(ntrees.value)}
+
+
+def product_time_ps(m: int, k: int, n: int, pX: int, pY: int) -> int:
+    """Modelled time, in picoseconds, of one tiled product on the GPU (the opt-in objective that
+    Sec. 4's gap between multiplication count and run time motivates; stated in oracle.c)."""
+    return int(_lib.oracle_product_time_ps(m, k, n, pX, pY))
+
+
+def plan_bruteforce_time(dims, props, trans=None) -> dict:
+    """The tree with the smallest modelled time, by enumerating every tree.  Returns time_ps,
+    mults (of that tree), n_eff, splits."""
+    d, p = _dims(dims), _props(chain_props(props, trans))
+    n = len(p)
+    t, mu, neff = ctypes.c_uint64(), ctypes.c_uint64(), ctypes.c_int32()
+    splits = np.zeros(max(n, 1), dtype=np.int32)
+    rc = _lib.oracle_plan_bruteforce_time(n, d.ctypes.data_as(_i64p), p.ctypes.data_as(_i32p), ctypes.byref(t),
+                                          ctypes.byref(mu), ctypes.byref(neff), splits.ctypes.data_as(_i32p))
+    if rc != 0:
+        raise OverflowError("a sum does not fit in 64 bits")
+    k = max(neff.value - 1, 0)
+    return {"time_ps": int(t.value), "mults": int(mu.value), "n_eff": int(neff.value),
+            "splits": [int(x) for x in splits[:k]]}
+
+
+def tree_time_ps(dims, props, splits, trans=None) -> int:
+    """Modelled time of one given tree: the sum over its products."""
+    d, p = _dims(dims), _props(chain_props(props, trans))
+    s = np.ascontiguousarray(np.asarray(list(splits) + [0], dtype=np.int32))
+    t = ctypes.c_uint64()
+    rc = _lib.oracle_tree_time(len(p), d.ctypes.data_as(_i64p), p.ctypes.data_as(_i32p),
+                               s.ctypes.data_as(_i32p), ctypes.byref(t))
+    if rc == 1:
+        raise OverflowError("time does not fit in 64 bits")
+    if rc == 2:
+        raise ValueError("malformed split list")
+    return int(t.value)
 
 
 def tree_cost(dims, props, splits, trans=None) -> Tuple[int, int]:

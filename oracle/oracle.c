@@ -21,6 +21,9 @@
  *     the properties of operands and intermediates into account
  *                                      [Sec. 2, "Operations" and "Transformations"]
  *
+ *   - an opt-in second objective: a stated integer time model of one tiled
+ *     product on the GPU, summed over the tree  [motivated by Sec. 4, Results]
+ *
  * All floating point work is done in double precision.
  *
  * Pins (tests/test_oracle_*.py): the paper's 5x5 lowerTri*lowerTri example with
@@ -273,6 +276,183 @@ int oracle_tree_cost(int32_t n, const int64_t *dims, const int32_t *props,
 done:
     free(d); free(p); free(where);
     return rc;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Time model of one binary product on the GPU, and the tree that minimises  */
+/* its sum.  The paper's objective is the multiplication count [Sec. 2,      */
+/* Transformations]; its own experiment shows that count and run time are    */
+/* different things (5.94 times fewer multiplications bought 1.24 times the  */
+/* speed) [Sec. 4, Results].  This is the opt-in alternative objective: an    */
+/* estimate, in integer picoseconds, of what the tiled product kernel        */
+/* spends on X (m x k, pX) * Y (k x n, pY).  Stated so that both sides can   */
+/* compute it exactly:                                                       */
+/*   T  = 64 if m <= 64 or n <= 64, else 128        (square output tiles)    */
+/*   a tile (I, J) of the result exists unless the result is triangular and  */
+/*   the tile lies wholly in its zero half                                   */
+/*   k-range of a tile: [0, k) clipped by the operands' structures           */
+/*     X lowerTri: k < min((I+1)T, m)      X upperTri: k >= I*T              */
+/*     Y lowerTri: k >= J*T                Y upperTri: k < min((J+1)T, n)    */
+/*   start rounded down to a multiple of 32; chunks = ceil(length / 32)      */
+/*   a product whose tiles all run the full k (general * general), with      */
+/*   fewer than 256 tiles and at least 64 chunks, is cut into                */
+/*   s = min(ceil(384 / tiles), chunks / 8) slices (s > 1), each a           */
+/*   workgroup of its own, followed by a launch that adds the slices         */
+/*   matrix time = max(longest workgroup, ceil(all chunks / 256)) * chunk_ps */
+/*     (256 compute units; chunk_ps = one T x T x 32 chunk at 256 FLOP per   */
+/*     clock and 2.4 GHz: 1706667 ps for T = 128, 426667 ps for T = 64)      */
+/*   memory time = 4 bytes * (structural entries of X, Y and the result) at  */
+/*     8 bytes per picosecond                                                */
+/*   time = 6000000 (launch) + max(matrix, memory)                           */
+/*          + [split] 6000000 + 4 * (s + 1) * m * n / 8                      */
+
+enum { TIME_LAUNCH_PS = 6000000, TIME_CHUNK128_PS = 1706667, TIME_CHUNK64_PS = 426667 };
+
+static u128 structural_entries(int64_t rows, int64_t cols, int prop)
+{
+    if (prop == P_LOWER || prop == P_UPPER) return (u128)rows * (u128)(rows + 1) / 2;
+    return (u128)rows * (u128)cols;
+}
+
+static u128 product_time(int64_t m, int64_t k, int64_t n, int pX, int pY)
+{
+    if (pX == P_IDENTITY || pY == P_IDENTITY) return 0;           /* no computation at all */
+    int64_t T = (m <= 64 || n <= 64) ? 64 : 128;
+    u128 chunk_ps = T == 128 ? TIME_CHUNK128_PS : TIME_CHUNK64_PS;
+    int pR = product_property(pX, pY);
+    int64_t tm = (m + T - 1) / T, tn = (n + T - 1) / T;
+    u128 tiles = 0, all_chunks = 0, longest = 0;
+    for (int64_t I = 0; I < tm; ++I)
+        for (int64_t J = 0; J < tn; ++J) {
+            if (pR == P_LOWER && J > I) continue;
+            if (pR == P_UPPER && J < I) continue;
+            int64_t r0 = I * T, r1 = r0 + T < m ? r0 + T : m;
+            int64_t c0 = J * T, c1 = c0 + T < n ? c0 + T : n;
+            int64_t lo = 0, hi = k;
+            if (pX == P_LOWER && r1 < hi) hi = r1;
+            if (pX == P_UPPER && r0 > lo) lo = r0;
+            if (pY == P_LOWER && c0 > lo) lo = c0;
+            if (pY == P_UPPER && c1 < hi) hi = c1;
+            lo = (lo / 32) * 32;
+            u128 chunks = hi > lo ? (u128)((hi - lo + 31) / 32) : 0;
+            ++tiles;
+            all_chunks += chunks;
+            if (chunks > longest) longest = chunks;
+        }
+    u128 extra = 0;
+    int general = (pX == P_GENERAL && pY == P_GENERAL);
+    int64_t chunks_full = (k + 31) / 32;
+    if (general && tiles < 256 && chunks_full >= 64) {
+        u128 want = (384 + tiles - 1) / tiles, most = (u128)(chunks_full / 8);
+        u128 s = want < most ? want : most;
+        if (s > 1) {
+            u128 per = ((u128)chunks_full + s - 1) / s;          /* chunks of one slice */
+            longest = per;
+            extra = TIME_LAUNCH_PS + 4 * (s + 1) * (u128)m * (u128)n / 8;
+        }
+    }
+    u128 spread = (all_chunks + 255) / 256;
+    u128 matrix = (longest > spread ? longest : spread) * chunk_ps;
+    u128 memory = 4 * (structural_entries(m, k, pX) + structural_entries(k, n, pY) +
+                       structural_entries(m, n, pR)) / 8;
+    return TIME_LAUNCH_PS + (matrix > memory ? matrix : memory) + extra;
+}
+
+uint64_t oracle_product_time_ps(int64_t m, int64_t k, int64_t n, int32_t pX, int32_t pY)
+{
+    u128 t = product_time(m, k, n, pX, pY);
+    return (t >> 64) ? UINT64_MAX : (uint64_t)t;
+}
+
+/* Modelled time of a complete tree: the sum over its products. */
+static subresult_t time_tree(const int64_t *dims, const int32_t *props,
+                             int lo, int hi, const int32_t *splits, int *pos)
+{
+    subresult_t r;
+    if (lo == hi) {
+        r.rows = dims[lo]; r.cols = dims[lo + 1]; r.prop = props[lo]; r.cost = 0;
+        return r;
+    }
+    int s = splits[(*pos)++];
+    subresult_t a = time_tree(dims, props, lo, s, splits, pos);
+    subresult_t b = time_tree(dims, props, s + 1, hi, splits, pos);
+    r.rows = a.rows; r.cols = b.cols;
+    r.prop = product_property(a.prop, b.prop);
+    r.cost = a.cost + b.cost + product_time(a.rows, a.cols, b.cols, a.prop, b.prop);
+    return r;
+}
+
+/*
+ * The tree with the smallest modelled time, by exhaustive enumeration, ties to
+ * the lexicographically smallest preorder split list.  Identity factors are
+ * dropped first.  Outputs as oracle_plan_bruteforce, with *time_ps the
+ * minimum and *mults the multiplication count of that same tree.
+ * Returns 0, or 1 when a sum does not fit in 64 bits.
+ */
+int oracle_plan_bruteforce_time(int32_t n, const int64_t *dims, const int32_t *props,
+                                uint64_t *time_ps, uint64_t *mults, int32_t *n_eff, int32_t *out_splits)
+{
+    int64_t *d = (int64_t *)malloc(sizeof(int64_t) * (n + 1));
+    int32_t *p = (int32_t *)malloc(sizeof(int32_t) * (n > 0 ? n : 1));
+    int32_t *orig = (int32_t *)malloc(sizeof(int32_t) * (n > 0 ? n : 1));
+    int m = 0;
+    for (int i = 0; i < n; ++i) {
+        if (props[i] == P_IDENTITY) continue;
+        d[m] = dims[i]; p[m] = props[i]; orig[m] = i; ++m;
+    }
+    d[m] = dims[n];
+    *n_eff = m; *time_ps = 0; *mults = 0;
+    if (m == 0) { free(d); free(p); free(orig); return 0; }
+    int len = m - 1;
+    int32_t *trees;
+    int64_t cnt = all_trees(0, m - 1, &trees);
+    u128 best = 0; int64_t best_idx = -1;
+    for (int64_t t = 0; t < cnt; ++t) {
+        int pos = 0;
+        subresult_t r = time_tree(d, p, 0, m - 1, trees ? trees + t * len : NULL, &pos);
+        if (best_idx < 0 || r.cost < best ||
+            (r.cost == best && lex_less(trees + t * len, trees + best_idx * len, len))) {
+            best = r.cost; best_idx = t;
+        }
+    }
+    int pos = 0;
+    subresult_t c = cost_tree(d, p, 0, m - 1, trees ? trees + best_idx * len : NULL, &pos);
+    for (int i = 0; i < len; ++i) out_splits[i] = orig[trees[best_idx * len + i]];
+    int overflow = (best >> 64) != 0 || (c.cost >> 64) != 0;
+    *time_ps = (uint64_t)best; *mults = (uint64_t)c.cost;
+    free(trees); free(d); free(p); free(orig);
+    return overflow;
+}
+
+/* Modelled time of one given tree (splits as in oracle_tree_cost). */
+int oracle_tree_time(int32_t n, const int64_t *dims, const int32_t *props,
+                     const int32_t *splits, uint64_t *time_ps)
+{
+    uint64_t cost; int32_t rp;
+    int rc = oracle_tree_cost(n, dims, props, splits, &cost, &rp);     /* validates the split list */
+    if (rc == 2) return 2;
+    int64_t *d = (int64_t *)malloc(sizeof(int64_t) * (n + 1));
+    int32_t *p = (int32_t *)malloc(sizeof(int32_t) * (n > 0 ? n : 1));
+    int32_t *where = (int32_t *)malloc(sizeof(int32_t) * (n > 0 ? n : 1));
+    int m = 0;
+    for (int i = 0; i < n; ++i) {
+        where[i] = -1;
+        if (props[i] == P_IDENTITY) continue;
+        d[m] = dims[i]; p[m] = props[i]; where[i] = m; ++m;
+    }
+    d[m] = dims[n];
+    *time_ps = 0;
+    if (m > 0) {
+        int32_t *s = (int32_t *)malloc(sizeof(int32_t) * m);
+        for (int i = 0; i + 1 < m; ++i) s[i] = where[splits[i]];
+        int pos = 0;
+        subresult_t r = time_tree(d, p, 0, m - 1, s, &pos);
+        free(s);
+        if (r.cost >> 64) { free(d); free(p); free(where); return 1; }
+        *time_ps = (uint64_t)r.cost;
+    }
+    free(d); free(p); free(where);
+    return 0;
 }
 
 /* ------------------------------------------------------------------------ */
