@@ -39,12 +39,16 @@ WORKLOADS = {
     "general5": ("general5", None),
     "general5_left_to_right": ("general5", [3, 2, 1, 0]),   # the tree Sec. 4 would start from
     "batched32": ("batched32", None),
+    # a chain on which the two planning objectives part: the multiplication-optimal tree, and the
+    # tree of the time objective (timed with its own, larger, multiplication count as tree_flop)
+    "ulg2048_min_mults": ("ulg2048", None),
+    "ulg2048_min_time": ("ulg2048", "min_time"),
     # plain copy of a general 8192x8192 matrix (a chain with one factor): the known-size kernel
     # that the HBM counters are calibrated against
     "copy8192": ("copy8192", None),
 }
 SIDE_WORKLOADS = ["trmm4096", "trmm4096_transposed", "general5", "general5_left_to_right", "mixed5_tri_intermediate",
-                  "mixed5_left_to_right", "batched32"]
+                  "mixed5_left_to_right", "batched32", "ulg2048_min_mults", "ulg2048_min_time"]
 
 sc.CONFIGS["copy8192"] = sc.ChainConfig("copy8192", 9, (8192, 8192), (sc.GENERAL,))
 
@@ -144,7 +148,10 @@ def measure(mom, workload, steps, warmup, want_cpu_baseline):
     host = sc.make_config(cfg_name)
     trans = list(cfg.trans) if cfg.trans else None
     best = mom.mom_chain_plan(cfg.dims, cfg.props, trans=trans)    # the planner's tree
-    plan = best if splits is None else mom.mom_plan_from_splits(cfg.dims, cfg.props, splits, trans=trans)
+    if splits == "min_time":
+        plan = mom.mom_chain_plan_ex(cfg.dims, cfg.props, trans, objective=mom.MOM_PLAN_MIN_TIME)
+    else:
+        plan = best if splits is None else mom.mom_plan_from_splits(cfg.dims, cfg.props, splits, trans=trans)
     dev = [None if f is None else f.cuda() for f in host]
     rows, cols, rprop = plan.result
     # arguments are marshalled once; a step is one call of the C entry point

@@ -105,6 +105,26 @@ mom_status_t mom_plan_from_splits(const int64_t *dims, const int32_t *props, int
 
 /* What the parenthesisation minimises. */
 #define MOM_PLAN_MIN_MULTS 0            /* scalar multiplications (Sec. 2, "Transformations") */
+#define MOM_PLAN_MIN_TIME  1            /* modelled run time on the GPU, see below */
+
+/*
+ * MOM_PLAN_MIN_TIME: the paper minimises the multiplication count, and its own experiment
+ * (Sec. 4, "Results": 5.94 times fewer multiplications, 1.24 times the speed) shows that the
+ * count is not the run time.  This opt-in objective minimises, by the same dynamic program, the
+ * sum over the tree's products of an integer estimate in picoseconds of the tiled kernel's
+ * time for X (m x k) * Y (k x n):
+ *   T = 64 if m <= 64 or n <= 64, else 128 (square output tiles); k-chunks of 32;
+ *   a tile (I, J) exists unless it lies wholly in the zero half of a triangular result;
+ *   its k-range is [0, k) clipped by the operands' structures (X lowerTri: k < min((I+1)T, m);
+ *   X upperTri: k >= I*T; Y lowerTri: k >= J*T; Y upperTri: k < min((J+1)T, n)), start rounded
+ *   down to a chunk; general*general with fewer than 256 tiles and at least 64 chunks is cut
+ *   into s = min(ceil(384/tiles), chunks/8) > 1 k-slices, a workgroup each, plus a summing launch;
+ *   matrix = max(longest workgroup's chunks, ceil(all chunks / 256)) * (1706667 for T = 128,
+ *   426667 for T = 64: one chunk of one tile at 256 FLOP per clock and 2.4 GHz);
+ *   memory = 4 * (structural entries of X, Y and the result) / 8 (8 bytes per picosecond);
+ *   time = 6000000 + max(matrix, memory)  [+ 6000000 + 4 * (s+1) * m * n / 8 when sliced].
+ * Ties go to the smallest root split, recursively, as for the multiplication count.
+ */
 
 /*
  * The general planning call: mom_chain_plan / mom_plan_from_splits plus transposed factors
@@ -116,7 +136,7 @@ mom_status_t mom_plan_from_splits(const int64_t *dims, const int32_t *props, int
  *         carries the mirrored one: lowerTri(A) -> upperTri(A^T) (Sec. 2, "Transformations",
  *         the inference rule printed there); general and Identity are their own mirror image.
  *         Nothing is transposed in memory: the product kernels read the buffer as it is.
- *   objective        MOM_PLAN_MIN_MULTS.
+ *   objective        MOM_PLAN_MIN_MULTS or MOM_PLAN_MIN_TIME (anything else: MOM_ERR_BAD_FLAGS).
  *   preorder_splits  [host] NULL: the optimal tree; else a forced tree as in mom_plan_from_splits.
  * Costs, the tree and the result's property follow from the properties inside the chain.
  */
@@ -131,6 +151,10 @@ void mom_plan_destroy(mom_plan_t *plan);                       /* NULL is allowe
 
 /* Scalar multiplications of the plan's tree (0 for a NULL plan). */
 uint64_t mom_plan_cost_mults(const mom_plan_t *plan);
+
+/* Modelled time of the plan's tree in picoseconds (the MOM_PLAN_MIN_TIME objective, whatever
+ * objective the plan was made with; 0 for a NULL plan). */
+uint64_t mom_plan_cost_time_ps(const mom_plan_t *plan);
 
 /* Number of binary products the evaluation launches: survivors-1, or 0. */
 int32_t mom_plan_num_products(const mom_plan_t *plan);

@@ -23,9 +23,9 @@ STATUS_NAMES = ["MOM_OK", "MOM_ERR_NULL", "MOM_ERR_BAD_N", "MOM_ERR_BAD_DIM", "M
                 "MOM_ERR_BUFFER_TOO_SMALL", "MOM_ERR_BAD_STRIDE", "MOM_ERR_UNSUPPORTED", "MOM_ERR_HIP",
                 "MOM_ERR_NOMEM", "MOM_ERR_BAD_FLAGS", "MOM_ERR_NOT_READY", "MOM_ERR_BAD_TRANS"]
 
-MOM_PLAN_MIN_MULTS = 0
+MOM_PLAN_MIN_MULTS, MOM_PLAN_MIN_TIME = 0, 1
 
-EXPORTS = ["mom_chain_plan", "mom_plan_from_splits", "mom_chain_plan_ex", "mom_plan_destroy", "mom_plan_cost_mults",
+EXPORTS = ["mom_chain_plan", "mom_plan_from_splits", "mom_chain_plan_ex", "mom_plan_destroy", "mom_plan_cost_mults", "mom_plan_cost_time_ps",
            "mom_plan_num_products", "mom_plan_result", "mom_plan_string", "mom_plan_splits",
            "mom_plan_product", "mom_plan_num_launches", "mom_plan_workspace_bytes", "mom_init", "mom_chain_eval", "mom_chain_eval_static", "mom_chain_eval_batched", "mom_probe_mfma_peak",
            "mom_status_string"]
@@ -61,6 +61,8 @@ _lib.mom_plan_destroy.restype = None
 _lib.mom_plan_destroy.argtypes = [ctypes.c_void_p]
 _lib.mom_plan_cost_mults.restype = ctypes.c_uint64
 _lib.mom_plan_cost_mults.argtypes = [ctypes.c_void_p]
+_lib.mom_plan_cost_time_ps.restype = ctypes.c_uint64
+_lib.mom_plan_cost_time_ps.argtypes = [ctypes.c_void_p]
 _lib.mom_plan_num_products.restype = ctypes.c_int32
 _lib.mom_plan_num_products.argtypes = [ctypes.c_void_p]
 _lib.mom_plan_result.restype = ctypes.c_int
@@ -126,6 +128,10 @@ class Plan:
     @property
     def cost_mults(self) -> int:
         return mom_plan_cost_mults(self)
+
+    @property
+    def cost_time_ps(self) -> int:
+        return int(_lib.mom_plan_cost_time_ps(self.handle))
 
     @property
     def string(self) -> str:

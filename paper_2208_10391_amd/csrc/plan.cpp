@@ -49,6 +49,76 @@ u128 product_mults(int64_t m, int64_t k, int64_t n, int px, int py)
 // lowerTri(A) -> upperTri(A^T)).
 inline int mirrored(int p) { return p == kLower ? kUpper : (p == kUpper ? kLower : p); }
 
+// Modelled time of X(m x k)*Y(k x n) on the GPU in picoseconds: the objective of
+// MOM_PLAN_MIN_TIME (include/mom.h states the model).  The tile shape and the slice cut are the
+// ones the evaluator will use (choose_launch); the k-chunks of all tiles are summed in closed
+// form per tile row, tile column, diagonal or shell, never tile by tile.
+constexpr uint64_t kLaunchPs = 6000000, kChunk128Ps = 1706667, kChunk64Ps = 426667;
+
+u128 structural_entries(int64_t rows, int64_t cols, int p)
+{
+    return is_tri(p) ? (u128)rows * (u128)(rows + 1) / 2 : (u128)rows * (u128)cols;
+}
+
+u128 product_time_ps(int64_t m, int64_t k, int64_t n, int px, int py)
+{
+    mom::ProductStep st{};
+    st.m = m; st.k = k; st.n = n; st.pa = px; st.pb = py; st.pc = join(px, py);
+    const mom::Launch L = mom::choose_launch(st);
+    const int64_t T = L.bm, q = T / 32, tm = L.tiles_m, tn = L.tiles_n;
+    const u128 chunk_ps = L.shape == mom::kTile128 ? kChunk128Ps : kChunk64Ps;
+    auto chunks_up_to = [](int64_t x) { return (u128)((x + 31) / 32); };          // chunks covering [0, x)
+    auto row_end = [&](int64_t I, int64_t extent) { return std::min((I + 1) * T, extent); };
+    u128 all = 0, longest = 0;
+    const bool xt = is_tri(px), yt = is_tri(py);
+    if (!xt && !yt) {
+        longest = chunks_up_to(k);
+        all = (u128)tm * (u128)tn * longest;
+        if (L.split_k > 1) longest = (longest + L.split_k - 1) / L.split_k;        // one slice's share
+    } else if (xt && !yt) {            // the k-range depends on the tile row only
+        u128 rows = 0;
+        for (int64_t I = 0; I < tm; ++I) {
+            const u128 c = px == kLower ? chunks_up_to(row_end(I, m)) : chunks_up_to(k - I * T);
+            rows += c;
+            longest = std::max(longest, c);
+        }
+        all = rows * (u128)tn;
+    } else if (!xt && yt) {            // ... on the tile column only
+        u128 cols = 0;
+        for (int64_t J = 0; J < tn; ++J) {
+            const u128 c = py == kLower ? chunks_up_to(k - J * T) : chunks_up_to(row_end(J, n));
+            cols += c;
+            longest = std::max(longest, c);
+        }
+        all = cols * (u128)tm;
+    } else if (px == py) {             // L*L -> L (tiles I >= J: [J*T, end(I))), U*U -> U mirrored
+        for (int64_t I = 0; I < tm; ++I) {
+            const u128 c = chunks_up_to(row_end(I, n));
+            all += (u128)(I + 1) * c - (u128)q * (u128)I * (u128)(I + 1) / 2;
+            longest = std::max(longest, c);
+        }
+    } else if (px == kLower) {         // L*U: [0, end(min(I, J))): shell s has 2*(tm-s)-1 tiles
+        for (int64_t s = 0; s < tm; ++s) {
+            const u128 c = chunks_up_to(row_end(s, n));
+            all += c * (u128)(2 * (tm - s) - 1);
+            longest = std::max(longest, c);
+        }
+    } else {                           // U*L: [max(I, J)*T, n): shell s has 2*s+1 tiles
+        for (int64_t s = 0; s < tm; ++s) {
+            const u128 c = chunks_up_to(n - s * T);
+            all += c * (u128)(2 * s + 1);
+            longest = std::max(longest, c);
+        }
+    }
+    const u128 spread = (all + mom::kComputeUnits - 1) / mom::kComputeUnits;
+    const u128 matrix = std::max(longest, spread) * chunk_ps;
+    const u128 memory = 4 * (structural_entries(m, k, px) + structural_entries(k, n, py) +
+                             structural_entries(m, n, st.pc)) / 8;
+    u128 t = kLaunchPs + std::max(matrix, memory);
+    if (L.split_k > 1) t += kLaunchPs + 4 * (u128)(L.split_k + 1) * (u128)m * (u128)n / 8;
+    return t;
+}
+
 mom_status_t validate(const int64_t *dims, const int32_t *props, const int32_t *trans, int32_t n)
 {
     if (!dims || !props) return MOM_ERR_NULL;
@@ -117,7 +187,7 @@ struct Builder {
     std::vector<int> producer;         // temporary id -> index of the step that writes it
     size_t cursor = 0;
     int depth = 0, max_depth = 0;
-    u128 total = 0;
+    u128 total = 0, total_time = 0;
     bool ok = true;
 
     struct Value { mom::Operand op; int64_t rows, cols; int prop; };
@@ -143,6 +213,7 @@ struct Builder {
         st.tb = b.op.where == mom::Where::Factor && plan->trans[b.op.index];
         const u128 c = product_mults(st.m, st.k, st.n, st.pa, st.pb);
         total += c;
+        total_time += product_time_ps(st.m, st.k, st.n, st.pa, st.pb);
         st.mults = c > kU64Max ? std::numeric_limits<uint64_t>::max() : (uint64_t)c;
         auto level_of = [&](const mom::Operand &o) {
             return o.where == mom::Where::Temp ? plan->steps[producer[o.index]].level : 0;
@@ -274,6 +345,7 @@ mom_status_t finish(mom_plan *plan, const std::vector<int64_t> &d, const std::ve
     if (!b.ok || b.cursor != split_pos.size()) return MOM_ERR_BAD_SPLITS;
     if (b.total > kU64Max) return MOM_ERR_OVERFLOW;
     plan->cost = (uint64_t)b.total;
+    plan->time_ps = b.total_time > kU64Max ? std::numeric_limits<uint64_t>::max() : (uint64_t)b.total_time;
     plan->result_prop = root.prop;
     plan->stack_depth = b.max_depth;
     plan->splits.clear();
@@ -338,9 +410,12 @@ void start(mom_plan *plan, const int64_t *dims, const int32_t *props, const int3
     d.push_back(dims[n]);
 }
 
-// The chain DP: fewest multiplications for every sub-chain of the survivors, smallest split on
-// ties; returns the chosen tree as preorder positions.
-mom_status_t optimal_splits(const std::vector<int64_t> &d, const std::vector<int32_t> &p, std::vector<int32_t> &split_pos)
+// The chain DP: the smallest sum of product costs (multiplications, or modelled picoseconds)
+// for every sub-chain of the survivors, smallest split on ties; returns the chosen tree as
+// preorder positions.  Both costs are sums over the products of a tree, and the shape and
+// property of a sub-chain's product do not depend on its tree, so the recurrence is exact.
+mom_status_t optimal_splits(const std::vector<int64_t> &d, const std::vector<int32_t> &p, int objective,
+                            std::vector<int32_t> &split_pos)
 {
     const int m = (int)p.size();
     if (m <= 1) return MOM_OK;
@@ -361,7 +436,9 @@ mom_status_t optimal_splits(const std::vector<int64_t> &d, const std::vector<int
             int where = -1;
             for (int k = i; k < j; ++k) {       // ascending; only a strictly smaller cost
                 const u128 c = best[at(i, k)] + best[at(k + 1, j)] +
-                               product_mults(d[i], d[k + 1], d[j + 1], prop[at(i, k)], prop[at(k + 1, j)]);
+                               (objective == MOM_PLAN_MIN_TIME
+                                    ? product_time_ps(d[i], d[k + 1], d[j + 1], prop[at(i, k)], prop[at(k + 1, j)])
+                                    : product_mults(d[i], d[k + 1], d[j + 1], prop[at(i, k)], prop[at(k + 1, j)]));
                 if (where < 0 || c < lowest) { lowest = c; where = k; }   // replaces: smallest split wins ties
             }
             best[at(i, j)] = lowest;
@@ -390,7 +467,7 @@ mom_status_t make_plan(const int64_t *dims, const int32_t *props, const int32_t 
 {
     mom_status_t st = validate(dims, props, trans, n);
     if (st != MOM_OK) return st;
-    if (objective != MOM_PLAN_MIN_MULTS) return MOM_ERR_BAD_FLAGS;
+    if (objective != MOM_PLAN_MIN_MULTS && objective != MOM_PLAN_MIN_TIME) return MOM_ERR_BAD_FLAGS;
     std::unique_ptr<mom_plan> plan(new mom_plan());
     plan->objective = objective;
     std::vector<int64_t> d;
@@ -399,7 +476,7 @@ mom_status_t make_plan(const int64_t *dims, const int32_t *props, const int32_t 
     const int m = (int)p.size();
     std::vector<int32_t> split_pos;
     if (!forced_tree) {
-        st = optimal_splits(d, p, split_pos);
+        st = optimal_splits(d, p, objective, split_pos);
         if (st != MOM_OK) return st;
     } else if (m > 1) {
         if (!forced) return MOM_ERR_NULL;
@@ -462,6 +539,8 @@ mom_status_t mom_chain_plan_ex(const int64_t *dims, const int32_t *props, const 
 void mom_plan_destroy(mom_plan_t *plan) { delete plan; }
 
 uint64_t mom_plan_cost_mults(const mom_plan_t *plan) { return plan ? plan->cost : 0; }
+
+uint64_t mom_plan_cost_time_ps(const mom_plan_t *plan) { return plan ? plan->time_ps : 0; }
 
 int32_t mom_plan_num_products(const mom_plan_t *plan) { return plan ? (int32_t)plan->steps.size() : 0; }
 

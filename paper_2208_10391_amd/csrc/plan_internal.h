@@ -64,7 +64,8 @@ struct mom_plan {
     int32_t objective = 0;           // what the tree minimises (MOM_PLAN_MIN_MULTS / MOM_PLAN_MIN_TIME)
     std::vector<int32_t> survivors;  // original indices of the non-Identity factors
     std::vector<int32_t> splits;     // preorder, original indices, survivors-1 entries
-    uint64_t cost = 0;
+    uint64_t cost = 0;               // scalar multiplications of the tree
+    uint64_t time_ps = 0;            // modelled time of the tree (sum over its products)
     int64_t rows = 0, cols = 0;
     int32_t result_prop = 0;
     std::vector<mom::ProductStep> steps;      // post-order

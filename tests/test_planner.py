@@ -200,3 +200,42 @@ def test_plans_with_transposed_factors_equal_bruteforce():
     fptr = ctypes.cast(fake, ctypes.POINTER(ctypes.c_void_p))
     bad = mom.binding.STATUS_NAMES.index("MOM_ERR_BAD_STRIDE")
     assert lib.mom_chain_eval(p.handle, fptr, (ctypes.c_int64 * 2)(2, 2), ctypes.c_void_p(1024), 0, None, 0, 0, None) == bad
+
+
+def test_time_objective_equals_the_oracle_enumeration():
+    """MOM_PLAN_MIN_TIME: the library's DP (closed-form chunk sums) against the oracle's exhaustive
+    search over the same stated model (tile by tile): tree and picoseconds bit-exact."""
+    rng = np.random.default_rng(55)
+    pool = [1, 5, 31, 32, 33, 64, 65, 96, 127, 128, 129, 130, 200, 256, 300, 512, 1000, 2050, 4096]
+    checked = 0
+    for trial in range(2500):
+        n = int(rng.integers(1, 8))
+        props = [int(rng.choice([G, G, L, U, I])) for _ in range(n)]
+        dims = [int(rng.choice(pool))]
+        for q in props:
+            dims.append(dims[-1] if q != G else int(rng.choice(pool)))
+        trans = [int(x) for x in rng.integers(0, 2, size=n)] if trial % 3 == 0 else None
+        want = oracle.plan_bruteforce_time(dims, props, trans=trans)
+        plan = mom.mom_chain_plan_ex(dims, props, trans, objective=mom.MOM_PLAN_MIN_TIME)
+        assert (plan.cost_time_ps, plan.splits, plan.cost_mults) == (want["time_ps"], want["splits"], want["mults"]), (dims, props)
+        # the default objective is untouched, and any plan reports its modelled time
+        base = mom.mom_chain_plan(dims, props, trans=trans)
+        ref = oracle.plan_bruteforce(dims, props, trans=trans)
+        assert (base.cost_mults, base.splits) == (ref["cost"], ref["splits"])
+        assert base.cost_time_ps == oracle.tree_time_ps(dims, props, base.splits, trans=trans)
+        assert base.cost_time_ps >= plan.cost_time_ps and base.cost_mults <= plan.cost_mults
+        checked += 1
+    assert checked == 2500
+    # single products against the hand-worked values
+    for m, k, n, px, py, want in ([int(x) for x in ln.split()] for ln in golden_lines("time_model.txt")):
+        assert mom.mom_chain_plan([m, k, n], [px, py]).cost_time_ps == want
+    # the workloads keep their trees under the time model
+    for name in ("trmm4096", "general5", "mixed5"):
+        c = sc.CONFIGS[name]
+        a = mom.mom_chain_plan(c.dims, c.props)
+        b = mom.mom_chain_plan_ex(c.dims, c.props, None, objective=mom.MOM_PLAN_MIN_TIME)
+        assert a.splits == b.splits
+    # and one chain where the objectives part (see tests/test_oracle_time_model.py)
+    a = mom.mom_chain_plan([2050, 2050, 2050, 96], [U, L, G])
+    b = mom.mom_chain_plan_ex([2050, 2050, 2050, 96], [U, L, G], None, objective=mom.MOM_PLAN_MIN_TIME)
+    assert (a.string, b.string) == ("(0 (1 2))", "((0 1) 2)")
