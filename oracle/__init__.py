@@ -6,7 +6,7 @@ the GPU library, and the GPU library never falls back to it.
 
 Thin ctypes layer over oracle.c; every function documents the passage of the
 paper (MOM: Matrix Operations in MLIR) that it states.  Properties are the
-integers 0 general, 1 lowerTri, 2 upperTri, 3 Identity (Sec. 2).
+integers 0 general, 1 lowerTri, 2 upperTri, 3 Identity, 4 diagonal = {lowerTri, upperTri} (Sec. 2).
 """
 import ctypes
 from typing import List, Optional, Sequence, Tuple
@@ -15,7 +15,7 @@ import numpy as np
 
 from .build import build as _build
 
-GENERAL, LOWER_TRI, UPPER_TRI, IDENTITY = 0, 1, 2, 3
+GENERAL, LOWER_TRI, UPPER_TRI, IDENTITY, DIAGONAL = 0, 1, 2, 3, 4
 
 _lib = ctypes.CDLL(_build())
 

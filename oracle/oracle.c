@@ -8,7 +8,8 @@
  *
  * What it states (paper sections in brackets):
  *   - a chain  A_0 * A_1 * ... * A_{n-1}  of f32 matrices, each carrying one
- *     property: general, lowerTri, upperTri or Identity           [Sec. 2, "Matrix
+ *     property: general, lowerTri, upperTri or Identity, or the set
+ *     {lowerTri, upperTri} = diagonal                          [Sec. 2, "Matrix
  *     Attribute" and "Types: Matrix, Term and Identity"]
  *   - memory of a triangular matrix is a plain dense row-major buffer whose
  *     other half holds zeros; the diagonal is stored             [Sec. 2, bufferization]
@@ -38,7 +39,10 @@
 #include <stdlib.h>
 #include <string.h>
 
-enum { P_GENERAL = 0, P_LOWER = 1, P_UPPER = 2, P_IDENTITY = 3 };
+/* P_DIAGONAL is the property SET {lowerTri, upperTri}: a matrix that is both
+ * has zeros above and below the diagonal and an arbitrary stored diagonal
+ * [Sec. 2, Matrix Attribute: a set of non-conflicting properties].          */
+enum { P_GENERAL = 0, P_LOWER = 1, P_UPPER = 2, P_IDENTITY = 3, P_DIAGONAL = 4 };
 
 /* ------------------------------------------------------------------------ */
 /* Structure of a property: is position (i,j) allowed to be non-zero?       */
@@ -50,6 +54,7 @@ static int structurally_nonzero(int prop, int64_t i, int64_t j)
     case P_LOWER:    return j <= i;
     case P_UPPER:    return j >= i;
     case P_IDENTITY: return j == i;
+    case P_DIAGONAL: return j == i;
     default:         return 1;
     }
 }
@@ -70,12 +75,15 @@ uint64_t oracle_count_mults(int64_t m, int64_t k, int64_t n, int32_t pX, int32_t
 }
 
 /* ------------------------------------------------------------------------ */
-/* Property of a product of two operands.  Identity is neutral; equal       */
-/* triangles keep their triangle; everything else is general.               */
+/* Property of a product of two operands.  Identity is neutral; a diagonal   */
+/* operand only scales rows or columns, so the other operand's structure    */
+/* stays; equal triangles keep their triangle; everything else is general.  */
 static int product_property(int pX, int pY)
 {
     if (pX == P_IDENTITY) return pY;
     if (pY == P_IDENTITY) return pX;
+    if (pX == P_DIAGONAL) return pY;          /* scaling rows keeps the structure of Y */
+    if (pY == P_DIAGONAL) return pX;          /* scaling columns keeps that of X       */
     if (pX == pY && (pX == P_LOWER || pX == P_UPPER)) return pX;
     return P_GENERAL;
 }
@@ -102,6 +110,9 @@ static u128 product_cost(int64_t m, int64_t k, int64_t n, int pX, int pY)
     int triX = (pX == P_LOWER || pX == P_UPPER);
     int triY = (pY == P_LOWER || pY == P_UPPER);
     if (pX == P_IDENTITY || pY == P_IDENTITY) return 0;
+    /* a diagonal operand meets every structural entry of the other exactly once */
+    if (pX == P_DIAGONAL) return pY == P_DIAGONAL ? N : (triY ? N * (N + 1) / 2 : K * N);
+    if (pY == P_DIAGONAL) return triX ? M * (M + 1) / 2 : M * K;
     if (!triX && !triY) return M * K * N;
     if (triX && !triY)  return N * (M * (M + 1) / 2);          /* m == k */
     if (!triX && triY)  return M * (N * (N + 1) / 2);          /* k == n */
@@ -305,18 +316,27 @@ done:
 /*     8 bytes per picosecond                                                */
 /*   time = 6000000 (launch) + max(matrix, memory)                           */
 /*          + [split] 6000000 + 4 * (s + 1) * m * n / 8                      */
+/*   a product with a diagonal operand is an element-wise scaling pass:      */
+/*   time = 6000000 + memory                                                 */
 
 enum { TIME_LAUNCH_PS = 6000000, TIME_CHUNK128_PS = 1706667, TIME_CHUNK64_PS = 426667 };
 
 static u128 structural_entries(int64_t rows, int64_t cols, int prop)
 {
     if (prop == P_LOWER || prop == P_UPPER) return (u128)rows * (u128)(rows + 1) / 2;
+    if (prop == P_DIAGONAL) return (u128)rows;
     return (u128)rows * (u128)cols;
 }
 
 static u128 product_time(int64_t m, int64_t k, int64_t n, int pX, int pY)
 {
     if (pX == P_IDENTITY || pY == P_IDENTITY) return 0;           /* no computation at all */
+    if (pX == P_DIAGONAL || pY == P_DIAGONAL) {
+        /* rows or columns of the other operand scaled: an element-wise pass, memory only */
+        int pD = product_property(pX, pY);
+        return TIME_LAUNCH_PS + 4 * (structural_entries(m, k, pX) + structural_entries(k, n, pY) +
+                                     structural_entries(m, n, pD)) / 8;
+    }
     int64_t T = (m <= 64 || n <= 64) ? 64 : 128;
     u128 chunk_ps = T == 128 ? TIME_CHUNK128_PS : TIME_CHUNK64_PS;
     int pR = product_property(pX, pY);
@@ -567,6 +587,7 @@ static void k_range(int prop, int64_t i, int64_t k, int64_t *lo, int64_t *hi)   
     *lo = 0; *hi = k;
     if (prop == P_LOWER) *hi = i + 1;
     if (prop == P_UPPER) *lo = i;
+    if (prop == P_DIAGONAL) { *lo = i; *hi = i + 1; }
 }
 
 static void j_range(int prop, int64_t t, int64_t n, int64_t *lo, int64_t *hi)   /* j with Y[t][j] != 0 */
@@ -574,6 +595,7 @@ static void j_range(int prop, int64_t t, int64_t n, int64_t *lo, int64_t *hi)   
     *lo = 0; *hi = n;
     if (prop == P_LOWER) *hi = t + 1;
     if (prop == P_UPPER) *lo = t;
+    if (prop == P_DIAGONAL) { *lo = t; *hi = t + 1; }
 }
 
 /* p holds the properties the factors have INSIDE the chain (a transposed     */

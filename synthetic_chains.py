@@ -6,7 +6,7 @@ entries from a seed and writes the zeros a factor's property prescribes, as the
 Fill operation of the paper does when it initialises an object (Sec. 2, Table 1).
 
 Properties: 0 general, 1 lowerTri (zeros above the diagonal), 2 upperTri (zeros below
-the diagonal), 3 Identity (no buffer at all).  The diagonal of a triangular factor is
+the diagonal), 3 Identity (no buffer at all), 4 diagonal (both triangles' zeros).  The diagonal of a triangular factor is
 ordinary data.
 """
 from dataclasses import dataclass
@@ -14,7 +14,7 @@ from typing import List, Optional, Sequence
 
 import torch
 
-GENERAL, LOWER_TRI, UPPER_TRI, IDENTITY = 0, 1, 2, 3
+GENERAL, LOWER_TRI, UPPER_TRI, IDENTITY, DIAGONAL = 0, 1, 2, 3, 4
 
 
 @dataclass(frozen=True)
@@ -66,6 +66,8 @@ def make_factor(rows: int, cols: int, prop: int, seed: int, batch: int = 0) -> O
         a = torch.tril(a)
     elif prop == UPPER_TRI:
         a = torch.triu(a)
+    elif prop == DIAGONAL:
+        a = torch.tril(torch.triu(a))
     elif prop != GENERAL:
         raise ValueError("unknown property %r" % (prop,))
     return a.contiguous()
