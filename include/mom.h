@@ -19,7 +19,7 @@
  *     other half of its (dense, fully allocated) buffer may be loaded but is masked before any
  *     arithmetic, so whatever it holds, NaN included, never reaches a result.  Identity factors
  *     have no buffer.
- *   - lowerTri, upperTri and Identity factors must be square.
+ *   - lowerTri, upperTri, diagonal and Identity factors must be square.
  *   - Plans live in host memory, belong to the library until mom_plan_destroy, are immutable
  *     and may be evaluated concurrently on different streams with different workspaces.
  *   - The library never allocates, frees or synchronises device memory.  Inputs, output and
@@ -41,12 +41,19 @@
 extern "C" {
 #endif
 
-/* Matrix properties (Sec. 2, "Matrix Attribute"; Identity is the paper's Identity type). */
+/* Matrix properties (Sec. 2, "Matrix Attribute"; Identity is the paper's Identity type).
+ * The paper's attribute is a SET of non-conflicting properties; the one set with two members
+ * that this library knows is {lowerTri, upperTri} = MOM_DIAGONAL: zeros off the diagonal, the
+ * diagonal stored in a dense square buffer of which nothing else is ever read.  A product with
+ * a diagonal operand scales the rows (D*X) or columns (X*D) of the other operand, keeps that
+ * operand's structure, costs one multiplication per structural entry of it, and runs as an
+ * element-wise pass. */
 typedef enum {
     MOM_GENERAL   = 0,
     MOM_LOWER_TRI = 1,
     MOM_UPPER_TRI = 2,
-    MOM_IDENTITY  = 3
+    MOM_IDENTITY  = 3,
+    MOM_DIAGONAL  = 4
 } mom_prop_t;
 
 typedef enum {
@@ -88,7 +95,8 @@ typedef struct mom_plan mom_plan_t;   /* opaque */
  *   *out receives a new plan (NULL on error); release it with mom_plan_destroy.
  * Cost of X(m x k)*Y(k x n) = number of scalar products with no structurally-zero operand:
  *   general*general m*k*n; tri*general n*m(m+1)/2; general*tri m*n(n+1)/2;
- *   L*L, U*U n(n+1)(n+2)/6 (result keeps the triangle); L*U, U*L n(n+1)(2n+1)/6 (general).
+ *   L*L, U*U n(n+1)(n+2)/6 (result keeps the triangle); L*U, U*L n(n+1)(2n+1)/6 (general);
+ *   with a diagonal operand: the structural entries of the other one.
  * Among equal-cost trees the one with the smallest root split wins, recursively.
  */
 mom_status_t mom_chain_plan(const int64_t *dims, const int32_t *props, int32_t n, mom_plan_t **out);
@@ -122,7 +130,8 @@ mom_status_t mom_plan_from_splits(const int64_t *dims, const int32_t *props, int
  *   matrix = max(longest workgroup's chunks, ceil(all chunks / 256)) * (1706667 for T = 128,
  *   426667 for T = 64: one chunk of one tile at 256 FLOP per clock and 2.4 GHz);
  *   memory = 4 * (structural entries of X, Y and the result) / 8 (8 bytes per picosecond);
- *   time = 6000000 + max(matrix, memory)  [+ 6000000 + 4 * (s+1) * m * n / 8 when sliced].
+ *   time = 6000000 + max(matrix, memory)  [+ 6000000 + 4 * (s+1) * m * n / 8 when sliced];
+ *   a product with a diagonal operand is an element-wise pass: time = 6000000 + memory.
  * Ties go to the smallest root split, recursively, as for the multiplication count.
  */
 

@@ -12,7 +12,7 @@ import torch
 
 from . import build as _build
 
-MOM_GENERAL, MOM_LOWER_TRI, MOM_UPPER_TRI, MOM_IDENTITY = 0, 1, 2, 3
+MOM_GENERAL, MOM_LOWER_TRI, MOM_UPPER_TRI, MOM_IDENTITY, MOM_DIAGONAL = 0, 1, 2, 3, 4
 MOM_OK = 0
 MOM_OUT_ZERO_FILL_TRIANGLE = 1
 MOM_MAX_FACTORS = 1024

@@ -226,7 +226,8 @@ inline hipError_t launch_batched(const mom_plan *plan, const float *const *bases
     p.out_cols = (int)plan->cols;
     p.batch = batch;
     // three full, aligned 32x32 factors multiplied as X0 * (X1 * X2): the register-only kernel
-    if (nl == 3 && p.vec[0] && p.vec[1] && p.vec[2] && !p.trans[0] && !p.trans[1] && !p.trans[2] && p.num_products == 2 && p.a_slot[0] == 1 && p.b_slot[0] == 2 &&
+    const bool no_diagonal = p.prop[0] != kDiagonal && p.prop[1] != kDiagonal && p.prop[2] != kDiagonal;
+    if (nl == 3 && no_diagonal && p.vec[0] && p.vec[1] && p.vec[2] && !p.trans[0] && !p.trans[1] && !p.trans[2] && p.num_products == 2 && p.a_slot[0] == 1 && p.b_slot[0] == 2 &&
         p.a_slot[1] == 0 && p.b_slot[1] == 1) {
         hipLaunchKernelGGL(chain3_kernel_for(p.prop[0], p.prop[1], p.prop[2]), dim3((batch + 3) / 4), dim3(256), 0, stream, p);
         return hipGetLastError();

@@ -148,6 +148,24 @@ mom_status_t eval_chain(const mom_plan_t *plan, const float *const *d_factors, c
     };
     // The launches were laid out with the plan; only addresses are filled in here.
     for (const PlannedLaunch &pl : plan->launches) {
+        if (pl.kind == kLaunchScale) {                     // a diagonal operand: element-wise pass
+            const ProductStep &st = plan->steps[pl.step[0]];
+            const bool left = st.pa == kDiagonal;          // D * X, else X * D
+            const Resolved d = left ? resolve(st.a, st.k) : resolve(st.b, st.n);
+            const Resolved x = left ? resolve(st.b, st.n) : resolve(st.a, st.k);
+            const Resolved c = resolve(st.c, st.n);
+            const bool x_trans = left ? st.tb : st.ta;
+            ScaleParams sp;
+            sp.D = d.ptr; sp.ldd = d.ld;
+            sp.X = x.ptr; sp.x_rs = x_trans ? 1 : x.ld; sp.x_cs = x_trans ? x.ld : 1;
+            sp.C = const_cast<float *>(c.ptr); sp.ldc = c.ld;
+            sp.M = (int)st.m; sp.N = (int)st.n; sp.side = left ? 0 : 1;
+            sp.px = left ? st.pb : st.pa;
+            sp.vec = !x_trans && aligned16(x.ptr, x.ld) && aligned16(c.ptr, c.ld);
+            hipLaunchKernelGGL(diag_scale_kernel, rowwise_grid(sp.M, sp.N, 1), dim3(256), 0, stream, sp);
+            if (hipGetLastError() != hipSuccess) return MOM_ERR_HIP;
+            continue;
+        }
         ProductBatch batch = pl.batch;
         for (int i = 0; i < batch.count; ++i) {
             const ProductStep &st = plan->steps[pl.step[i]];
@@ -178,7 +196,7 @@ mom_status_t eval_chain(const mom_plan_t *plan, const float *const *d_factors, c
         }
     }
 
-    if (zero_fill && (plan->result_prop == kLower || plan->result_prop == kUpper)) {
+    if (zero_fill && (plan->result_prop == kLower || plan->result_prop == kUpper || plan->result_prop == kDiagonal)) {
         hipLaunchKernelGGL(zero_other_half_kernel, rowwise_grid(M, M, 1), dim3(256), 0, stream, d_out, ld_out, M,
                            plan->result_prop, (int)aligned16(d_out, ld_out));
         if (hipGetLastError() != hipSuccess) return MOM_ERR_HIP;

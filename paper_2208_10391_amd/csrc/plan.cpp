@@ -13,6 +13,7 @@
 
 namespace {
 
+using mom::kDiagonal;
 using mom::kGeneral;
 using mom::kIdentity;
 using mom::kLower;
@@ -24,12 +25,14 @@ constexpr u128 kU64Max = (u128)std::numeric_limits<uint64_t>::max();
 inline bool is_tri(int p) { return p == kLower || p == kUpper; }
 
 // Property of X*Y (Sec. 2: properties of intermediate results are inferred).  With Identity
-// below the triangles below general, this is the join of the two operand properties:
-// equal triangles keep their triangle, anything else fills the matrix.
+// below diagonal (= {lowerTri, upperTri}) below the triangles below general, this is the join of
+// the two operand properties: equal triangles keep their triangle, anything else fills the matrix.
 inline int join(int px, int py)
 {
     if (px == kIdentity) return py;
     if (py == kIdentity) return px;
+    if (px == kDiagonal) return py;      // rows scaled: the structure of the other operand stays
+    if (py == kDiagonal) return px;      // columns scaled
     if (px == py) return px;
     return kGeneral;
 }
@@ -38,6 +41,9 @@ inline int join(int px, int py)
 u128 product_mults(int64_t m, int64_t k, int64_t n, int px, int py)
 {
     const u128 M = (u128)m, K = (u128)k, N = (u128)n;
+    // a diagonal operand meets every structural entry of the other operand exactly once
+    if (px == kDiagonal) return py == kDiagonal ? N : (is_tri(py) ? N * (N + 1) / 2 : K * N);
+    if (py == kDiagonal) return is_tri(px) ? M * (M + 1) / 2 : M * K;
     if (!is_tri(px) && !is_tri(py)) return M * K * N;
     if (is_tri(px) && !is_tri(py)) return N * (M * (M + 1) / 2);       // row i of X has i+1 (or m-i) entries
     if (!is_tri(px) && is_tri(py)) return M * (N * (N + 1) / 2);
@@ -57,6 +63,7 @@ constexpr uint64_t kLaunchPs = 6000000, kChunk128Ps = 1706667, kChunk64Ps = 4266
 
 u128 structural_entries(int64_t rows, int64_t cols, int p)
 {
+    if (p == kDiagonal) return (u128)rows;
     return is_tri(p) ? (u128)rows * (u128)(rows + 1) / 2 : (u128)rows * (u128)cols;
 }
 
@@ -64,6 +71,9 @@ u128 product_time_ps(int64_t m, int64_t k, int64_t n, int px, int py)
 {
     mom::ProductStep st{};
     st.m = m; st.k = k; st.n = n; st.pa = px; st.pb = py; st.pc = join(px, py);
+    if (mom::is_scaling(st))           // element-wise pass: launch + bytes
+        return kLaunchPs + 4 * (structural_entries(m, k, px) + structural_entries(k, n, py) +
+                                structural_entries(m, n, st.pc)) / 8;
     const mom::Launch L = mom::choose_launch(st);
     const int64_t T = L.bm, q = T / 32, tm = L.tiles_m, tn = L.tiles_n;
     const u128 chunk_ps = L.shape == mom::kTile128 ? kChunk128Ps : kChunk64Ps;
@@ -126,7 +136,7 @@ mom_status_t validate(const int64_t *dims, const int32_t *props, const int32_t *
     for (int i = 0; i <= n; ++i)
         if (dims[i] <= 0 || dims[i] > (int64_t)MOM_MAX_DIM) return MOM_ERR_BAD_DIM;
     for (int i = 0; i < n; ++i) {
-        if (props[i] < kGeneral || props[i] > kIdentity) return MOM_ERR_BAD_PROP;
+        if (props[i] < kGeneral || props[i] > kDiagonal) return MOM_ERR_BAD_PROP;
         if (props[i] != kGeneral && dims[i] != dims[i + 1]) return MOM_ERR_NOT_SQUARE;
         if (trans && trans[i] != 0 && trans[i] != 1) return MOM_ERR_BAD_TRANS;
     }
@@ -263,6 +273,19 @@ mom_status_t lay_out_launches(mom_plan *plan)
         for (size_t first = next; first < level_end; ++first) {
             if (done[first - next]) continue;
             PlannedLaunch pl{};
+            if (is_scaling(plan->steps[order[first]])) {        // an element-wise pass of its own
+                const ProductStep &st = plan->steps[order[first]];
+                done[first - next] = 1;
+                pl.kind = kLaunchScale;
+                pl.step[0] = order[first];
+                pl.batch.count = 1;
+                ProductParams &p = pl.batch.prob[0];
+                p.M = (int)st.m; p.N = (int)st.n; p.K = (int)st.k;
+                p.pa = st.pa; p.pb = st.pb; p.pc = st.pc;
+                plan->launches.push_back(pl);
+                continue;
+            }
+            pl.kind = kLaunchProduct;
             pl.shape = choose_launch(plan->steps[order[first]]).shape;
             pl.variant = (plan->steps[order[first]].ta ? 1 : 0) + (plan->steps[order[first]].tb ? 2 : 0);
             int64_t reduce_quads = 0;
@@ -270,7 +293,7 @@ mom_status_t lay_out_launches(mom_plan *plan)
             for (size_t i = first; i < level_end && pl.batch.count < kMaxFused; ++i) {
                 const ProductStep &st = plan->steps[order[i]];
                 const Launch L = choose_launch(st);
-                if (done[i - next] || L.shape != pl.shape || (st.ta ? 1 : 0) + (st.tb ? 2 : 0) != pl.variant) continue;
+                if (done[i - next] || is_scaling(st) || L.shape != pl.shape || (st.ta ? 1 : 0) + (st.tb ? 2 : 0) != pl.variant) continue;
                 const bool small_launch = (int64_t)L.grid * L.split_k <= 4 * kComputeUnits;
                 if (pl.batch.count > 0 && (!small_launch || !batch_small)) continue;
                 batch_small = small_launch;

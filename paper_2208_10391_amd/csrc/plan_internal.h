@@ -9,7 +9,8 @@
 
 namespace mom {
 
-enum : int { kGeneral = 0, kLower = 1, kUpper = 2, kIdentity = 3 };
+// kDiagonal is the property set {lowerTri, upperTri}: zeros off the diagonal, the diagonal stored.
+enum : int { kGeneral = 0, kLower = 1, kUpper = 2, kIdentity = 3, kDiagonal = 4 };
 
 // Where an operand of a binary product lives.
 enum class Where : int { Factor = 0, Temp = 1, Out = 2 };
@@ -42,6 +43,9 @@ struct Temp {
 // launches.  A launch carries up to kMaxFused independent products of one level; when some of
 // them are cut along k, one slice-sum launch follows.
 struct PlannedLaunch {
+    int kind;                        // kLaunchProduct, or kLaunchScale: one product with a diagonal
+                                     // operand, run as an element-wise scaling pass (batch.prob[0]
+                                     // carries its shapes and properties)
     int shape;                       // TileShape of the product kernel
     int variant;                     // which operands are stored transposed (ProductVariant)
     int step[kMaxFused];             // index into mom_plan::steps of batch.prob[i]
@@ -50,6 +54,8 @@ struct PlannedLaunch {
     int reduce_of[kMaxFused];        // reduce.prob[i] sums the slices of batch.prob[reduce_of[i]]
     unsigned reduce_grid_x;
 };
+
+enum : int { kLaunchProduct = 0, kLaunchScale = 1 };
 
 constexpr int kBatchedSlots = 8;     // surviving factors the batched kernels hold at once
 

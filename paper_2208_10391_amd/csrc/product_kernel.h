@@ -27,10 +27,11 @@ namespace mom {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-// Is (i, j) inside the structure of property p?  (p is never Identity here.)
+// Is (i, j) inside the structure of property p?  (p is never Identity here; diagonal, the last
+// case, reaches the batched and the element-wise kernels only.)
 __device__ __forceinline__ bool in_structure(int p, int i, int j)
 {
-    return p == kGeneral ? true : (p == kLower ? j <= i : j >= i);
+    return p == kGeneral ? true : (p == kLower ? j <= i : (p == kUpper ? j >= i : j == i));
 }
 
 __device__ __forceinline__ int isqrt_floor(int64_t x)

@@ -58,9 +58,17 @@ inline int tile_order(const ProductStep &st)
     return kRowMajor;
 }
 
+// A product with a diagonal operand scales the rows or columns of the other operand: it runs
+// as an element-wise pass, not through the tiled kernel.
+inline bool is_scaling(const ProductStep &st) { return st.pa == kDiagonal || st.pb == kDiagonal; }
+
 inline Launch choose_launch(const ProductStep &st)
 {
     Launch L{};
+    if (is_scaling(st)) {
+        L.shape = kTile128; L.bm = L.bn = 128; L.split_k = 1;
+        return L;
+    }
     const bool small = st.m <= 64 || st.n <= 64;
     L.shape = small ? kTile64 : kTile128;
     L.bm = L.bn = small ? 64 : 128;

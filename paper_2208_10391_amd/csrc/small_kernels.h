@@ -58,8 +58,8 @@ constexpr int kRowUnroll = 4;          // rows a thread has in flight at once
 // Columns [lo, hi) of row i that lie inside the structure of property p (N columns in all).
 __device__ __forceinline__ void structure_span(int p, int i, int N, int &lo, int &hi)
 {
-    lo = p == kUpper ? min(i, N) : 0;
-    hi = p == kLower ? min(i + 1, N) : N;
+    lo = (p == kUpper || p == kDiagonal) ? min(i, N) : 0;
+    hi = (p == kLower || p == kDiagonal) ? min(i + 1, N) : N;
 }
 
 // out = A restricted to its structure (single surviving factor: A*I -> A)
@@ -126,6 +126,47 @@ __global__ __launch_bounds__(256) void copy_transposed_kernel(const float *S, in
     }
 }
 
+// A product with a diagonal operand: C = D * X (side 0: row i of X scaled by D[i][i]) or
+// C = X * D (side 1: column j scaled by D[j][j]), written inside the structure px of X, which
+// is also the result's.  X is addressed through a row and a column stride, so a factor stored
+// transposed is read in place; D's own transposition does not matter.
+struct ScaleParams {
+    const float *D;
+    int64_t ldd;
+    const float *X;
+    int64_t x_rs, x_cs;
+    float *C;
+    int64_t ldc;
+    int M, N, side, px, vec;
+};
+
+__global__ __launch_bounds__(256) void diag_scale_kernel(const ScaleParams p)
+{
+    const int quads = (p.N + 3) / 4;
+    for (int i = blockIdx.y; i < p.M; i += gridDim.y) {
+        int lo, hi;
+        structure_span(p.px, i, p.N, lo, hi);
+        const float di = p.side == 0 ? p.D[(int64_t)i * (p.ldd + 1)] : 0.0f;
+        for (int q = blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += gridDim.x * blockDim.x) {
+            const int j = 4 * q;
+            if (j >= hi || j + 4 <= lo) continue;
+            if (p.vec && j >= lo && j + 4 <= hi) {
+                f32x4 v = *reinterpret_cast<const f32x4 *>(p.X + (int64_t)i * p.x_rs + j);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] *= p.side == 0 ? di : p.D[(int64_t)(j + e) * (p.ldd + 1)];
+                *reinterpret_cast<f32x4 *>(p.C + (int64_t)i * p.ldc + j) = v;
+            } else {
+                for (int e = 0; e < 4; ++e) {
+                    const int c = j + e;
+                    if (c < lo || c >= hi) continue;
+                    const float d = p.side == 0 ? di : p.D[(int64_t)c * (p.ldd + 1)];
+                    p.C[(int64_t)i * p.ldc + c] = d * p.X[(int64_t)i * p.x_rs + (int64_t)c * p.x_cs];
+                }
+            }
+        }
+    }
+}
+
 // out = I (every factor was an Identity: I*I = I)
 __global__ __launch_bounds__(256) void write_identity_kernel(float *C, int64_t ldc, int M, int vec)
 {
@@ -147,17 +188,19 @@ __global__ __launch_bounds__(256) void zero_other_half_kernel(float *C, int64_t 
 {
     const int quads = (M + 3) / 4;
     for (int i = blockIdx.y; i < M; i += gridDim.y) {
-        // the other half of row i: columns (i, M) of a lowerTri result, [0, i) of an upperTri one
-        const int lo = prop == kLower ? i + 1 : 0, hi = prop == kLower ? M : i;
+        // the other half of row i: columns (i, M) of a lowerTri result, [0, i) of an upperTri
+        // one, both for a diagonal one; [s0, s1) is the structure, which is left alone
+        int s0, s1;
+        structure_span(prop, i, M, s0, s1);
         for (int q = blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += gridDim.x * blockDim.x) {
             const int j = 4 * q;
-            if (j + 4 <= lo || j >= hi) continue;
-            if (vec && j >= lo && j + 4 <= hi) {
+            if (j >= s0 && j + 4 <= s1) continue;
+            if (vec && j + 4 <= M && (j + 4 <= s0 || j >= s1)) {
                 const f32x4 z = {0.0f, 0.0f, 0.0f, 0.0f};
                 *reinterpret_cast<f32x4 *>(C + (int64_t)i * ldc + j) = z;
             } else {
                 for (int e = 0; e < 4; ++e)
-                    if (j + e >= lo && j + e < hi) C[(int64_t)i * ldc + j + e] = 0.0f;
+                    if (j + e < M && (j + e < s0 || j + e >= s1)) C[(int64_t)i * ldc + j + e] = 0.0f;
             }
         }
     }

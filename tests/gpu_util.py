@@ -6,7 +6,7 @@ import oracle
 import paper_2208_10391_amd as mom
 import synthetic_chains as sc
 
-G, L, U, I = 0, 1, 2, 3
+G, L, U, I, D = 0, 1, 2, 3, 4
 TOL = 1e-4          # max relative Frobenius error against the f64 oracle
 
 
@@ -23,7 +23,7 @@ def structure_mask(prop: int, rows: int, cols: int) -> np.ndarray:
         return np.tril(ones)
     if prop == U:
         return np.triu(ones)
-    if prop == I:
+    if prop in (I, D):
         return np.eye(rows, cols, dtype=bool)
     return ones
 
@@ -31,10 +31,11 @@ def structure_mask(prop: int, rows: int, cols: int) -> np.ndarray:
 def poison_other_half(t: torch.Tensor, prop: int) -> torch.Tensor:
     """Device copy of a triangular factor whose zero half holds NaN: the library must not let
     it reach a result (it only ever reads the triangle)."""
-    if prop not in (L, U):
+    if prop not in (L, U, D):
         return t
     nan = torch.full_like(t, float("nan"))
-    keep = torch.tril(torch.ones_like(t, dtype=torch.bool)) if prop == L else torch.triu(torch.ones_like(t, dtype=torch.bool))
+    ones = torch.ones_like(t, dtype=torch.bool)
+    keep = torch.tril(ones) if prop == L else torch.triu(ones) if prop == U else torch.tril(torch.triu(ones))
     return torch.where(keep, t, nan)
 
 
@@ -116,7 +117,7 @@ def check_against_dense(dims, props, factors, splits=None, flags=0, **kw):
     err = rel_fro(np.where(mask, got, 0.0), np.where(mask, want, 0.0))
     assert err <= TOL, "relative Frobenius error %.3e" % err
     assert_close_by_tiles(got, want, prop)
-    if prop in (L, U):
+    if prop in (L, U, D):
         other = got[~mask]
         if flags & mom.MOM_OUT_ZERO_FILL_TRIANGLE:
             assert np.all(other == 0.0), "other half must be zero-filled"

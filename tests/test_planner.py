@@ -239,3 +239,25 @@ def test_time_objective_equals_the_oracle_enumeration():
     a = mom.mom_chain_plan([2050, 2050, 2050, 96], [U, L, G])
     b = mom.mom_chain_plan_ex([2050, 2050, 2050, 96], [U, L, G], None, objective=mom.MOM_PLAN_MIN_TIME)
     assert (a.string, b.string) == ("(0 (1 2))", "((0 1) 2)")
+
+
+def test_plans_with_diagonal_factors_equal_bruteforce_under_both_objectives():
+    D = 4
+    rng = np.random.default_rng(91)
+    pool = [1, 5, 32, 64, 65, 130, 256, 1000]
+    for trial in range(2000):
+        n = int(rng.integers(1, 8))
+        props = [int(rng.choice([G, L, U, I, D, D])) for _ in range(n)]
+        dims = [int(rng.choice(pool))]
+        for q in props:
+            dims.append(dims[-1] if q != G else int(rng.choice(pool)))
+        want = oracle.plan_bruteforce(dims, props)
+        plan = mom.mom_chain_plan(dims, props)
+        assert (plan.cost_mults, plan.splits, plan.result[2]) == (want["cost"], want["splits"], want["result_prop"])
+        wt = oracle.plan_bruteforce_time(dims, props)
+        pt = mom.mom_chain_plan_ex(dims, props, None, objective=mom.MOM_PLAN_MIN_TIME)
+        assert (pt.cost_time_ps, pt.splits, pt.cost_mults) == (wt["time_ps"], wt["splits"], wt["mults"])
+    assert mom.mom_chain_plan([6, 6, 6], [D, D]).result == (6, 6, D)
+    assert mom.mom_chain_plan([6, 6, 6], [D, I]).result == (6, 6, D)
+    assert status_of(mom.mom_chain_plan, [6, 7], [D]) == mom.binding.STATUS_NAMES.index("MOM_ERR_NOT_SQUARE")
+    assert status_of(mom.mom_chain_plan, [6, 6], [5]) == mom.binding.STATUS_NAMES.index("MOM_ERR_BAD_PROP")
