@@ -49,6 +49,10 @@ _lib.oracle_plan_bruteforce_time.argtypes = [ctypes.c_int32, _i64p, _i32p, ctype
                                              ctypes.POINTER(ctypes.c_uint64), _i32p, _i32p]
 _lib.oracle_tree_time.restype = ctypes.c_int
 _lib.oracle_tree_time.argtypes = [ctypes.c_int32, _i64p, _i32p, _i32p, ctypes.POINTER(ctypes.c_uint64)]
+_lib.oracle_sum_property.restype = ctypes.c_int32
+_lib.oracle_sum_property.argtypes = [ctypes.c_int32, _i32p]
+_lib.oracle_add_dense.restype = ctypes.c_int
+_lib.oracle_add_dense.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, _i32p, _i32p, _fpp, _f64p]
 _lib.oracle_max_threads.restype = ctypes.c_int
 
 
@@ -268,3 +272,54 @@ def eval_plan(dims, props, factors, splits, trans=None) -> Tuple[np.ndarray, int
         raise ValueError("malformed split list")
     del keep
     return out, int(rprop.value)
+
+
+def sum_property(props, trans=None) -> int:
+    """Property of a sum of terms (Table 1, Add): the smallest structure that holds every term's."""
+    p = _props(chain_props(props, trans))
+    return int(_lib.oracle_sum_property(len(p), p.ctypes.data_as(_i32p)))
+
+
+def add_dense(rows: int, cols: int, props, terms, trans=None) -> np.ndarray:
+    """The variadic Add by its plain definition: entry-wise f64 sum of the terms in their order
+    (Table 1, Add; Sec. 2, Operations).  A transposed term is stored cols x rows; Identity is eye."""
+    p = _props(props)
+    n = len(p)
+    keep = []
+    ptrs = (ctypes.c_void_p * n)()
+    for t in range(n):
+        if terms[t] is None:
+            if p[t] != IDENTITY:
+                raise ValueError("term %d has no buffer but is not an Identity" % t)
+            ptrs[t] = None
+            continue
+        a = np.ascontiguousarray(np.asarray(terms[t], dtype=np.float32))
+        want = (cols, rows) if (trans is not None and trans[t]) else (rows, cols)
+        if a.shape != want:
+            raise ValueError("term %d has shape %s, expected %s" % (t, a.shape, want))
+        keep.append(a)
+        ptrs[t] = a.ctypes.data
+    tp, tkeep = _trans(trans, n)
+    out = np.zeros((rows, cols), dtype=np.float64)
+    rc = _lib.oracle_add_dense(rows, cols, n, p.ctypes.data_as(_i32p), tp, ctypes.cast(ptrs, _fpp),
+                               out.ctypes.data_as(_f64p))
+    if rc != 0:
+        raise ValueError("oracle_add_dense failed: %d" % rc)
+    del keep
+    return out
+
+
+def equation_dense(chains) -> np.ndarray:
+    """A sum of chain products (mixed Add / Mul, Sec. 2 Operations): every addend by the dense
+    definition of the chain product, added up in order.  chains: list of (dims, props, factors,
+    trans or None)."""
+    total = None
+    for dims, props, factors, trans in chains:
+        term = eval_dense(dims, props, factors, trans=trans)
+        total = term if total is None else total + term
+    return total
+
+
+def equation_property(chains) -> int:
+    """Property of the sum of the chains' products."""
+    return sum_property([plan_bruteforce(d, p, trans=t)["result_prop"] for d, p, _, t in chains])

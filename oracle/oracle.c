@@ -22,6 +22,9 @@
  *     the properties of operands and intermediates into account
  *                                      [Sec. 2, "Operations" and "Transformations"]
  *
+ *   - Add is variadic as well: the sum of any number of equally shaped terms,
+ *     whose structure is the union of the terms' structures
+ *                                      [Table 1 "Add"; Sec. 2, "Operations"]
  *   - an opt-in second objective: a stated integer time model of one tiled
  *     product on the GPU, summed over the tree  [motivated by Sec. 4, Results]
  *
@@ -691,6 +694,55 @@ int oracle_eval_plan(int32_t n, const int64_t *dims, const int32_t *props,
                      double *out, int32_t *result_prop)
 {
     return oracle_eval_plan_t(n, dims, props, NULL, factors, splits, out, result_prop);
+}
+
+/* ------------------------------------------------------------------------ */
+/* Variadic Add [Table 1, "Add"; Sec. 2, Operations: Mul and Add take an     */
+/* arbitrary number of values].                                              */
+
+/*
+ * Property of a sum of terms with the given properties (as they stand in the
+ * sum, transposed terms already mirrored): the smallest structure that holds
+ * every term's structure.  One term keeps its property; several terms that
+ * are all Identity or diagonal give a diagonal (I + I has 2 on its diagonal:
+ * no Identity); diagonal / Identity / lowerTri terms give lowerTri; the same
+ * for upperTri; anything else is general.
+ */
+int32_t oracle_sum_property(int32_t n, const int32_t *props)
+{
+    if (n == 1) return props[0];
+    int any_lower = 0, any_upper = 0, any_general = 0;
+    for (int t = 0; t < n; ++t) {
+        if (props[t] == P_LOWER) any_lower = 1;
+        else if (props[t] == P_UPPER) any_upper = 1;
+        else if (props[t] == P_GENERAL) any_general = 1;
+    }
+    if (any_general || (any_lower && any_upper)) return P_GENERAL;
+    if (any_lower) return P_LOWER;
+    if (any_upper) return P_UPPER;
+    return P_DIAGONAL;
+}
+
+/*
+ * out[i][j] = sum over the terms, in their order, of term t's entry (i, j),
+ * in double precision; every term is rows x cols (a transposed term is
+ * stored cols x rows), Identity terms are eye.  No property logic.
+ */
+int oracle_add_dense(int64_t rows, int64_t cols, int32_t n, const int32_t *props, const int32_t *trans,
+                     const float *const *terms, double *out)
+{
+    if (n <= 0) return 1;
+    for (int64_t i = 0; i < rows; ++i)
+        for (int64_t j = 0; j < cols; ++j) {
+            double s = 0.0;
+            for (int t = 0; t < n; ++t) {
+                if (props[t] == P_IDENTITY) s += (i == j) ? 1.0 : 0.0;
+                else if (trans && trans[t]) s += (double)terms[t][j * rows + i];
+                else s += (double)terms[t][i * cols + j];
+            }
+            out[i * cols + j] = s;
+        }
+    return 0;
 }
 
 int oracle_max_threads(void)
