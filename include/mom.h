@@ -262,6 +262,46 @@ mom_status_t mom_chain_eval_batched(const mom_plan_t *plan, const float *const *
                                     int64_t out_batch_stride, int32_t batch, void *stream);
 
 /*
+ * Sums of chain products: the paper's Equation with its variadic Add and Mul (Table 1, "Add",
+ * "Mul", "Equation"; Sec. 2, "Operations").  out = C_0 + C_1 + ... where every addend C_c is a
+ * chain of chain_len[c] factors (a chain of one factor is a plain matrix term, so a pure
+ * variadic Add is an equation whose chains all have length 1; an all-Identity chain adds I).
+ *   chain_len [host] n_chains lengths, each 1..MOM_MAX_FACTORS.
+ *   dims      [host] the chains' dimension lists one after the other (chain_len[c] + 1 each);
+ *   props, trans (may be NULL) [host] one entry per factor, chain after chain, with the
+ *             meaning they have in mom_chain_plan_ex; every chain must have the same rows x cols
+ *             (MOM_ERR_BAD_DIM otherwise).
+ *   objective as in mom_chain_plan_ex; every addend gets its own optimal tree.
+ * The sum's property is the smallest structure that holds every addend's: one addend keeps its
+ * property; Identity / diagonal addends give MOM_DIAGONAL (I + I is not an Identity); adding
+ * lowerTri addends gives lowerTri, upperTri likewise; anything else is general.
+ * No algebraic rewriting across addends (common factors are not pulled out).
+ */
+typedef struct mom_equation mom_equation_t;   /* opaque, host memory, immutable */
+mom_status_t mom_equation_plan(const int64_t *dims, const int32_t *props, const int32_t *trans,
+                               const int32_t *chain_len, int32_t n_chains, int32_t objective, mom_equation_t **out);
+void mom_equation_destroy(mom_equation_t *eq);                 /* NULL is allowed */
+mom_status_t mom_equation_result(const mom_equation_t *eq, int64_t *rows, int64_t *cols, int32_t *prop);
+uint64_t mom_equation_cost_mults(const mom_equation_t *eq);    /* multiplications of all addends */
+size_t mom_equation_workspace_bytes(const mom_equation_t *eq);
+int32_t mom_equation_num_chains(const mom_equation_t *eq);
+/* The plan of addend c (borrowed: it lives as long as the equation), NULL when out of range. */
+const mom_plan_t *mom_equation_chain(const mom_equation_t *eq, int32_t c);
+
+/*
+ * Enqueue the evaluation of the equation on `stream`; same rules as mom_chain_eval (caller's
+ * memory, no allocation, no synchronisation, only the sum's structure is written unless
+ * MOM_OUT_ZERO_FILL_TRIANGLE is set).  d_factors / lds [host]: one entry per factor, chain
+ * after chain.  Addends that are plain matrices are summed by one element-wise launch per eight
+ * of them; an addend with products is evaluated by the chain evaluator, straight into d_out
+ * when its result has the sum's structure, otherwise (and for every further one) into a
+ * temporary in the workspace that an element-wise launch then adds to d_out.
+ */
+mom_status_t mom_equation_eval(const mom_equation_t *eq, const float *const *d_factors, const int64_t *lds,
+                               float *d_out, int64_t ld_out, void *d_workspace, size_t workspace_bytes,
+                               uint32_t flags, void *stream);
+
+/*
  * Calibration aid for measurements (not a step of the method): enqueue one launch of a
  * register-only v_mfma_f32_32x32x2_f32 loop, the rate the matrix pipes of this GPU sustain
  * with no memory traffic at all, which is what the product kernels' f32 throughput (the f32

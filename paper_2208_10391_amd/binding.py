@@ -27,7 +27,9 @@ MOM_PLAN_MIN_MULTS, MOM_PLAN_MIN_TIME = 0, 1
 
 EXPORTS = ["mom_chain_plan", "mom_plan_from_splits", "mom_chain_plan_ex", "mom_plan_destroy", "mom_plan_cost_mults", "mom_plan_cost_time_ps",
            "mom_plan_num_products", "mom_plan_result", "mom_plan_string", "mom_plan_splits",
-           "mom_plan_product", "mom_plan_num_launches", "mom_plan_workspace_bytes", "mom_init", "mom_chain_eval", "mom_chain_eval_static", "mom_chain_eval_batched", "mom_probe_mfma_peak",
+           "mom_plan_product", "mom_plan_num_launches", "mom_plan_workspace_bytes", "mom_init", "mom_chain_eval", "mom_chain_eval_static", "mom_chain_eval_batched", "mom_equation_plan", "mom_equation_destroy", "mom_equation_result",
+           "mom_equation_cost_mults", "mom_equation_workspace_bytes", "mom_equation_num_chains", "mom_equation_chain",
+           "mom_equation_eval", "mom_probe_mfma_peak",
            "mom_status_string"]
 
 
@@ -88,6 +90,23 @@ _lib.mom_chain_eval_static.argtypes = [ctypes.c_void_p, _vpp, _i64p, ctypes.c_vo
 _lib.mom_chain_eval_batched.restype = ctypes.c_int
 _lib.mom_chain_eval_batched.argtypes = [ctypes.c_void_p, _vpp, _i64p, ctypes.c_void_p, ctypes.c_int64,
                                         ctypes.c_int32, ctypes.c_void_p]
+_lib.mom_equation_plan.restype = ctypes.c_int
+_lib.mom_equation_plan.argtypes = [_i64p, _i32p, _i32p, _i32p, ctypes.c_int32, ctypes.c_int32, _vpp]
+_lib.mom_equation_destroy.restype = None
+_lib.mom_equation_destroy.argtypes = [ctypes.c_void_p]
+_lib.mom_equation_result.restype = ctypes.c_int
+_lib.mom_equation_result.argtypes = [ctypes.c_void_p, _i64p, _i64p, _i32p]
+_lib.mom_equation_cost_mults.restype = ctypes.c_uint64
+_lib.mom_equation_cost_mults.argtypes = [ctypes.c_void_p]
+_lib.mom_equation_workspace_bytes.restype = ctypes.c_size_t
+_lib.mom_equation_workspace_bytes.argtypes = [ctypes.c_void_p]
+_lib.mom_equation_num_chains.restype = ctypes.c_int32
+_lib.mom_equation_num_chains.argtypes = [ctypes.c_void_p]
+_lib.mom_equation_chain.restype = ctypes.c_void_p
+_lib.mom_equation_chain.argtypes = [ctypes.c_void_p, ctypes.c_int32]
+_lib.mom_equation_eval.restype = ctypes.c_int
+_lib.mom_equation_eval.argtypes = [ctypes.c_void_p, _vpp, _i64p, ctypes.c_void_p, ctypes.c_int64,
+                                   ctypes.c_void_p, ctypes.c_size_t, ctypes.c_uint32, ctypes.c_void_p]
 _lib.mom_probe_mfma_peak.restype = ctypes.c_int
 _lib.mom_probe_mfma_peak.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
 _lib.mom_status_string.restype = ctypes.c_char_p
@@ -401,6 +420,109 @@ def mom_chain_eval_batched(plan: Plan, factors: Sequence[Optional[torch.Tensor]]
                            out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     """One call of the C entry point: marshal (bind_chain_eval_batched) and enqueue."""
     return bind_chain_eval_batched(plan, factors, out)(stream)
+
+
+class Equation:
+    """Owner of a mom_equation_t handle: a sum of chains.  chains: list of (dims, props, trans or None)."""
+
+    def __init__(self, handle: int, chains):
+        self.handle = ctypes.c_void_p(handle)
+        self.chains = [([int(d) for d in dims], [int(p) for p in props],
+                        [0] * len(props) if trans is None else [1 if t else 0 for t in trans])
+                       for dims, props, trans in chains]
+
+    def __del__(self):
+        if getattr(self, "handle", None):
+            _lib.mom_equation_destroy(self.handle)
+            self.handle = None
+
+    @property
+    def result(self):
+        r, c, p = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int32()
+        st = _lib.mom_equation_result(self.handle, ctypes.byref(r), ctypes.byref(c), ctypes.byref(p))
+        if st != MOM_OK:
+            raise MomError(st, "mom_equation_result")
+        return int(r.value), int(c.value), int(p.value)
+
+    @property
+    def cost_mults(self) -> int:
+        return int(_lib.mom_equation_cost_mults(self.handle))
+
+    @property
+    def workspace_bytes(self) -> int:
+        return int(_lib.mom_equation_workspace_bytes(self.handle))
+
+    def chain_string(self, c: int) -> str:
+        """Parenthesisation of addend c."""
+        h = _lib.mom_equation_chain(self.handle, int(c))
+        buf = ctypes.create_string_buffer(16 * len(self.chains[c][1]) + 16)
+        st = _lib.mom_plan_string(ctypes.c_void_p(h), buf, len(buf))
+        if st != MOM_OK:
+            raise MomError(st, "mom_plan_string")
+        return buf.value.decode()
+
+
+def mom_equation_plan(chains, objective: int = MOM_PLAN_MIN_MULTS) -> Equation:
+    """chains: list of (dims, props, trans or None), every chain with the same rows x cols."""
+    dims, props, trans, lens = [], [], [], []
+    any_trans = any(t is not None for _, _, t in chains)
+    for d, p, t in chains:
+        if len(d) != len(p) + 1:
+            raise ValueError("dims must have len(props)+1 entries")
+        dims += list(d)
+        props += list(p)
+        trans += [0] * len(p) if t is None else list(t)
+        lens.append(len(p))
+    out = ctypes.c_void_p()
+    st = _lib.mom_equation_plan(_i64(dims), _i32(props), _i32(trans) if any_trans else None, _i32(lens), len(lens),
+                                int(objective), ctypes.byref(out))
+    if st != MOM_OK:
+        raise MomError(st, "mom_equation_plan")
+    return Equation(out.value, chains)
+
+
+def mom_equation_eval(eq: Equation, factors: Sequence[Sequence[Optional[torch.Tensor]]], out: Optional[torch.Tensor] = None,
+                      workspace: Optional[torch.Tensor] = None, flags: int = 0, stream=None) -> torch.Tensor:
+    """factors[c][t]: the buffer of factor t of addend c (None for Identity), stored shape."""
+    flat, stored = [], []
+    for (dims, props, trans), fs in zip(eq.chains, factors):
+        if len(fs) != len(props):
+            raise ValueError("wrong number of factors in an addend")
+        for t, f in enumerate(fs):
+            r, c = (dims[t + 1], dims[t]) if trans[t] else (dims[t], dims[t + 1])
+            flat.append(f)
+            stored.append((r, c))
+    n = len(flat)
+    ptrs = (ctypes.c_void_p * n)()
+    lds = (ctypes.c_int64 * n)()
+    for i, (f, (r, c)) in enumerate(zip(flat, stored)):
+        if f is None:
+            ptrs[i] = None
+            lds[i] = c
+            continue
+        _check_factor(f, "factor %d" % i)
+        if f.dim() != 2 or tuple(f.shape) != (r, c) or f.stride(1) != 1:
+            raise ValueError("factor %d must be %dx%d with unit column stride" % (i, r, c))
+        ptrs[i] = f.data_ptr()
+        lds[i] = f.stride(0) if r > 1 else max(f.stride(0), c)
+    rows, cols, _ = eq.result
+    dev = next((f.device for f in flat if f is not None), torch.device("cuda", torch.cuda.current_device()))
+    if out is None:
+        out = torch.empty((rows, cols), dtype=torch.float32, device=dev)
+    _check_factor(out, "out")
+    if tuple(out.shape) != (rows, cols) or out.stride(1) != 1:
+        raise ValueError("out must be %dx%d with unit column stride" % (rows, cols))
+    need = eq.workspace_bytes
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    ld_out = out.stride(0) if rows > 1 else max(out.stride(0), cols)
+    st = _lib.mom_equation_eval(eq.handle, ctypes.cast(ptrs, _vpp), lds, ctypes.c_void_p(out.data_ptr()), ld_out,
+                                ctypes.c_void_p(ws_ptr), ws_bytes, int(flags), _stream_handle(stream))
+    if st != MOM_OK:
+        raise MomError(st, "mom_equation_eval")
+    return out
 
 
 def mom_probe_mfma_peak(iters: int, sink: torch.Tensor, stream=None) -> float:

@@ -266,6 +266,102 @@ extern "C" mom_status_t mom_chain_eval_static(const mom_plan_t *plan, const floa
     return eval_chain(plan, d_factors, lds, d_out, ld_out, ws, flags, stream);
 }
 
+// Sum of chain products: addends without products (single matrices, Identity) are summed by the
+// add kernel, up to kMaxAddTerms per launch; an addend with products is evaluated by the chain
+// evaluator, straight into the output when it may go first, else into a temporary that the add
+// kernel then accumulates.
+extern "C" mom_status_t mom_equation_eval(const mom_equation_t *eq, const float *const *d_factors, const int64_t *lds,
+                                          float *d_out, int64_t ld_out, void *d_workspace, size_t workspace_bytes,
+                                          uint32_t flags, void *stream_)
+{
+    if (!eq || !d_out) return MOM_ERR_NULL;
+    if (flags & ~(uint32_t)MOM_OUT_ZERO_FILL_TRIANGLE) return MOM_ERR_BAD_FLAGS;
+    if (ld_out == 0) ld_out = eq->cols;
+    if (ld_out < eq->cols) return MOM_ERR_BAD_STRIDE;
+    const int n_chains = (int)eq->chains.size();
+    for (int c = 0; c < n_chains; ++c) {                   // every addend's own argument checks first
+        const mom_plan_t *plan = eq->chains[c];
+        int64_t ld = ld_out;
+        const int32_t at = eq->first_factor[c];
+        if (!d_factors && !plan->survivors.empty()) return MOM_ERR_NULL;
+        const mom_status_t st = check_eval_arguments(plan, d_factors ? d_factors + at : nullptr, lds ? lds + at : nullptr,
+                                                     d_out, ld, 0);
+        if (st != MOM_OK) return st;
+    }
+    if (eq->workspace_bytes > 0 &&
+        (!d_workspace || workspace_bytes < eq->workspace_bytes || (reinterpret_cast<uintptr_t>(d_workspace) & 255)))
+        return MOM_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    mom_status_t st = ensure_device_ready(true, stream);
+    if (st != MOM_OK) return st;
+    char *const ws = static_cast<char *>(d_workspace);
+    float *const temp = reinterpret_cast<float *>(ws + eq->temp_offset);
+    const int M = (int)eq->rows, N = (int)eq->cols;
+
+    bool written = false;                                  // does the output hold a partial sum yet?
+    if (eq->direct_chain >= 0) {
+        const int c = eq->direct_chain, at = eq->first_factor[c];
+        st = eval_chain(eq->chains[c], d_factors + at, lds ? lds + at : nullptr, d_out, ld_out, ws, 0, stream);
+        if (st != MOM_OK) return st;
+        written = true;
+    }
+    AddParams ap{};
+    auto flush = [&]() -> mom_status_t {                   // launch what has been gathered
+        if (ap.count == 0 && written) return MOM_OK;
+        ap.C = d_out; ap.ldc = ld_out; ap.M = M; ap.N = N; ap.pc = eq->result_prop;
+        ap.accumulate = written ? 1 : 0;
+        ap.c_vec = aligned16(d_out, ld_out);
+        hipLaunchKernelGGL(add_terms_kernel, rowwise_grid(M, N, 1), dim3(256), 0, stream, ap);
+        if (hipGetLastError() != hipSuccess) return MOM_ERR_HIP;
+        written = true;
+        ap.count = 0;
+        return MOM_OK;
+    };
+    auto gather = [&](const float *ptr, int64_t ld, bool transposed, int prop) -> mom_status_t {
+        const int t = ap.count++;
+        ap.X[t] = ptr;
+        ap.rs[t] = transposed ? 1 : ld;
+        ap.cs[t] = transposed ? ld : 1;
+        ap.prop[t] = prop;
+        ap.vec[t] = ptr && !transposed && aligned16(ptr, ld);
+        return ap.count == kMaxAddTerms ? flush() : MOM_OK;
+    };
+    for (int c = 0; c < n_chains; ++c) {                   // addends that are plain matrices
+        const mom_plan_t *plan = eq->chains[c];
+        if (!plan->steps.empty()) continue;
+        if (plan->survivors.empty()) {
+            st = gather(nullptr, 0, false, kIdentity);
+        } else {
+            const int32_t f = plan->survivors[0], at = eq->first_factor[c];
+            const int64_t ld = lds ? lds[at + f] : (plan->trans[f] ? plan->dims[f] : plan->dims[f + 1]);
+            st = gather(d_factors[at + f], ld, plan->trans[f] != 0, plan->chain_props[f]);
+        }
+        if (st != MOM_OK) return st;
+    }
+    for (int c = 0; c < n_chains; ++c) {                   // addends with products, through the temporary
+        const mom_plan_t *plan = eq->chains[c];
+        if (plan->steps.empty() || c == eq->direct_chain) continue;
+        st = flush();                                      // the temporary is about to be overwritten
+        if (st != MOM_OK) return st;
+        const int at = eq->first_factor[c];
+        st = eval_chain(plan, d_factors + at, lds ? lds + at : nullptr, temp, N, ws, 0, stream);
+        if (st != MOM_OK) return st;
+        st = gather(temp, N, false, plan->result_prop);
+        if (st != MOM_OK) return st;
+        st = flush();
+        if (st != MOM_OK) return st;
+    }
+    st = flush();
+    if (st != MOM_OK) return st;
+    const int rp = eq->result_prop;
+    if ((flags & MOM_OUT_ZERO_FILL_TRIANGLE) && (rp == kLower || rp == kUpper || rp == kDiagonal)) {
+        hipLaunchKernelGGL(zero_other_half_kernel, rowwise_grid(M, M, 1), dim3(256), 0, stream, d_out, ld_out, M, rp,
+                           (int)aligned16(d_out, ld_out));
+        if (hipGetLastError() != hipSuccess) return MOM_ERR_HIP;
+    }
+    return MOM_OK;
+}
+
 extern "C" mom_status_t mom_chain_eval_batched(const mom_plan_t *plan, const float *const *d_factor_bases,
                                                const int64_t *batch_strides, float *d_out,
                                                int64_t out_batch_stride, int32_t batch, void *stream_)

@@ -559,6 +559,99 @@ mom_status_t mom_chain_plan_ex(const int64_t *dims, const int32_t *props, const 
     });
 }
 
+// Property of a sum: the smallest structure that holds every addend's structure.  One addend
+// keeps its property; several Identity / diagonal addends give a diagonal (never an Identity).
+static int sum_property(const std::vector<int> &props)
+{
+    if (props.size() == 1) return props[0];
+    bool lower = false, upper = false, general = false;
+    for (int p : props) {
+        lower |= p == kLower;
+        upper |= p == kUpper;
+        general |= p == kGeneral;
+    }
+    if (general || (lower && upper)) return kGeneral;
+    return lower ? kLower : (upper ? kUpper : kDiagonal);
+}
+
+mom_status_t mom_equation_plan(const int64_t *dims, const int32_t *props, const int32_t *trans,
+                               const int32_t *chain_len, int32_t n_chains, int32_t objective, mom_equation_t **out)
+{
+    if (!out) return MOM_ERR_NULL;
+    *out = nullptr;
+    if (!dims || !props || !chain_len) return MOM_ERR_NULL;
+    if (n_chains <= 0 || n_chains > MOM_MAX_FACTORS) return MOM_ERR_BAD_N;
+    return guarded([&]() -> mom_status_t {
+        std::unique_ptr<mom_equation> eq(new mom_equation());
+        std::vector<int> result_props;
+        int64_t factor_at = 0, dim_at = 0;
+        size_t largest_products_ws = 0;
+        bool any_products = false;
+        u128 cost = 0, time = 0;
+        for (int c = 0; c < n_chains; ++c) {
+            const int32_t len = chain_len[c];
+            if (len <= 0 || len > MOM_MAX_FACTORS) return MOM_ERR_BAD_N;
+            mom_plan_t *plan = nullptr;
+            const mom_status_t st = make_plan(dims + dim_at, props + factor_at, trans ? trans + factor_at : nullptr, len,
+                                              objective, false, nullptr, &plan);
+            if (st != MOM_OK) return st;
+            eq->chains.push_back(plan);
+            eq->first_factor.push_back((int32_t)factor_at);
+            if (c == 0) { eq->rows = plan->rows; eq->cols = plan->cols; }
+            if (plan->rows != eq->rows || plan->cols != eq->cols) return MOM_ERR_BAD_DIM;
+            result_props.push_back(plan->result_prop);
+            cost += plan->cost;
+            time += plan->time_ps;
+            if (!plan->steps.empty()) {
+                any_products = true;
+                largest_products_ws = std::max(largest_products_ws, plan->workspace_bytes);
+            }
+            factor_at += len;
+            dim_at += len + 1;
+        }
+        if (cost > kU64Max) return MOM_ERR_OVERFLOW;
+        eq->cost = (uint64_t)cost;
+        eq->time_ps = time > kU64Max ? std::numeric_limits<uint64_t>::max() : (uint64_t)time;
+        eq->result_prop = sum_property(result_props);
+        // the first addend with products whose result fills the sum's structure goes straight to
+        // the output; every other addend with products passes through one temporary
+        int through_temp = 0;
+        for (int c = 0; c < n_chains; ++c) {
+            if (eq->chains[c]->steps.empty()) continue;
+            if (eq->direct_chain < 0 && eq->chains[c]->result_prop == eq->result_prop) eq->direct_chain = c;
+            else ++through_temp;
+        }
+        eq->chain_bytes = any_products ? (largest_products_ws + 255) & ~(size_t)255 : 0;
+        eq->temp_offset = eq->chain_bytes;
+        const size_t temp = through_temp ? (size_t)eq->rows * (size_t)eq->cols * sizeof(float) : 0;
+        eq->workspace_bytes = eq->chain_bytes + temp;
+        *out = eq.release();
+        return MOM_OK;
+    });
+}
+
+void mom_equation_destroy(mom_equation_t *eq) { delete eq; }
+
+mom_status_t mom_equation_result(const mom_equation_t *eq, int64_t *rows, int64_t *cols, int32_t *prop)
+{
+    if (!eq) return MOM_ERR_NULL;
+    if (rows) *rows = eq->rows;
+    if (cols) *cols = eq->cols;
+    if (prop) *prop = eq->result_prop;
+    return MOM_OK;
+}
+
+uint64_t mom_equation_cost_mults(const mom_equation_t *eq) { return eq ? eq->cost : 0; }
+
+size_t mom_equation_workspace_bytes(const mom_equation_t *eq) { return eq ? eq->workspace_bytes : 0; }
+
+int32_t mom_equation_num_chains(const mom_equation_t *eq) { return eq ? (int32_t)eq->chains.size() : 0; }
+
+const mom_plan_t *mom_equation_chain(const mom_equation_t *eq, int32_t c)
+{
+    return (eq && c >= 0 && c < (int32_t)eq->chains.size()) ? eq->chains[c] : nullptr;
+}
+
 void mom_plan_destroy(mom_plan_t *plan) { delete plan; }
 
 uint64_t mom_plan_cost_mults(const mom_plan_t *plan) { return plan ? plan->cost : 0; }

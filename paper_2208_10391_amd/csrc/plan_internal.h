@@ -90,3 +90,22 @@ struct mom_plan {
     int32_t stack_depth = 0;
     int32_t a_slot[mom::kBatchedSlots] = {}, b_slot[mom::kBatchedSlots] = {};
 };
+
+// A sum of chain products (the paper's Equation holding variadic Add and Mul): one plan per
+// addend, all of one shape.
+struct mom_equation {
+    std::vector<mom_plan *> chains;          // owned
+    std::vector<int32_t> first_factor;       // position of chain c's first factor in the caller's arrays
+    int64_t rows = 0, cols = 0;
+    int32_t result_prop = 0;
+    int32_t direct_chain = -1;               // addend with products whose result has the sum's own
+                                             // structure: evaluated straight into the output
+    uint64_t cost = 0, time_ps = 0;
+    size_t chain_bytes = 0;                  // largest workspace of any addend
+    size_t temp_offset = 0;                  // one rows x cols temporary behind it (0 bytes if unused)
+    size_t workspace_bytes = 0;
+    ~mom_equation()
+    {
+        for (mom_plan *p : chains) delete p;
+    }
+};

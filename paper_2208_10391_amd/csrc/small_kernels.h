@@ -167,6 +167,66 @@ __global__ __launch_bounds__(256) void diag_scale_kernel(const ScaleParams p)
     }
 }
 
+// Variadic Add (paper Table 1): C = [C +] sum of up to kMaxAddTerms terms, each with its own
+// structure (an Identity term has no buffer and adds 1 on the diagonal), written inside the
+// structure `pc` of the sum.  Terms are addressed through a row and a column stride, so a term
+// stored transposed is read in place.
+constexpr int kMaxAddTerms = 8;
+struct AddParams {
+    const float *X[kMaxAddTerms];
+    int64_t rs[kMaxAddTerms], cs[kMaxAddTerms];
+    int prop[kMaxAddTerms], vec[kMaxAddTerms];
+    int count;
+    float *C;
+    int64_t ldc;
+    int M, N, pc, accumulate, c_vec;
+};
+
+__global__ __launch_bounds__(256) void add_terms_kernel(const AddParams p)
+{
+    const int quads = (p.N + 3) / 4;
+    for (int i = blockIdx.y; i < p.M; i += gridDim.y) {
+        int lo, hi;
+        structure_span(p.pc, i, p.N, lo, hi);
+        for (int q = blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += gridDim.x * blockDim.x) {
+            const int j = 4 * q;
+            if (j >= hi || j + 4 <= lo) continue;
+            const bool whole = p.c_vec && j >= lo && j + 4 <= hi;
+            float *dst = p.C + (int64_t)i * p.ldc + j;
+            f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (p.accumulate) {
+                if (whole) {
+                    s = *reinterpret_cast<const f32x4 *>(dst);
+                } else {
+                    for (int e = 0; e < 4; ++e)
+                        if (j + e >= lo && j + e < hi) s[e] = dst[e];
+                }
+            }
+            for (int t = 0; t < p.count; ++t) {
+                if (p.prop[t] == kIdentity) {
+                    for (int e = 0; e < 4; ++e) s[e] += (j + e == i) ? 1.0f : 0.0f;
+                    continue;
+                }
+                int tlo, thi;
+                structure_span(p.prop[t], i, p.N, tlo, thi);
+                if (j >= thi || j + 4 <= tlo) continue;
+                if (p.vec[t] && j >= tlo && j + 4 <= thi) {
+                    s += *reinterpret_cast<const f32x4 *>(p.X[t] + (int64_t)i * p.rs[t] + j);
+                } else {
+                    for (int e = 0; e < 4; ++e)
+                        if (j + e >= tlo && j + e < thi) s[e] += p.X[t][(int64_t)i * p.rs[t] + (int64_t)(j + e) * p.cs[t]];
+                }
+            }
+            if (whole) {
+                *reinterpret_cast<f32x4 *>(dst) = s;
+            } else {
+                for (int e = 0; e < 4; ++e)
+                    if (j + e >= lo && j + e < hi) dst[e] = s[e];
+            }
+        }
+    }
+}
+
 // out = I (every factor was an Identity: I*I = I)
 __global__ __launch_bounds__(256) void write_identity_kernel(float *C, int64_t ldc, int M, int vec)
 {

@@ -261,3 +261,41 @@ def test_plans_with_diagonal_factors_equal_bruteforce_under_both_objectives():
     assert mom.mom_chain_plan([6, 6, 6], [D, I]).result == (6, 6, D)
     assert status_of(mom.mom_chain_plan, [6, 7], [D]) == mom.binding.STATUS_NAMES.index("MOM_ERR_NOT_SQUARE")
     assert status_of(mom.mom_chain_plan, [6, 6], [5]) == mom.binding.STATUS_NAMES.index("MOM_ERR_BAD_PROP")
+
+
+def test_equation_plans_sum_property_cost_and_errors():
+    # Table 1 Add / Equation: a sum of chains; every addend planned like a chain of its own
+    D = 4
+    rng = np.random.default_rng(101)
+    for trial in range(300):
+        n = int(rng.choice([1, 3, 8, 20]))
+        k = int(rng.integers(1, 5))
+        chains = []
+        for c in range(k):
+            length = int(rng.integers(1, 4))
+            props = [int(rng.choice([G, L, U, I, D])) for _ in range(length)]
+            trans = [int(x) for x in rng.integers(0, 2, size=length)]
+            chains.append(([n] * (length + 1), props, trans))
+        eq = mom.mom_equation_plan(chains)
+        want_prop = oracle.equation_property([(d, p, None, t) for d, p, t in chains])
+        assert eq.result == (n, n, want_prop)
+        assert eq.cost_mults == sum(oracle.plan_bruteforce(d, p, trans=t)["cost"] for d, p, t in chains)
+        for c, (d, p, t) in enumerate(chains):
+            assert eq.chain_string(c) == oracle.plan_string(p, oracle.plan_bruteforce(d, p, trans=t)["splits"])
+    # a pure variadic Add needs no workspace; a single product-bearing addend goes straight to the output
+    assert mom.mom_equation_plan([([5, 5], [G], None)] * 4).workspace_bytes == 0
+    assert mom.mom_equation_plan([([5, 5, 5], [G, G], None), ([5, 5], [G], None)]).workspace_bytes == 0
+    two = mom.mom_equation_plan([([64, 64, 64], [G, G], None), ([64, 64, 64], [L, G], None)])
+    assert two.workspace_bytes == 64 * 64 * 4
+    code = {n: i for i, n in enumerate(mom.binding.STATUS_NAMES)}
+    assert status_of(mom.mom_equation_plan, [([5, 5], [G], None), ([5, 6], [G], None)]) == code["MOM_ERR_BAD_DIM"]
+    assert status_of(mom.mom_equation_plan, []) == code["MOM_ERR_BAD_N"]
+    assert status_of(mom.mom_equation_plan, [([5, 6], [L], None)]) == code["MOM_ERR_NOT_SQUARE"]
+    lib = mom.library()
+    assert lib.mom_equation_eval(None, None, None, None, 0, None, 0, 0, None) == code["MOM_ERR_NULL"]
+    assert lib.mom_equation_eval(two.handle, None, None, ctypes.c_void_p(1024), 0, None, 0, 0, None) == code["MOM_ERR_NULL"]
+    fake = (ctypes.c_void_p * 4)(256, 512, 768, 1024)
+    fptr = ctypes.cast(fake, ctypes.POINTER(ctypes.c_void_p))
+    assert lib.mom_equation_eval(two.handle, fptr, None, ctypes.c_void_p(1024), 0, None, 0, 0, None) == code["MOM_ERR_WORKSPACE"]
+    assert lib.mom_equation_eval(two.handle, fptr, None, ctypes.c_void_p(1024), 0, None, 0, 8, None) == code["MOM_ERR_BAD_FLAGS"]
+    assert lib.mom_equation_eval(two.handle, fptr, None, ctypes.c_void_p(1024), 3, None, 0, 0, None) == code["MOM_ERR_BAD_STRIDE"]
