@@ -57,7 +57,7 @@ def kernel_sources_digest():
     import hashlib
     h = hashlib.sha256()
     # what decides the kernels and their launch geometry; the planner's host code is left out
-    names = ("batched_kernel.h", "eval.hip", "launch_params.h", "product_kernel.h", "product_variant.h",
+    names = ("batched_kernel.h", "eval.hip", "launch_params.h", "product_kernel.h", "product_variant.h", "skinny_pair_kernel.h",
              "schedule.h", "small_kernels.h")
     for path in (os.path.join(ROOT, "paper_2208_10391_amd", "csrc", n) for n in names):
         with open(path, "rb") as f:

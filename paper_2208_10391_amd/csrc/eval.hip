@@ -7,6 +7,7 @@
 #include "product_variant.h"
 #include "schedule.h"
 #include "small_kernels.h"
+#include "skinny_pair_kernel.h"
 #include "batched_kernel.h"
 
 #include <hip/hip_runtime.h>
@@ -45,7 +46,11 @@ hipError_t configure_kernels()
         const hipError_t e = kConfigurers[v]();
         if (e != hipSuccess) return e;
     }
-    return hipSuccess;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&skinny_pair_kernel<true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kPairLdsBytes);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&skinny_pair_kernel<false>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, kPairLdsBytes);
 }
 
 // Make the current device ready for launches.  `stream` is the stream an evaluation is about
@@ -163,6 +168,25 @@ mom_status_t eval_chain(const mom_plan_t *plan, const float *const *d_factors, c
             sp.px = left ? st.pb : st.pa;
             sp.vec = !x_trans && aligned16(x.ptr, x.ld) && aligned16(c.ptr, c.ld);
             hipLaunchKernelGGL(diag_scale_kernel, rowwise_grid(sp.M, sp.N, 1), dim3(256), 0, stream, sp);
+            if (hipGetLastError() != hipSuccess) return MOM_ERR_HIP;
+            continue;
+        }
+        if (pl.kind == kLaunchPair) {                      // (X * Y) * Z, narrow intermediate kept on chip
+            const ProductStep &inner = plan->steps[pl.step[0]], &outer = plan->steps[pl.step[1]];
+            const Resolved x = resolve(inner.a, inner.k), y = resolve(inner.b, inner.n);
+            const Resolved z = resolve(outer.b, outer.n), c = resolve(outer.c, outer.n);
+            SkinnyPairParams sp;
+            sp.X = x.ptr; sp.Y = y.ptr; sp.Z = z.ptr; sp.C = const_cast<float *>(c.ptr);
+            sp.ldx = x.ld; sp.ldy = y.ld; sp.ldz = z.ld; sp.ldc = c.ld;
+            sp.M = (int)inner.m; sp.K1 = (int)inner.k; sp.W = (int)inner.n; sp.N = (int)outer.n;
+            sp.x_vec = aligned16(x.ptr, x.ld); sp.c_vec = aligned16(c.ptr, c.ld);
+            sp.yz_vec = ((reinterpret_cast<uintptr_t>(y.ptr) | reinterpret_cast<uintptr_t>(z.ptr)) & 7) == 0 &&
+                        ((y.ld | z.ld) & 1) == 0;
+            const dim3 grid((sp.M + kPairRows - 1) / kPairRows);
+            if (skinny_pair_is_fast(sp))
+                hipLaunchKernelGGL(skinny_pair_kernel<true>, grid, dim3(kPairThreads), kPairLdsBytes, stream, sp);
+            else
+                hipLaunchKernelGGL(skinny_pair_kernel<false>, grid, dim3(kPairThreads), kPairLdsBytes, stream, sp);
             if (hipGetLastError() != hipSuccess) return MOM_ERR_HIP;
             continue;
         }

@@ -264,6 +264,20 @@ mom_status_t lay_out_launches(mom_plan *plan)
 {
     using namespace mom;
     const std::vector<int32_t> &order = plan->order;
+    // products whose narrow result is consumed as the left operand of a product they can share
+    // a launch with: absorbed_by[i] = the consumer's step index
+    std::vector<int> absorbed_by(plan->steps.size(), -1), absorbs(plan->steps.size(), -1);
+    for (size_t j = 0; j < plan->steps.size(); ++j) {
+        const ProductStep &outer = plan->steps[j];
+        if (outer.a.where != Where::Temp) continue;
+        for (size_t i = 0; i < plan->steps.size(); ++i) {
+            const ProductStep &inner = plan->steps[i];
+            if (inner.c.where == Where::Temp && inner.c.index == outer.a.index && fits_skinny_pair(inner, outer)) {
+                absorbed_by[i] = (int)j;
+                absorbs[j] = (int)i;
+            }
+        }
+    }
     size_t next = 0;
     while (next < order.size()) {
         const int level = plan->steps[order[next]].level;
@@ -273,6 +287,18 @@ mom_status_t lay_out_launches(mom_plan *plan)
         for (size_t first = next; first < level_end; ++first) {
             if (done[first - next]) continue;
             PlannedLaunch pl{};
+            if (absorbed_by[order[first]] >= 0) {               // runs inside its consumer's launch
+                done[first - next] = 1;
+                continue;
+            }
+            if (absorbs[order[first]] >= 0) {                   // (X * Y) * Z in one launch
+                done[first - next] = 1;
+                pl.kind = kLaunchPair;
+                pl.step[0] = absorbs[order[first]];
+                pl.step[1] = order[first];
+                plan->launches.push_back(pl);
+                continue;
+            }
             if (is_scaling(plan->steps[order[first]])) {        // an element-wise pass of its own
                 const ProductStep &st = plan->steps[order[first]];
                 done[first - next] = 1;
@@ -293,7 +319,8 @@ mom_status_t lay_out_launches(mom_plan *plan)
             for (size_t i = first; i < level_end && pl.batch.count < kMaxFused; ++i) {
                 const ProductStep &st = plan->steps[order[i]];
                 const Launch L = choose_launch(st);
-                if (done[i - next] || is_scaling(st) || L.shape != pl.shape || (st.ta ? 1 : 0) + (st.tb ? 2 : 0) != pl.variant) continue;
+                if (done[i - next] || is_scaling(st) || absorbed_by[order[i]] >= 0 || absorbs[order[i]] >= 0 ||
+                    L.shape != pl.shape || (st.ta ? 1 : 0) + (st.tb ? 2 : 0) != pl.variant) continue;
                 const bool small_launch = (int64_t)L.grid * L.split_k <= 4 * kComputeUnits;
                 if (pl.batch.count > 0 && (!small_launch || !batch_small)) continue;
                 batch_small = small_launch;

@@ -55,7 +55,9 @@ struct PlannedLaunch {
     unsigned reduce_grid_x;
 };
 
-enum : int { kLaunchProduct = 0, kLaunchScale = 1 };
+// kLaunchPair: two products (X * Y) * Z with a narrow intermediate in one launch of the
+// skinny-pair kernel; step[0] is X * Y (whose temporary is never written), step[1] the consumer.
+enum : int { kLaunchProduct = 0, kLaunchScale = 1, kLaunchPair = 2 };
 
 constexpr int kBatchedSlots = 8;     // surviving factors the batched kernels hold at once
 

@@ -62,6 +62,18 @@ inline int tile_order(const ProductStep &st)
 // as an element-wise pass, not through the tiled kernel.
 inline bool is_scaling(const ProductStep &st) { return st.pa == kDiagonal || st.pb == kDiagonal; }
 
+// (X * Y) * Z runs as one launch of the skinny-pair kernel when the intermediate has at most
+// 64 columns, everything is general and stored as read, there are enough 32-row blocks to fill
+// the chip, and the second product is wide enough to be worth keeping the rows in registers.
+constexpr int kPairMinRowBlocks = 192, kPairMinCols = 256;
+inline bool fits_skinny_pair(const ProductStep &inner, const ProductStep &outer)
+{
+    const bool general = inner.pa == kGeneral && inner.pb == kGeneral && outer.pb == kGeneral;
+    const bool as_read = !inner.ta && !inner.tb && !outer.tb;
+    return general && as_read && inner.n <= 64 && inner.n >= 8 && (inner.m + 31) / 32 >= kPairMinRowBlocks &&
+           outer.n >= kPairMinCols;
+}
+
 inline Launch choose_launch(const ProductStep &st)
 {
     Launch L{};

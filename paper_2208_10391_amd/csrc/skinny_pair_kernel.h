@@ -1,0 +1,268 @@
+// Two products in one launch when the intermediate is narrow: C = (X * Y) * Z with X (M x K1),
+// Y (K1 x W), W <= 64, and Z (W x N), all general and stored as they are read.  The tiled
+// kernel would run X * Y on few workgroups (M/64 tiles of 64 x 64) and then (X Y) * Z as a
+// k = W product that spends its time loading, storing and starting up; here a workgroup
+// keeps its 32 rows of T = X * Y in registers and multiplies them into every column strip of
+// the result, so T never reaches memory and one launch replaces two.
+//
+// Layout trick (the one the batched kernel uses): v_mfma_f32_32x32x2_f32 is fed B-operand
+// first, so register v of lane (l32, half) of an accumulator holds row l32 and the block's
+// column i(v) = 8*(v/4) + 4*half + v%4.  A 64-column strip is handled as two 32-column blocks
+// that INTERLEAVE: block b holds the strip's columns 2*i + b, so a lane fetches both blocks'
+// operand values for one k with a single 8-byte load (columns 2*l32, 2*l32 + 1) and stores
+// eight consecutive columns of its row with two 16-byte stores.
+//   phase 1: T = X * Y.  The workgroup's 32 rows of X go to LDS, 512 columns at a time, with
+//            coalesced 16-byte loads that are all in flight at once (read lane-per-row straight
+//            from memory, a wavefront would touch 32 cache lines per load).  The four
+//            wavefronts split k (groups of 8 k-values, interleaved), each accumulates a partial
+//            T in two accumulators (even / odd columns of T) with Y straight from memory; the
+//            partials are summed through LDS so that every wavefront holds T.  A lane then
+//            owns T[l32][2*i(v) + b] for v = 0..15, b = 0, 1.
+//   phase 2: since the order of summation over k is free, those 32 values ARE the A-operand
+//            values of the second product when MFMA step (b, v) sums k = 2*i(v) + b; Z is
+//            fetched in that same k order.  Wavefront w takes column strips w, w+4, ... (from
+//            a starting point that differs between workgroups); per strip 64 MFMAs from
+//            registers, Z straight from memory, half a strip's loads in flight under the other
+//            half's MFMAs.
+// In both phases loads are issued a whole batch ahead from two register sets in turn, never
+// behind a branch (past the end the last valid batch is fetched again and dropped), and with at
+// most 32 loads per batch: the hardware counts at most 63 outstanding memory operations, so a
+// larger batch could not be told apart from the one before it.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "product_kernel.h"
+
+namespace mom {
+
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kPairRows = 32;            // rows of the result per workgroup
+constexpr int kPairMaxWidth = 64;        // widest intermediate (two interleaved 32-column blocks)
+constexpr int kPairWaves = 4;            // wavefronts per workgroup, one per SIMD
+constexpr int kPairThreads = 64 * kPairWaves;
+constexpr int kPairBatch = 4;            // k-groups of 8 a wavefront fetches per register set (16 loads of Y)
+constexpr int kPartLd = 36;              // LDS floats per lane and wavefront (32 + pad, 16-byte aligned)
+constexpr int kPairChunk = 512;          // columns of X staged in LDS at a time
+constexpr int kPairXLd = kPairChunk + 4; // LDS row stride of the staged X block: 16-byte reads of 32 rows
+                                         // at one k fall into distinct banks
+constexpr int kPairLdsFloats = kPairRows * kPairXLd > kPairWaves * 64 * kPartLd ? kPairRows * kPairXLd
+                                                                                : kPairWaves * 64 * kPartLd;
+constexpr int kPairLdsBytes = kPairLdsFloats * 4;      // X stage and partial sums share the space
+
+struct SkinnyPairParams {
+    const float *X, *Y, *Z;
+    float *C;
+    int64_t ldx, ldy, ldz, ldc;
+    int M, K1, W, N;
+    int x_vec, c_vec;                    // 16-byte loads of X rows / stores of C rows are legal
+    int yz_vec;                          // 8-byte loads of Y and Z rows are legal
+};
+
+// FAST (chosen by the host, see skinny_pair_is_fast): whole row blocks, K1 a multiple of 8,
+// W = 64, N a multiple of 64, aligned rows: no bounds checks anywhere.  The checked version
+// predicates every access.
+template <bool FAST>
+__device__ __forceinline__ void skinny_pair_body(const SkinnyPairParams &p, float *lds)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
+    const int row0 = blockIdx.x * kPairRows, row = row0 + l32;
+    const bool row_ok = FAST || row < p.M;
+    // Y and Z are read at (uniform row and column) + (this lane's rows below and 2*l32 columns):
+    // the lane's part sits in one pointer, everything else is scalar arithmetic
+    const float *yl = p.Y + (int64_t)(4 * half) * p.ldy + 2 * l32;      // phase 1: k = 8g + 4*half + e
+    const float *zl = p.Z + (int64_t)(8 * half) * p.ldz + 2 * l32;      // phase 2: k = 16q + 2r + b + 8*half
+
+    // ---- phase 1: partial T over this wavefront's share of k
+    f32x16 acc0, acc1;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc0[v] = acc1[v] = 0.0f;
+    struct Batch {
+        f32x2 y[kPairBatch][4];
+    };
+    for (int kb = 0; kb < p.K1; kb += kPairChunk) {
+        // the workgroup's rows of X, columns [kb, kb + 512), into LDS (zeros past the matrix)
+        if (kb > 0) __syncthreads();                       // the previous block has been read
+        // (only the columns that exist, rounded up to whole groups of 8 k-values, are staged)
+        const int kc = min(kPairChunk, p.K1 - kb), quads_per_row = ((kc + 7) / 8) * 2, quads = kPairRows * quads_per_row;
+#pragma unroll 4
+        for (int idx = tid; idx < quads; idx += kPairThreads) {
+            const int r = idx / quads_per_row, c = (idx % quads_per_row) * 4;
+            const float *src = p.X + (int64_t)(row0 + r) * p.ldx + kb + c;
+            f32x4 v;
+            if (FAST || (p.x_vec && row0 + r < p.M && kb + c + 4 <= p.K1)) {
+                v = *reinterpret_cast<const f32x4 *>(src);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = (row0 + r < p.M && kb + c + e < p.K1) ? src[e] : 0.0f;
+            }
+            *reinterpret_cast<f32x4 *>(lds + r * kPairXLd + c) = v;
+        }
+        // this wavefront's k-groups of the block are wave, wave + 4, ...
+        const int kgroups = (kc + 7) / 8;
+        const int mine_count = kgroups > wave ? (kgroups - wave + kPairWaves - 1) / kPairWaves : 0;
+        auto load_batch = [&](int i0, Batch &bt) {         // Y: 8-byte loads, row kb + 8g + 4*half + e
+#pragma unroll
+            for (int u = 0; u < kPairBatch; ++u) {
+                const int g = wave + kPairWaves * min(i0 + u, mine_count - 1);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float *src = yl + (int64_t)(kb + 8 * g + e) * p.ldy;
+                    if (FAST) {
+                        bt.y[u][e] = *reinterpret_cast<const f32x2 *>(src);
+                    } else {
+                        const bool k_ok = kb + 8 * g + 4 * half + e < p.K1;
+                        bt.y[u][e][0] = (k_ok && 2 * l32 < p.W) ? src[0] : 0.0f;
+                        bt.y[u][e][1] = (k_ok && 2 * l32 + 1 < p.W) ? src[1] : 0.0f;
+                    }
+                }
+            }
+        };
+        // (a k-group past the end was fetched from the last valid one: it multiplies as zero)
+        auto multiply_batch = [&](int i0, const Batch &bt) {
+#pragma unroll
+            for (int u = 0; u < kPairBatch; ++u) {
+                const bool valid = i0 + u < mine_count;
+                const int g = wave + kPairWaves * min(i0 + u, mine_count - 1);
+                const f32x4 x = *reinterpret_cast<const f32x4 *>(lds + l32 * kPairXLd + 8 * g + 4 * half);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float a = valid ? x[e] : 0.0f;
+                    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(bt.y[u][e][0], a, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(bt.y[u][e][1], a, acc1, 0, 0, 0);
+                }
+            }
+        };
+        Batch b0, b1;
+        if (mine_count > 0) load_batch(0, b0);             // in flight while the X block lands
+        __syncthreads();
+        if (mine_count > 0) {
+            // (the scheduling barriers keep the compiler from sinking a batch's loads down to their uses)
+            for (int i = 0; i < mine_count; i += 2 * kPairBatch) {
+                load_batch(i + kPairBatch, b1);
+                __builtin_amdgcn_sched_barrier(0);
+                multiply_batch(i, b0);
+                __builtin_amdgcn_sched_barrier(0);
+                load_batch(i + 2 * kPairBatch, b0);
+                __builtin_amdgcn_sched_barrier(0);
+                multiply_batch(i + kPairBatch, b1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+    __syncthreads();                                       // the X block is dead: its space takes the partial sums
+    // partial sums meet in LDS: part[wave][lane][0..15] from acc0, [16..31] from acc1
+    float *part = lds;
+    float *mine = part + (wave * 64 + lane) * kPartLd;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const f32x4 v0 = {acc0[4 * q], acc0[4 * q + 1], acc0[4 * q + 2], acc0[4 * q + 3]};
+        const f32x4 v1 = {acc1[4 * q], acc1[4 * q + 1], acc1[4 * q + 2], acc1[4 * q + 3]};
+        *reinterpret_cast<f32x4 *>(mine + 4 * q) = v0;
+        *reinterpret_cast<f32x4 *>(mine + 16 + 4 * q) = v1;
+    }
+    __syncthreads();
+    // t[16b + v] = T[row l32][2*i(v) + b], summed over the wavefronts in a fixed order
+    float t[32];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        f32x4 s = *reinterpret_cast<const f32x4 *>(part + (0 * 64 + lane) * kPartLd + 4 * q);
+#pragma unroll
+        for (int w = 1; w < kPairWaves; ++w) s += *reinterpret_cast<const f32x4 *>(part + (w * 64 + lane) * kPartLd + 4 * q);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) t[4 * q + r] = s[r];
+    }
+
+    // ---- phase 2: this wavefront's 64-column strips, half of the k-values (one of the two
+    // interleaved blocks of T) at a time: z[v] = Z[k][strip's columns 2*l32, 2*l32 + 1] for
+    // k = 2*i(v) + b = (16*(v/4) + 2*(v%4) + b) + 8*half
+    const int strips = (p.N + 63) / 64;
+    auto load_half = [&](int strip, int b, f32x2 (&z)[16]) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int kc = 16 * (v / 4) + 2 * (v % 4) + b, k = kc + 8 * half;
+            const float *src = zl + (int64_t)kc * p.ldz + strip * 64;         // (uniform part is scalar)
+            if (FAST) {
+                z[v] = *reinterpret_cast<const f32x2 *>(src);
+            } else if (p.yz_vec && k < p.W && strip * 64 + 2 * l32 + 2 <= p.N) {
+                z[v] = *reinterpret_cast<const f32x2 *>(src);
+            } else {
+                z[v][0] = (k < p.W && strip * 64 + 2 * l32 < p.N) ? src[0] : 0.0f;
+                z[v][1] = (k < p.W && strip * 64 + 2 * l32 + 1 < p.N) ? src[1] : 0.0f;
+            }
+        }
+    };
+    auto multiply_half = [&](int b, const f32x2 (&z)[16]) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(z[v][0], t[16 * b + v], acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(z[v][1], t[16 * b + v], acc1, 0, 0, 0);
+        }
+    };
+    // acc0[v] / acc1[v]: row l32, strip columns 2*i(v) / 2*i(v) + 1; registers 4q .. 4q+3 of both
+    // together are the eight consecutive columns 16q + 8*half .. + 7
+    auto store_strip = [&](int strip) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int h2 = 0; h2 < 2; ++h2) {
+                const int col = strip * 64 + 16 * q + 8 * half + 4 * h2;
+                const f32x4 v = {acc0[4 * q + 2 * h2], acc1[4 * q + 2 * h2], acc0[4 * q + 2 * h2 + 1], acc1[4 * q + 2 * h2 + 1]};
+                float *dst = p.C + (int64_t)row * p.ldc + col;
+                if (FAST || (row_ok && p.c_vec && col + 4 <= p.N)) {
+                    *reinterpret_cast<f32x4 *>(dst) = v;
+                } else if (row_ok) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (col + e < p.N) dst[e] = v[e];
+                }
+            }
+    };
+    const int my_strips = strips > wave ? (strips - wave + kPairWaves - 1) / kPairWaves : 0;
+    const int last_strip = wave + kPairWaves * (my_strips - 1);
+    // Every workgroup walks the strips from a different starting point: rows of Z are a power
+    // of two apart more often than not, so the 64 rows of one strip sit in the same few L2
+    // channels, and workgroups that all asked for the same strip at the same moment would queue
+    // up there.
+    const int rotate = blockIdx.x % strips;
+    auto rotated = [&](int s) { const int r = s + rotate; return r >= strips ? r - strips : r; };
+    if (my_strips > 0) {
+        // Two register sets take turns, half a strip each: a half's loads are in flight under the
+        // other half's MFMAs; after the last strip its first half is fetched once more and dropped.
+        f32x2 za[16], zb[16];
+        load_half(rotated(wave), 0, za);
+        for (int j = 0; j < my_strips; ++j) {
+            const int strip = rotated(wave + kPairWaves * j);
+            load_half(strip, 1, zb);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc0[v] = acc1[v] = 0.0f;
+            multiply_half(0, za);
+            __builtin_amdgcn_sched_barrier(0);
+            load_half(rotated(min(wave + kPairWaves * (j + 1), last_strip)), 0, za);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply_half(1, zb);
+            store_strip(strip);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
+
+// Four wavefronts, one per SIMD: a workgroup overlaps its own loads, MFMAs and stores, and
+// two workgroups share a compute unit when there are more than the chip has units.
+template <bool FAST>
+__global__ __launch_bounds__(kPairThreads, 1) void skinny_pair_kernel(const SkinnyPairParams p)
+{
+    extern __shared__ __align__(16) float pair_lds[];
+    skinny_pair_body<FAST>(p, pair_lds);
+}
+
+// FAST needs: aligned rows of X, Y, Z and C, M a multiple of 32, K1 of 8, N of 64, W = 64.
+inline bool skinny_pair_is_fast(const SkinnyPairParams &p)
+{
+    return p.x_vec && p.c_vec && p.yz_vec && p.M % kPairRows == 0 && p.K1 % 8 == 0 && p.W == kPairMaxWidth &&
+           p.N % 64 == 0;
+}
+
+}  // namespace mom
