@@ -41,14 +41,14 @@ WORKLOADS = {
     "batched32": ("batched32", None),
     # a chain on which the two planning objectives part: the multiplication-optimal tree, and the
     # tree of the time objective (timed with its own, larger, multiplication count as tree_flop)
-    "ulg2048_min_mults": ("ulg2048", None),
-    "ulg2048_min_time": ("ulg2048", "min_time"),
+    "uug2048_min_mults": ("uug2048", None),
+    "uug2048_min_time": ("uug2048", "min_time"),
     # plain copy of a general 8192x8192 matrix (a chain with one factor): the known-size kernel
     # that the HBM counters are calibrated against
     "copy8192": ("copy8192", None),
 }
 SIDE_WORKLOADS = ["trmm4096", "trmm4096_transposed", "general5", "general5_left_to_right", "mixed5_tri_intermediate",
-                  "mixed5_left_to_right", "batched32", "ulg2048_min_mults", "ulg2048_min_time"]
+                  "mixed5_left_to_right", "batched32", "uug2048_min_mults", "uug2048_min_time"]
 
 sc.CONFIGS["copy8192"] = sc.ChainConfig("copy8192", 9, (8192, 8192), (sc.GENERAL,))
 

@@ -308,10 +308,11 @@ done:
 /*     X lowerTri: k < min((I+1)T, m)      X upperTri: k >= I*T              */
 /*     Y lowerTri: k >= J*T                Y upperTri: k < min((J+1)T, n)    */
 /*   start rounded down to a multiple of 32; chunks = ceil(length / 32)      */
-/*   a product whose tiles all run the full k (general * general), with      */
-/*   fewer than 256 tiles and at least 64 chunks, is cut into                */
-/*   s = min(ceil(384 / tiles), chunks / 8) slices (s > 1), each a           */
-/*   workgroup of its own, followed by a launch that adds the slices         */
+/*   a product with a general result, fewer than 256 tiles and at least 64   */
+/*   chunks in the full k is cut into s = min(ceil(384 / tiles), chunks / 8) */
+/*   slices (s > 1): every tile's own chunks are dealt out to s workgroups,  */
+/*   ceil(chunks of the tile / s) each, followed by a launch that adds the   */
+/*   slices                                                                  */
 /*   matrix time = max(longest workgroup, ceil(all chunks / 256)) * chunk_ps */
 /*     (256 compute units; chunk_ps = one T x T x 32 chunk at 256 FLOP per   */
 /*     clock and 2.4 GHz: 1706667 ps for T = 128, 426667 ps for T = 64)      */
@@ -363,14 +364,12 @@ static u128 product_time(int64_t m, int64_t k, int64_t n, int pX, int pY)
             if (chunks > longest) longest = chunks;
         }
     u128 extra = 0;
-    int general = (pX == P_GENERAL && pY == P_GENERAL);
     int64_t chunks_full = (k + 31) / 32;
-    if (general && tiles < 256 && chunks_full >= 64) {
+    if (pR == P_GENERAL && tiles < 256 && chunks_full >= 64) {
         u128 want = (384 + tiles - 1) / tiles, most = (u128)(chunks_full / 8);
         u128 s = want < most ? want : most;
         if (s > 1) {
-            u128 per = ((u128)chunks_full + s - 1) / s;          /* chunks of one slice */
-            longest = per;
+            longest = (longest + s - 1) / s;                     /* the longest tile's slice */
             extra = TIME_LAUNCH_PS + 4 * (s + 1) * (u128)m * (u128)n / 8;
         }
     }

@@ -84,7 +84,6 @@ u128 product_time_ps(int64_t m, int64_t k, int64_t n, int px, int py)
     if (!xt && !yt) {
         longest = chunks_up_to(k);
         all = (u128)tm * (u128)tn * longest;
-        if (L.split_k > 1) longest = (longest + L.split_k - 1) / L.split_k;        // one slice's share
     } else if (xt && !yt) {            // the k-range depends on the tile row only
         u128 rows = 0;
         for (int64_t I = 0; I < tm; ++I) {
@@ -120,6 +119,7 @@ u128 product_time_ps(int64_t m, int64_t k, int64_t n, int px, int py)
             longest = std::max(longest, c);
         }
     }
+    if (L.split_k > 1) longest = (longest + L.split_k - 1) / L.split_k;            // the longest tile's slice
     const u128 spread = (all + mom::kComputeUnits - 1) / mom::kComputeUnits;
     const u128 matrix = std::max(longest, spread) * chunk_ps;
     const u128 memory = 4 * (structural_entries(m, k, px) + structural_entries(k, n, py) +

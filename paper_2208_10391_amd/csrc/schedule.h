@@ -103,15 +103,17 @@ inline Launch choose_launch(const ProductStep &st)
     // every grid-th tile, so that the loads of its next tile overlap the MFMAs of this one.
     const int resident = kComputeUnits * (small ? 4 : 2);
     if (L.order == kRowMajor && L.num_tiles > resident && st.k >= 8 * (small ? kChunk64 : kChunk128)) L.grid = resident;
-    // Split-K: a general product with few output tiles and a long k leaves most compute units
-    // idle; cut k into slices (one workgroup per tile and slice, partial sums to scratch, summed
-    // by a second small kernel) until about one and a half workgroups per compute unit exist, keeping at
-    // least kMinChunksPerSlice chunks per slice.
+    // Split-K: a product with few output tiles and a long k leaves most compute units idle; cut
+    // every tile's k-range into slices (one workgroup per tile and slice, partial sums to scratch,
+    // summed by a second small kernel) until about one and a half workgroups per compute unit
+    // exist, keeping at least kMinChunksPerSlice chunks per slice of a full k-range.  The result
+    // must be general (the summing kernel writes whole matrices); the operands may be triangular,
+    // their tiles then have shorter k-ranges and shorter slices.
     L.split_k = 1;
     L.scratch_bytes = 0;
     const int bk = small ? kChunk64 : kChunk128;
     const int chunks = (int)((st.k + bk - 1) / bk);
-    if (L.order == kRowMajor && L.num_tiles < kComputeUnits && chunks >= kMinChunksToSplit) {
+    if (st.pc == kGeneral && L.num_tiles < kComputeUnits && chunks >= kMinChunksToSplit) {
         const int want = (kSplitTargetWorkgroups + L.num_tiles - 1) / L.num_tiles;
         const int split = std::min(want, chunks / kMinChunksPerSlice);
         if (split > 1) {

@@ -40,9 +40,10 @@ CONFIGS = {
     # L1 * I * L2 * U * G
     "mixed5": ChainConfig("mixed5", 4, (8192, 8192, 8192, 8192, 8192, 1024),
                           (LOWER_TRI, IDENTITY, LOWER_TRI, UPPER_TRI, GENERAL)),
-    # upperTri * lowerTri * narrow general: a chain on which the multiplication count and the
-    # time model choose different trees
-    "ulg2048": ChainConfig("ulg2048", 6, (2048, 2048, 2048, 96), (UPPER_TRI, LOWER_TRI, GENERAL)),
+    # upperTri * upperTri * general: a chain on which the multiplication count and the time model
+    # choose different trees (the count forms U*U first: few tiles, and a triangular result
+    # cannot be cut along k)
+    "uug2048": ChainConfig("uug2048", 6, (2048, 2048, 2048, 1024), (UPPER_TRI, UPPER_TRI, GENERAL)),
     # 4096 independent chains L * G * U of 32x32 factors
     "batched32": ChainConfig("batched32", 5, (32, 32, 32, 32), (LOWER_TRI, GENERAL, UPPER_TRI),
                              batch=4096),

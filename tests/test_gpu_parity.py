@@ -325,3 +325,18 @@ def test_first_evaluation_under_capture_returns_a_status_and_mom_init_makes_it_l
     r = subprocess.run([sys.executable, "-c", FIRST_USE_UNDER_CAPTURE % root], capture_output=True, text=True, timeout=240)
     assert r.returncode == 0, r.stdout + r.stderr
     assert "capture ok MOM_ERR_NOT_READY" in r.stdout
+
+
+@pytest.mark.parametrize("pa,pb", [(L, G), (U, G), (G, L), (G, U), (L, U), (U, L)])
+def test_few_tiles_with_triangular_operands_are_split_along_k(pa, pb):
+    # a general result on few tiles and a long k: every tile's own (clipped) k-range is dealt out
+    # to slices, the short tiles near the tip of the triangle leave some slices empty
+    n = 2304
+    dims = [n, n, 100] if pb == G else ([70, n, n] if pa == G else [n, n, n])
+    if pa != G and pb != G:
+        n = 1100                                   # 9 x 9 = 81 tiles of L*U / U*L
+        dims = [n, n, n]
+    props = [pa, pb]
+    plan, _ = check_against_dense(dims, props, chain(dims, props, 970))
+    # 72 chunks in the full k for n = 2304: product launch + slice sum; 35 chunks for n = 1100: one launch
+    assert mom.mom_plan_num_launches(plan) == (2 if n == 2304 else 1)

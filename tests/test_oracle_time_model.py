@@ -101,10 +101,11 @@ def test_large_matrix_bound_general_chains_get_the_multiplication_optimal_tree()
 
 
 def test_a_chain_where_the_two_objectives_part():
-    # upperTri * lowerTri * general with a narrow last factor: the fewest multiplications are in
-    # U (L G), two products of 17 long triangular tile-rows each; the time model prefers (U L) G
-    dims, props = [2050, 2050, 2050, 96], [U, L, G]
+    # upperTri * upperTri * general: the fewest multiplications are in (U U) G, whose first product
+    # has 136 tiles for 256 compute units and a triangular result that cannot be cut along k; the
+    # time model prefers U (U G)
+    dims, props = [2048, 2048, 2048, 1024], [U, U, G]
     a, b = oracle.plan_bruteforce(dims, props), oracle.plan_bruteforce_time(dims, props)
-    assert a["splits"] == [0, 1] and b["splits"] == [1, 0]
-    assert b["mults"] > 5 * a["cost"]
+    assert a["splits"] == [1, 0] and b["splits"] == [0, 1]
+    assert b["mults"] > 1.15 * a["cost"]
     assert oracle.tree_time_ps(dims, props, a["splits"]) > 1.4 * b["time_ps"]
