@@ -255,6 +255,28 @@ void render(const mom_plan *plan, const std::vector<int32_t> &split_pos, size_t 
     out += ')';
 }
 
+// (X * Y) * Z with a narrow X * Y runs as ONE launch that reads X, Y and Z and never writes
+// X * Y.  That launch happens where the outer product stands in the evaluation order, so the
+// inner product is moved to the outer one's level: its operands then stay alive (and its
+// never-written temporary stays reserved) until that launch has run, and nothing placed at
+// that level can overlap them.
+void find_shared_launches(mom_plan *plan)
+{
+    using namespace mom;
+    plan->absorbed_by.assign(plan->steps.size(), -1);
+    for (size_t j = 0; j < plan->steps.size(); ++j) {
+        const ProductStep &outer = plan->steps[j];
+        if (outer.a.where != Where::Temp) continue;
+        for (size_t i = 0; i < plan->steps.size(); ++i) {
+            ProductStep &inner = plan->steps[i];
+            if (inner.c.where == Where::Temp && inner.c.index == outer.a.index && fits_skinny_pair(inner, outer)) {
+                plan->absorbed_by[i] = (int32_t)j;
+                inner.level = outer.level;
+            }
+        }
+    }
+}
+
 // The evaluation as a list of launches.  Level by level; the products of a level that share a
 // tile shape go out in one launch (at most kMaxFused at a time), followed by one launch that
 // sums their split-K slices.  Only small products share a launch: a big one fills the chip by
@@ -264,20 +286,12 @@ mom_status_t lay_out_launches(mom_plan *plan)
 {
     using namespace mom;
     const std::vector<int32_t> &order = plan->order;
-    // products whose narrow result is consumed as the left operand of a product they can share
-    // a launch with: absorbed_by[i] = the consumer's step index
-    std::vector<int> absorbed_by(plan->steps.size(), -1), absorbs(plan->steps.size(), -1);
-    for (size_t j = 0; j < plan->steps.size(); ++j) {
-        const ProductStep &outer = plan->steps[j];
-        if (outer.a.where != Where::Temp) continue;
-        for (size_t i = 0; i < plan->steps.size(); ++i) {
-            const ProductStep &inner = plan->steps[i];
-            if (inner.c.where == Where::Temp && inner.c.index == outer.a.index && fits_skinny_pair(inner, outer)) {
-                absorbed_by[i] = (int)j;
-                absorbs[j] = (int)i;
-            }
-        }
-    }
+    // products whose narrow result is consumed as the left operand of a product they share a
+    // launch with (found before the workspace was laid out, see find_shared_launches)
+    const std::vector<int32_t> &absorbed_by = plan->absorbed_by;
+    std::vector<int> absorbs(plan->steps.size(), -1);
+    for (size_t i = 0; i < plan->steps.size(); ++i)
+        if (absorbed_by[i] >= 0) absorbs[absorbed_by[i]] = (int)i;
     size_t next = 0;
     while (next < order.size()) {
         const int level = plan->steps[order[next]].level;
@@ -402,6 +416,8 @@ mom_status_t finish(mom_plan *plan, const std::vector<int64_t> &d, const std::ve
     for (int s : split_pos) plan->splits.push_back(plan->survivors[s]);
     size_t cursor = 0;
     render(plan, split_pos, cursor, 0, m - 1, plan->text);
+
+    find_shared_launches(plan);
 
     // Evaluation order: level by level.  The products of one level do not depend on each
     // other, so the evaluator may put them into one launch; a temporary lives from the level

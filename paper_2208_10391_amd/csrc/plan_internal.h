@@ -84,6 +84,8 @@ struct mom_plan {
     size_t scratch_bytes = 0;
     size_t workspace_bytes = 0;
     std::string text;
+    std::vector<int32_t> absorbed_by;         // per step: the step whose launch also runs this one (a
+                                              // narrow left operand computed on the fly), or -1
     std::vector<mom::PlannedLaunch> launches;   // the evaluation, launch by launch
     // batched evaluation: largest dimension and operand-stack depth of the post-order walk;
     // product s multiplies LDS slot a_slot[s] by slot b_slot[s] and leaves the result in a_slot[s]

@@ -299,3 +299,16 @@ def test_equation_plans_sum_property_cost_and_errors():
     assert lib.mom_equation_eval(two.handle, fptr, None, ctypes.c_void_p(1024), 0, None, 0, 0, None) == code["MOM_ERR_WORKSPACE"]
     assert lib.mom_equation_eval(two.handle, fptr, None, ctypes.c_void_p(1024), 0, None, 0, 8, None) == code["MOM_ERR_BAD_FLAGS"]
     assert lib.mom_equation_eval(two.handle, fptr, None, ctypes.c_void_p(1024), 3, None, 0, 0, None) == code["MOM_ERR_BAD_STRIDE"]
+
+
+def test_operands_of_a_shared_launch_stay_alive_until_it_runs():
+    # ((((0 1) 2) 3) 4) of the five-factor workload: (T * A2) * A3 with T = A0 * A1 runs as one launch
+    # that reads T while it writes its result, so T (256 MiB), the never-written 8192 x 64
+    # intermediate (2 MiB) and the result (128 MiB) must not share workspace
+    c = sc.CONFIGS["general5"]
+    plan = mom.mom_plan_from_splits(c.dims, c.props, [3, 2, 1, 0])
+    assert mom.mom_plan_num_launches(plan) == 3
+    mib = 1 << 20
+    assert plan.workspace_bytes >= (256 + 2 + 128) * mib
+    levels = [mom.mom_plan_product(plan, i)["level"] for i in range(4)]
+    assert levels == [1, 3, 3, 4]                 # the absorbed product stands at its consumer's level (3)
