@@ -197,7 +197,7 @@ def measure(mom, workload, steps, warmup, want_cpu_baseline):
     per = sorted(s.elapsed_time(e) for s, e in events)
 
     traffic, traffic_detail, mfma_busy = measured_counters(workload)
-    launches = mom.mom_plan_num_launches(plan)
+    launches = 1 if cfg.batch else mom.mom_plan_num_launches(plan)      # a whole batch is one launch
     rec = {"workload": workload, "plan": plan.string, "mults": plan.cost_mults, "useful_flop": useful,
            "tree_flop": tree_flop, "launches_per_step": launches, "ms_per_step": wall_ms,
            "device_ms_per_step": dev_ms, "min_ms": per[0], "median_ms": per[len(per) // 2],

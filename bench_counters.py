@@ -95,7 +95,7 @@ def main():
             entry[leg + "_steps"] = steps
         vals = read_pass(os.path.join(top, w, "mfma"))
         if vals and "SQ_VALU_MFMA_BUSY_CYCLES" in vals and "GRBM_GUI_ACTIVE" in vals:
-            pick = [i for i, (name, _) in enumerate(vals["GRBM_GUI_ACTIVE"]) if "product_kernel" in name or "batched_chain" in name]
+            pick = [i for i, (name, _) in enumerate(vals["GRBM_GUI_ACTIVE"]) if "product_kernel" in name or "batched_chain" in name or "skinny_pair" in name]
             busy = sum(vals["SQ_VALU_MFMA_BUSY_CYCLES"][i][1] for i in pick) / SIMDS
             cycles = sum(vals["GRBM_GUI_ACTIVE"][i][1] for i in pick) / XCDS
             if cycles > 0:

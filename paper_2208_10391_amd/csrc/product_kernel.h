@@ -345,6 +345,17 @@ struct Pipeline {
 // the longest-first order when tiles are paired, else every grid-th tile.
 __device__ __forceinline__ int tile_at(const ProductParams &p, int block, int i)
 {
+    if (p.paired == 2) {
+        // die x = block % 8 owns tile rows 16j + x and 16j + 15 - x (counted from the short end);
+        // in descending length these are D[2i] = 16(nb-1-i) + 15 - x, D[2i+1] = 16(nb-1-i) + x, and
+        // pair q = (D[q], D[2nb-1-q]) always adds up to 16(nb-1) + 15: equal work everywhere
+        if (i > 1) return -1;
+        const int x = block % kXcds, s = block / kXcds, J = s % p.tiles_n, q = s / p.tiles_n;
+        const int nb = p.tiles_m / (2 * kXcds), pos = i == 0 ? q : 2 * nb - 1 - q;
+        const int len = 16 * (nb - 1 - pos / 2) + ((pos & 1) ? x : 15 - x);      // 0 = shortest row
+        // position of that row in the longest-first order of tile_coords
+        return (p.tiles_m - 1 - len) * p.tiles_n + J;
+    }
     if (p.paired) {
         const int partner = p.num_tiles - 1 - block;
         return i == 0 ? block : (i == 1 && partner > block ? partner : -1);

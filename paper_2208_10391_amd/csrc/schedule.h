@@ -10,6 +10,8 @@
 namespace mom {
 
 constexpr int kComputeUnits = 256;
+constexpr int kXcds = 8;                   // accelerator dies, each with an L2 of its own; workgroup b is
+                                           // dispatched to die b % 8
 constexpr int kMinChunksPerSlice = 8;
 constexpr int kSplitTargetWorkgroups = 384;
 constexpr int kMinChunksToSplit = 64;      // below this the second launch costs more than it saves
@@ -38,7 +40,8 @@ struct Launch {
     int tiles_m, tiles_n;
     int num_tiles;         // tiles that exist (a triangular result has no tiles in its zero half)
     int order;             // TileOrder
-    int paired;            // workgroup b also takes tile num_tiles-1-b (longest with shortest)
+    int paired;            // 1: workgroup b also takes tile num_tiles-1-b (longest with shortest);
+                           // 2: pairs are dealt so that every die works on tile rows of its own
     int grid;              // workgroups
     int split_k;           // >1: the k-range is cut into this many slices, summed by a second kernel
     size_t scratch_bytes;  // split_k * m * n floats of partial sums
@@ -97,6 +100,14 @@ inline Launch choose_launch(const ProductStep &st)
     // few: from about four rounds of resident workgroups on, handing out single tiles longest
     // first balances by itself and keeps more workgroups in flight.
     L.paired = (L.order != kRowMajor && L.num_tiles >= 2 * kComputeUnits && L.num_tiles < 8 * kComputeUnits) ? 1 : 0;
+    // A tall triangular operand against a narrow right-hand side (more than twice as many tile
+    // rows as tile columns): the triangle is the bulk of the traffic, and with the plain order
+    // every die streams all of it, once per tile column it holds.  Give each die 1/8 of the tile
+    // rows instead (rows x and 15-x of every group of 16, which pair up to equal work): the
+    // triangle is then fetched once, the narrow operand once per die.
+    if (L.paired && (L.order == kRowsDesc || L.order == kRowsAsc) && L.tiles_m % (2 * kXcds) == 0 &&
+        L.tiles_m > 2 * L.tiles_n && L.num_tiles % (2 * kXcds) == 0)
+        L.paired = 2;
     L.grid = L.paired ? (L.num_tiles + 1) / 2 : L.num_tiles;
     // Equal tiles (general * general) beyond what the chip holds at once, with a k long enough
     // to matter: launch only as many workgroups as are resident together and let each walk
