@@ -16,7 +16,7 @@ struct ProductParams {
     int64_t slice_stride;  // elements between split-K slices (0 when split_k == 1)
     int M, N, K;
     int pa, pb, pc;
-    int tiles_m, tiles_n, num_tiles, order, paired;
+    int tiles_m, tiles_n, num_tiles, order, paired, mirrored;
     int grid;              // workgroups per k-slice
     int a_vec, b_vec;      // 16-byte loads are legal for A / B (base and row stride aligned)
     int c_vec;             // 16-byte stores are legal for C

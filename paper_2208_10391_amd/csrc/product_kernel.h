@@ -345,6 +345,12 @@ struct Pipeline {
 // the longest-first order when tiles are paired, else every grid-th tile.
 __device__ __forceinline__ int tile_at(const ProductParams &p, int block, int i)
 {
+    if (p.mirrored) {            // the pair's two tiles belong to workgroups block and block + pairs
+        if (i > 0) return -1;
+        const int pairs = (p.num_tiles + 1) / 2;
+        i = block / pairs;
+        block %= pairs;
+    }
     if (p.paired == 2) {
         // die x = block % 8 owns tile rows 16j + x and 16j + 15 - x (counted from the short end);
         // in descending length these are D[2i] = 16(nb-1-i) + 15 - x, D[2i+1] = 16(nb-1-i) + x, and

@@ -42,6 +42,9 @@ struct Launch {
     int order;             // TileOrder
     int paired;            // 1: workgroup b also takes tile num_tiles-1-b (longest with shortest);
                            // 2: pairs are dealt so that every die works on tile rows of its own
+    int mirrored;          // pairs few enough to leave compute units with one workgroup: the two tiles of
+                           // a pair go to two workgroups, b (long tile) and b + pairs (short tile), which
+                           // the dispatcher places on the same compute unit; they then overlap each other
     int grid;              // workgroups
     int split_k;           // >1: the k-range is cut into this many slices, summed by a second kernel
     size_t scratch_bytes;  // split_k * m * n floats of partial sums
@@ -109,6 +112,8 @@ inline Launch choose_launch(const ProductStep &st)
         L.tiles_m > 2 * L.tiles_n && L.num_tiles % (2 * kXcds) == 0)
         L.paired = 2;
     L.grid = L.paired ? (L.num_tiles + 1) / 2 : L.num_tiles;
+    L.mirrored = (L.paired && L.grid <= kComputeUnits) ? 1 : 0;
+    if (L.mirrored) L.grid *= 2;
     // Equal tiles (general * general) beyond what the chip holds at once, with a k long enough
     // to matter: launch only as many workgroups as are resident together and let each walk
     // every grid-th tile, so that the loads of its next tile overlap the MFMAs of this one.
