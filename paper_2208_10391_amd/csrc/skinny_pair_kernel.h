@@ -22,8 +22,8 @@
 //            values of the second product when MFMA step (b, v) sums k = 2*i(v) + b; Z is
 //            fetched in that same k order.  Wavefront w takes column strips w, w+4, ... (from
 //            a starting point that differs between workgroups); per strip 64 MFMAs from
-//            registers, Z straight from memory, half a strip's loads in flight under the other
-//            half's MFMAs.
+//            registers, Z straight from memory, the next strip requested a whole strip ahead; a
+//            finished strip leaves through LDS as whole 256-byte row segments.
 // In both phases loads are issued a whole batch ahead from two register sets in turn, never
 // behind a branch (past the end the last valid batch is fetched again and dropped), and with at
 // most 32 loads per batch: the hardware counts at most 63 outstanding memory operations, so a
@@ -47,6 +47,7 @@ constexpr int kPartLd = 36;              // LDS floats per lane and wavefront (3
 constexpr int kPairChunk = 512;          // columns of X staged in LDS at a time
 constexpr int kPairXLd = kPairChunk + 4; // LDS row stride of the staged X block: 16-byte reads of 32 rows
                                          // at one k fall into distinct banks
+constexpr int kPatchLd = 68;             // LDS row stride of a wavefront's 32 x 64 patch of the result
 constexpr int kPairLdsFloats = kPairRows * kPairXLd > kPairWaves * 64 * kPartLd ? kPairRows * kPairXLd
                                                                                 : kPairWaves * 64 * kPartLd;
 constexpr int kPairLdsBytes = kPairLdsFloats * 4;      // X stage and partial sums share the space
@@ -73,6 +74,42 @@ __device__ __forceinline__ void skinny_pair_body(const SkinnyPairParams &p, floa
     // the lane's part sits in one pointer, everything else is scalar arithmetic
     const float *yl = p.Y + (int64_t)(4 * half) * p.ldy + 2 * l32;      // phase 1: k = 8g + 4*half + e
     const float *zl = p.Z + (int64_t)(8 * half) * p.ldz + 2 * l32;      // phase 2: k = 16q + 2r + b + 8*half
+
+    // ---- Z as phase 2 reads it: this wavefront's 64-column strips, half of the k-values (one of the two
+    // interleaved blocks of T) at a time: z[v] = Z[k][strip's columns 2*l32, 2*l32 + 1] for
+    // k = 2*i(v) + b = (16*(v/4) + 2*(v%4) + b) + 8*half
+    const int strips = (p.N + 63) / 64;
+    auto load_half = [&](int strip, int b, f32x2 (&z)[16]) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int kc = 16 * (v / 4) + 2 * (v % 4) + b, k = kc + 8 * half;
+            const float *src = zl + (int64_t)kc * p.ldz + strip * 64;         // (uniform part is scalar)
+            if (FAST) {
+                z[v] = *reinterpret_cast<const f32x2 *>(src);
+            } else if (p.yz_vec && k < p.W && strip * 64 + 2 * l32 + 2 <= p.N) {
+                z[v] = *reinterpret_cast<const f32x2 *>(src);
+            } else {
+                z[v][0] = (k < p.W && strip * 64 + 2 * l32 < p.N) ? src[0] : 0.0f;
+                z[v][1] = (k < p.W && strip * 64 + 2 * l32 + 1 < p.N) ? src[1] : 0.0f;
+            }
+        }
+    };
+    const int my_strips = strips > wave ? (strips - wave + kPairWaves - 1) / kPairWaves : 0;
+    const int last_strip = wave + kPairWaves * (my_strips - 1);
+    // Every workgroup walks the strips from a different starting point: rows of Z are a power
+    // of two apart more often than not, so the 64 rows of one strip sit in the same few L2
+    // channels, and workgroups that all asked for the same strip at the same moment would queue
+    // up there.
+    const int rotate = blockIdx.x % strips;
+    auto rotated = [&](int s) { const int r = s + rotate; return r >= strips ? r - strips : r; };
+    // The first strip's part of Z is requested before anything else: it does not depend on
+    // phase 1, and its way from memory is as long as that of X and Y.
+    f32x2 a0[16], b0[16];
+    if (my_strips > 0) {
+        load_half(rotated(wave), 0, a0);
+        load_half(rotated(wave), 1, b0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
 
     // ---- phase 1: partial T over this wavefront's share of k
     f32x16 acc0, acc1;
@@ -174,25 +211,7 @@ __device__ __forceinline__ void skinny_pair_body(const SkinnyPairParams &p, floa
         for (int r = 0; r < 4; ++r) t[4 * q + r] = s[r];
     }
 
-    // ---- phase 2: this wavefront's 64-column strips, half of the k-values (one of the two
-    // interleaved blocks of T) at a time: z[v] = Z[k][strip's columns 2*l32, 2*l32 + 1] for
-    // k = 2*i(v) + b = (16*(v/4) + 2*(v%4) + b) + 8*half
-    const int strips = (p.N + 63) / 64;
-    auto load_half = [&](int strip, int b, f32x2 (&z)[16]) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int kc = 16 * (v / 4) + 2 * (v % 4) + b, k = kc + 8 * half;
-            const float *src = zl + (int64_t)kc * p.ldz + strip * 64;         // (uniform part is scalar)
-            if (FAST) {
-                z[v] = *reinterpret_cast<const f32x2 *>(src);
-            } else if (p.yz_vec && k < p.W && strip * 64 + 2 * l32 + 2 <= p.N) {
-                z[v] = *reinterpret_cast<const f32x2 *>(src);
-            } else {
-                z[v][0] = (k < p.W && strip * 64 + 2 * l32 < p.N) ? src[0] : 0.0f;
-                z[v][1] = (k < p.W && strip * 64 + 2 * l32 + 1 < p.N) ? src[1] : 0.0f;
-            }
-        }
-    };
+    // ---- phase 2
     auto multiply_half = [&](int b, const f32x2 (&z)[16]) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
@@ -201,51 +220,65 @@ __device__ __forceinline__ void skinny_pair_body(const SkinnyPairParams &p, floa
         }
     };
     // acc0[v] / acc1[v]: row l32, strip columns 2*i(v) / 2*i(v) + 1; registers 4q .. 4q+3 of both
-    // together are the eight consecutive columns 16q + 8*half .. + 7
-    auto store_strip = [&](int strip) {
+    // together are the eight consecutive columns 16q + 8*half .. + 7.  Stored from there, one
+    // instruction would write 16-byte pieces of 32 different rows; the strip goes through this
+    // wavefront's 32 x 64 patch of LDS instead and leaves it as whole 256-byte row segments, four
+    // rows per store instruction.
+    __syncthreads();                                       // every wavefront has read the partial sums
+    float *patch = lds + wave * (kPairRows * kPatchLd);
+    auto stash_strip = [&]() {
 #pragma unroll
         for (int q = 0; q < 4; ++q)
 #pragma unroll
             for (int h2 = 0; h2 < 2; ++h2) {
-                const int col = strip * 64 + 16 * q + 8 * half + 4 * h2;
                 const f32x4 v = {acc0[4 * q + 2 * h2], acc1[4 * q + 2 * h2], acc0[4 * q + 2 * h2 + 1], acc1[4 * q + 2 * h2 + 1]};
-                float *dst = p.C + (int64_t)row * p.ldc + col;
-                if (FAST || (row_ok && p.c_vec && col + 4 <= p.N)) {
-                    *reinterpret_cast<f32x4 *>(dst) = v;
-                } else if (row_ok) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (col + e < p.N) dst[e] = v[e];
-                }
+                *reinterpret_cast<f32x4 *>(patch + l32 * kPatchLd + 16 * q + 8 * half + 4 * h2) = v;
             }
     };
-    const int my_strips = strips > wave ? (strips - wave + kPairWaves - 1) / kPairWaves : 0;
-    const int last_strip = wave + kPairWaves * (my_strips - 1);
-    // Every workgroup walks the strips from a different starting point: rows of Z are a power
-    // of two apart more often than not, so the 64 rows of one strip sit in the same few L2
-    // channels, and workgroups that all asked for the same strip at the same moment would queue
-    // up there.
-    const int rotate = blockIdx.x % strips;
-    auto rotated = [&](int s) { const int r = s + rotate; return r >= strips ? r - strips : r; };
+    auto flush_strip = [&](int strip) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int r = 4 * i + (lane >> 4), c = 4 * (lane & 15), col = strip * 64 + c;
+            const f32x4 v = *reinterpret_cast<const f32x4 *>(patch + r * kPatchLd + c);
+            float *dst = p.C + (int64_t)(row0 + r) * p.ldc + col;
+            if (FAST || (row0 + r < p.M && p.c_vec && col + 4 <= p.N)) {
+                *reinterpret_cast<f32x4 *>(dst) = v;
+            } else if (row0 + r < p.M) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (col + e < p.N) dst[e] = v[e];
+            }
+        }
+    };
     if (my_strips > 0) {
-        // Two register sets take turns, half a strip each: a half's loads are in flight under the
-        // other half's MFMAs; after the last strip its first half is fetched once more and dropped.
-        f32x2 za[16], zb[16];
-        load_half(rotated(wave), 0, za);
-        for (int j = 0; j < my_strips; ++j) {
-            const int strip = rotated(wave + kPairWaves * j);
-            load_half(strip, 1, zb);
+        // Two pairs of register sets take turns, a strip each: the next strip's two halves are
+        // requested while this strip is multiplied, a whole strip (4096 MFMA cycles) ahead of their
+        // use; after the last strip it is fetched once more and dropped.
+        f32x2 a1[16], b1[16];
+        auto strip_step = [&](int j, const f32x2 (&ca)[16], const f32x2 (&cb)[16], f32x2 (&na)[16], f32x2 (&nb)[16]) {
+            const int next = rotated(min(wave + kPairWaves * (j + 1), last_strip));
+            load_half(next, 0, na);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc0[v] = acc1[v] = 0.0f;
-            multiply_half(0, za);
+            multiply_half(0, ca);
             __builtin_amdgcn_sched_barrier(0);
-            load_half(rotated(min(wave + kPairWaves * (j + 1), last_strip)), 0, za);
+            load_half(next, 1, nb);
             __builtin_amdgcn_sched_barrier(0);
-            multiply_half(1, zb);
-            store_strip(strip);
+            // (the previous strip leaves its patch while this one's second half multiplies)
+            if (j > 0) flush_strip(rotated(wave + kPairWaves * (j - 1)));
+            multiply_half(1, cb);
+            stash_strip();
             __builtin_amdgcn_sched_barrier(0);
+        };
+        strip_step(0, a0, b0, a1, b1);
+        int j = 1;
+        for (; j + 1 < my_strips; j += 2) {
+            strip_step(j, a1, b1, a0, b0);
+            strip_step(j + 1, a0, b0, a1, b1);
         }
+        if (j < my_strips) strip_step(j, a1, b1, a0, b0);
+        flush_strip(rotated(last_strip));
     }
 }
 
