@@ -126,7 +126,7 @@ mom_status_t mom_plan_from_splits(const int64_t *dims, const int32_t *props, int
  *   its k-range is [0, k) clipped by the operands' structures (X lowerTri: k < min((I+1)T, m);
  *   X upperTri: k >= I*T; Y lowerTri: k >= J*T; Y upperTri: k < min((J+1)T, n)), start rounded
  *   down to a chunk; a product with a general result, fewer than 256 tiles and at least 64
- *   chunks in the full k is cut into s = min(ceil(384/tiles), chunks/8) > 1 k-slices (every tile's
+ *   chunks in the full k is cut into s = min(ceil(768/tiles), chunks/8) > 1 k-slices (every tile's
  *   chunks dealt out to s workgroups, ceil(tile's chunks / s) each), plus a summing launch;
  *   matrix = max(longest workgroup's chunks, ceil(all chunks / 256)) * (1706667 for T = 128,
  *   426667 for T = 64: one chunk of one tile at 256 FLOP per clock and 2.4 GHz);

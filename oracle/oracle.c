@@ -309,7 +309,7 @@ done:
 /*     Y lowerTri: k >= J*T                Y upperTri: k < min((J+1)T, n)    */
 /*   start rounded down to a multiple of 32; chunks = ceil(length / 32)      */
 /*   a product with a general result, fewer than 256 tiles and at least 64   */
-/*   chunks in the full k is cut into s = min(ceil(384 / tiles), chunks / 8) */
+/*   chunks in the full k is cut into s = min(ceil(768 / tiles), chunks / 8) */
 /*   slices (s > 1): every tile's own chunks are dealt out to s workgroups,  */
 /*   ceil(chunks of the tile / s) each, followed by a launch that adds the   */
 /*   slices                                                                  */
@@ -366,7 +366,7 @@ static u128 product_time(int64_t m, int64_t k, int64_t n, int pX, int pY)
     u128 extra = 0;
     int64_t chunks_full = (k + 31) / 32;
     if (pR == P_GENERAL && tiles < 256 && chunks_full >= 64) {
-        u128 want = (384 + tiles - 1) / tiles, most = (u128)(chunks_full / 8);
+        u128 want = (768 + tiles - 1) / tiles, most = (u128)(chunks_full / 8);
         u128 s = want < most ? want : most;
         if (s > 1) {
             longest = (longest + s - 1) / s;                     /* the longest tile's slice */

@@ -13,7 +13,7 @@ constexpr int kComputeUnits = 256;
 constexpr int kXcds = 8;                   // accelerator dies, each with an L2 of its own; workgroup b is
                                            // dispatched to die b % 8
 constexpr int kMinChunksPerSlice = 8;
-constexpr int kSplitTargetWorkgroups = 384;
+constexpr int kSplitTargetWorkgroups = 768;
 constexpr int kMinChunksToSplit = 64;      // below this the second launch costs more than it saves
 constexpr int kChunk128 = 32, kChunk64 = 32;   // k-chunk (BK) of the 128x128 and of the 64x64 tile shape
 
@@ -121,7 +121,7 @@ inline Launch choose_launch(const ProductStep &st)
     if (L.order == kRowMajor && L.num_tiles > resident && st.k >= 8 * (small ? kChunk64 : kChunk128)) L.grid = resident;
     // Split-K: a product with few output tiles and a long k leaves most compute units idle; cut
     // every tile's k-range into slices (one workgroup per tile and slice, partial sums to scratch,
-    // summed by a second small kernel) until about one and a half workgroups per compute unit
+    // summed by a second small kernel) until about three workgroups per compute unit
     // exist, keeping at least kMinChunksPerSlice chunks per slice of a full k-range.  The result
     // must be general (the summing kernel writes whole matrices); the operands may be triangular,
     // their tiles then have shorter k-ranges and shorter slices.
