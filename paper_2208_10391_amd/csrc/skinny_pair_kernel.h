@@ -9,8 +9,8 @@
 // first, so register v of lane (l32, half) of an accumulator holds row l32 and the block's
 // column i(v) = 8*(v/4) + 4*half + v%4.  A 64-column strip is handled as two 32-column blocks
 // that INTERLEAVE: block b holds the strip's columns 2*i + b, so a lane fetches both blocks'
-// operand values for one k with a single 8-byte load (columns 2*l32, 2*l32 + 1) and stores
-// eight consecutive columns of its row with two 16-byte stores.
+// operand values for one k with a single 8-byte load (columns 2*l32, 2*l32 + 1) and holds
+// eight consecutive columns of its row in registers 4q .. 4q+3 of the two accumulators.
 //   phase 1: T = X * Y.  The workgroup's 32 rows of X go to LDS, 512 columns at a time, with
 //            coalesced 16-byte loads that are all in flight at once (read lane-per-row straight
 //            from memory, a wavefront would touch 32 cache lines per load).  The four
@@ -68,8 +68,7 @@ template <bool FAST>
 __device__ __forceinline__ void skinny_pair_body(const SkinnyPairParams &p, float *lds)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
-    const int row0 = blockIdx.x * kPairRows, row = row0 + l32;
-    const bool row_ok = FAST || row < p.M;
+    const int row0 = blockIdx.x * kPairRows;
     // Y and Z are read at (uniform row and column) + (this lane's rows below and 2*l32 columns):
     // the lane's part sits in one pointer, everything else is scalar arithmetic
     const float *yl = p.Y + (int64_t)(4 * half) * p.ldy + 2 * l32;      // phase 1: k = 8g + 4*half + e
