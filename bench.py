@@ -43,14 +43,23 @@ WORKLOADS = {
     # tree of the time objective (timed with its own, larger, multiplication count as tree_flop)
     "uug2048_min_mults": ("uug2048", None),
     "uug2048_min_time": ("uug2048", "min_time"),
+    # element-wise passes, bound by HBM: a diagonal times a general matrix (one scaling launch)
+    # and the sum of three general matrices (an equation whose addends are plain matrices)
+    "dscale8192": ("dscale8192", None),
+    "add3_8192": ("add3_8192", "equation"),
     # plain copy of a general 8192x8192 matrix (a chain with one factor): the known-size kernel
     # that the HBM counters are calibrated against
     "copy8192": ("copy8192", None),
 }
+ELEMENTWISE_KERNEL = {"copy8192": "copy_structure_kernel", "dscale8192": "diag_scale_kernel", "add3_8192": "add_terms_kernel"}
 SIDE_WORKLOADS = ["trmm4096", "trmm4096_transposed", "general5", "general5_left_to_right", "mixed5_tri_intermediate",
-                  "mixed5_left_to_right", "batched32", "uug2048_min_mults", "uug2048_min_time"]
+                  "mixed5_left_to_right", "batched32", "uug2048_min_mults", "uug2048_min_time", "dscale8192", "add3_8192"]
 
 sc.CONFIGS["copy8192"] = sc.ChainConfig("copy8192", 9, (8192, 8192), (sc.GENERAL,))
+sc.CONFIGS["dscale8192"] = sc.ChainConfig("dscale8192", 10, (8192, 8192, 8192), (sc.DIAGONAL, sc.GENERAL))
+# three addends, each a chain of one general 8192 x 8192 factor (dims / props list the addends one after the other)
+sc.CONFIGS["add3_8192"] = sc.ChainConfig("add3_8192", 11, (8192, 8192), (sc.GENERAL,))
+ADD3_TERMS = 3
 
 
 def kernel_sources_digest():
@@ -86,6 +95,8 @@ def measured_counters(workload):
 def structural_bytes(rows, cols, prop):
     if prop in (sc.LOWER_TRI, sc.UPPER_TRI):
         return rows * (rows + 1) // 2 * 4
+    if prop == sc.DIAGONAL:
+        return rows * 4
     return rows * cols * 4
 
 
@@ -142,9 +153,58 @@ def settle(step, min_ms=60.0, max_ms=3000.0):
             return spent, windows, last
 
 
+def time_steps(step, steps, warmup):
+    """settle, warm up, then `steps` calls between events and between host clocks, then single calls."""
+    settle_ms, settle_windows, _ = settle(step)
+    for _ in range(warmup):
+        step()
+    first, last = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    first.record()
+    for _ in range(steps):
+        step()
+    last.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    dev_ms = first.elapsed_time(last) / steps
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(min(steps, 50))]
+    for s, e in events:
+        s.record()
+        step()
+        e.record()
+    torch.cuda.synchronize()
+    per = sorted(s.elapsed_time(e) for s, e in events)
+    return {"ms_per_step": wall_ms, "device_ms_per_step": dev_ms, "min_ms": per[0], "median_ms": per[len(per) // 2],
+            "settle_ms": settle_ms, "settle_windows": settle_windows}
+
+
+def measure_sum(mom, workload, cfg, steps, warmup):
+    """The sum of ADD3_TERMS general matrices through mom_equation_eval: one element-wise launch,
+    every addend read once and the sum written once."""
+    rows, cols = cfg.dims
+    terms = [sc.make_factor(rows, cols, sc.GENERAL, sc.factor_seed(cfg.number, t)).cuda() for t in range(ADD3_TERMS)]
+    eq = mom.mom_equation_plan([((rows, cols), (sc.GENERAL,), None)] * ADD3_TERMS)
+    out = torch.empty((rows, cols), dtype=torch.float32, device="cuda")
+    step = mom.bind_equation_eval(eq, [[t] for t in terms], out=out)
+    rec = {"workload": workload, "plan": " + ".join("(%d)" % t for t in range(ADD3_TERMS)), "mults": 0, "useful_flop": 0.0,
+           "tree_flop": 0.0, "launches_per_step": 1, "value": 0.0}
+    rec.update(time_steps(step, steps, warmup))
+    traffic, traffic_detail, _ = measured_counters(workload)
+    byts = (ADD3_TERMS + 1) * rows * cols * 4
+    ach = byts / (rec["device_ms_per_step"] * 1e-3) / 1e9
+    rec["roofline"] = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                       "traffic": traffic, "traffic_detail": traffic_detail, "kernel": ELEMENTWISE_KERNEL[workload],
+                       "algorithmic_bytes_per_launch": byts, "mfma_busy": None}
+    return rec
+
+
 def measure(mom, workload, steps, warmup, want_cpu_baseline):
     cfg_name, splits = WORKLOADS[workload]
     cfg = sc.CONFIGS[cfg_name]
+    if splits == "equation":
+        return measure_sum(mom, workload, cfg, steps, warmup), cfg, None
     host = sc.make_config(cfg_name)
     trans = list(cfg.trans) if cfg.trans else None
     best = mom.mom_chain_plan(cfg.dims, cfg.props, trans=trans)    # the planner's tree
@@ -170,45 +230,24 @@ def measure(mom, workload, steps, warmup, want_cpu_baseline):
     useful = float(cfg.dims[0]) ** 3 if cfg_name.startswith("trmm4096") else 2.0 * best.cost_mults * batch
     tree_flop = useful if splits is None else 2.0 * plan.cost_mults * batch
 
-    settle_ms, settle_windows, _ = settle(step)
-    for _ in range(warmup):
-        step()
     # The event pair sits on the launch stream (the library enqueues on torch's current stream)
-    # and brackets the timed region: device time per step, which feeds the roofline.
-    first, last = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    first.record()
-    for _ in range(steps):
-        step()
-    last.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
-    dev_ms = first.elapsed_time(last) / steps
-
-    # one evaluation at a time: minimum and median (the paper logs the minimum of its runs)
-    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-              for _ in range(min(steps, 50))]
-    for s, e in events:
-        s.record()
-        step()
-        e.record()
-    torch.cuda.synchronize()
-    per = sorted(s.elapsed_time(e) for s, e in events)
+    # and brackets the timed region: device time per step, which feeds the roofline; then one
+    # evaluation at a time: minimum and median (the paper logs the minimum of its runs)
+    timing = time_steps(step, steps, warmup)
+    wall_ms, dev_ms = timing["ms_per_step"], timing["device_ms_per_step"]
 
     traffic, traffic_detail, mfma_busy = measured_counters(workload)
     launches = 1 if cfg.batch else mom.mom_plan_num_launches(plan)      # a whole batch is one launch
     rec = {"workload": workload, "plan": plan.string, "mults": plan.cost_mults, "useful_flop": useful,
-           "tree_flop": tree_flop, "launches_per_step": launches, "ms_per_step": wall_ms,
-           "device_ms_per_step": dev_ms, "min_ms": per[0], "median_ms": per[len(per) // 2],
-           "settle_ms": settle_ms, "settle_windows": settle_windows,
+           "tree_flop": tree_flop, "launches_per_step": launches,
            "value": useful / (wall_ms * 1e-3) / 1e9}
-    if cfg.batch or workload == "copy8192":       # HBM-bound: factors in and result out, once
+    rec.update(timing)
+    if cfg.batch or workload in ELEMENTWISE_KERNEL:       # HBM-bound: factors in and result out, once
         byts = algorithmic_bytes(cfg, rprop)
         ach = byts / (dev_ms * 1e-3) / 1e9
         rec["roofline"] = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                            "frac": ach / HBM_PEAK_GBS, "traffic": traffic, "traffic_detail": traffic_detail,
-                           "kernel": "batched_chain3_right_kernel" if cfg.batch else "copy_structure_kernel",
+                           "kernel": "batched_chain3_right_kernel" if cfg.batch else ELEMENTWISE_KERNEL[workload],
                            "algorithmic_bytes_per_launch": byts, "mfma_busy": mfma_busy}
     else:
         # dominant kernel: product_kernel; a step's product launches are taken together (their

@@ -481,9 +481,11 @@ def mom_equation_plan(chains, objective: int = MOM_PLAN_MIN_MULTS) -> Equation:
     return Equation(out.value, chains)
 
 
-def mom_equation_eval(eq: Equation, factors: Sequence[Sequence[Optional[torch.Tensor]]], out: Optional[torch.Tensor] = None,
-                      workspace: Optional[torch.Tensor] = None, flags: int = 0, stream=None) -> torch.Tensor:
-    """factors[c][t]: the buffer of factor t of addend c (None for Identity), stored shape."""
+def bind_equation_eval(eq: Equation, factors: Sequence[Sequence[Optional[torch.Tensor]]], out: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None, flags: int = 0) -> BoundEval:
+    """Checks and marshals the arguments of mom_equation_eval; calling the result enqueues the
+    equation on the (current) stream.  factors[c][t]: the buffer of factor t of addend c (None
+    for Identity), stored shape."""
     flat, stored = [], []
     for (dims, props, trans), fs in zip(eq.chains, factors):
         if len(fs) != len(props):
@@ -518,11 +520,15 @@ def mom_equation_eval(eq: Equation, factors: Sequence[Sequence[Optional[torch.Te
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     ld_out = out.stride(0) if rows > 1 else max(out.stride(0), cols)
-    st = _lib.mom_equation_eval(eq.handle, ctypes.cast(ptrs, _vpp), lds, ctypes.c_void_p(out.data_ptr()), ld_out,
-                                ctypes.c_void_p(ws_ptr), ws_bytes, int(flags), _stream_handle(stream))
-    if st != MOM_OK:
-        raise MomError(st, "mom_equation_eval")
-    return out
+    head = (eq.handle, ctypes.cast(ptrs, _vpp), lds, ctypes.c_void_p(out.data_ptr()), ld_out,
+            ctypes.c_void_p(ws_ptr), ws_bytes, int(flags))
+    return BoundEval(_lib.mom_equation_eval, "mom_equation_eval", head, (), out, (eq, ptrs, lds, tuple(flat), workspace))
+
+
+def mom_equation_eval(eq: Equation, factors: Sequence[Sequence[Optional[torch.Tensor]]], out: Optional[torch.Tensor] = None,
+                      workspace: Optional[torch.Tensor] = None, flags: int = 0, stream=None) -> torch.Tensor:
+    """One call of the C entry point: marshal (bind_equation_eval) and enqueue."""
+    return bind_equation_eval(eq, factors, out, workspace, flags)(stream)
 
 
 def mom_probe_mfma_peak(iters: int, sink: torch.Tensor, stream=None) -> float:
