@@ -72,6 +72,13 @@ def test_paired_tiles_whole_result(pa, pb):
     run_whole(dims, props, sc.make_chain(dims, props, 71), reference="dense")
 
 
+@pytest.mark.parametrize("pa", [L, U])
+def test_paired_tiles_rectangular_right_hand_side_whole_result(pa):
+    # 24 x 28 = 672 tiles, paired, more tile columns than tile rows
+    dims, props = [3072, 3072, 3584], [pa, G]
+    run_whole(dims, props, sc.make_chain(dims, props, 75), reference="dense")
+
+
 def test_persistent_grid_whole_result():
     # 24 x 24 = 576 equal tiles > 512 resident workgroups, k = 288 >= 256: every workgroup
     # strides over the tiles, some take two
