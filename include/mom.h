@@ -125,13 +125,14 @@ mom_status_t mom_plan_from_splits(const int64_t *dims, const int32_t *props, int
  *   a tile (I, J) exists unless it lies wholly in the zero half of a triangular result;
  *   its k-range is [0, k) clipped by the operands' structures (X lowerTri: k < min((I+1)T, m);
  *   X upperTri: k >= I*T; Y lowerTri: k >= J*T; Y upperTri: k < min((J+1)T, n)), start rounded
- *   down to a chunk; a product with a general result, fewer than 256 tiles and at least 64
+ *   down to a chunk; a product with fewer than 256 tiles and at least 64
  *   chunks in the full k is cut into s = min(ceil(768/tiles), chunks/8) > 1 k-slices (every tile's
  *   chunks dealt out to s workgroups, ceil(tile's chunks / s) each), plus a summing launch;
  *   matrix = max(longest workgroup's chunks, ceil(all chunks / 256)) * (1706667 for T = 128,
  *   426667 for T = 64: one chunk of one tile at 256 FLOP per clock and 2.4 GHz);
  *   memory = 4 * (structural entries of X, Y and the result) / 8 (8 bytes per picosecond);
- *   time = 6000000 + max(matrix, memory)  [+ 6000000 + 4 * (s+1) * m * n / 8 when sliced];
+ *   time = 6000000 + max(matrix, memory)  [+ 6000000 + 4 * (s+1) * (structural entries of the
+ *   result) / 8 when sliced];
  *   a product with a diagonal operand is an element-wise pass: time = 6000000 + memory.
  * Ties go to the smallest root split, recursively, as for the multiplication count.
  */

@@ -308,7 +308,7 @@ done:
 /*     X lowerTri: k < min((I+1)T, m)      X upperTri: k >= I*T              */
 /*     Y lowerTri: k >= J*T                Y upperTri: k < min((J+1)T, n)    */
 /*   start rounded down to a multiple of 32; chunks = ceil(length / 32)      */
-/*   a product with a general result, fewer than 256 tiles and at least 64   */
+/*   a product with fewer than 256 tiles and at least 64                     */
 /*   chunks in the full k is cut into s = min(ceil(768 / tiles), chunks / 8) */
 /*   slices (s > 1): every tile's own chunks are dealt out to s workgroups,  */
 /*   ceil(chunks of the tile / s) each, followed by a launch that adds the   */
@@ -319,7 +319,7 @@ done:
 /*   memory time = 4 bytes * (structural entries of X, Y and the result) at  */
 /*     8 bytes per picosecond                                                */
 /*   time = 6000000 (launch) + max(matrix, memory)                           */
-/*          + [split] 6000000 + 4 * (s + 1) * m * n / 8                      */
+/*          + [split] 6000000 + 4 * (s + 1) * (entries of the result) / 8    */
 /*   a product with a diagonal operand is an element-wise scaling pass:      */
 /*   time = 6000000 + memory                                                 */
 
@@ -365,12 +365,12 @@ static u128 product_time(int64_t m, int64_t k, int64_t n, int pX, int pY)
         }
     u128 extra = 0;
     int64_t chunks_full = (k + 31) / 32;
-    if (pR == P_GENERAL && tiles < 256 && chunks_full >= 64) {
+    if (tiles < 256 && chunks_full >= 64) {
         u128 want = (768 + tiles - 1) / tiles, most = (u128)(chunks_full / 8);
         u128 s = want < most ? want : most;
         if (s > 1) {
             longest = (longest + s - 1) / s;                     /* the longest tile's slice */
-            extra = TIME_LAUNCH_PS + 4 * (s + 1) * (u128)m * (u128)n / 8;
+            extra = TIME_LAUNCH_PS + 4 * (s + 1) * structural_entries(m, n, pR) / 8;
         }
     }
     u128 spread = (all_chunks + 255) / 256;

@@ -37,6 +37,7 @@ struct ReduceParams {
     float *C;
     int64_t slice_stride, ldc;
     int slices, M, N;
+    int pc;                               // structure of the result: only that part of the slices exists
 };
 struct ReduceBatch {
     int count;

@@ -125,7 +125,7 @@ u128 product_time_ps(int64_t m, int64_t k, int64_t n, int px, int py)
     const u128 memory = 4 * (structural_entries(m, k, px) + structural_entries(k, n, py) +
                              structural_entries(m, n, st.pc)) / 8;
     u128 t = kLaunchPs + std::max(matrix, memory);
-    if (L.split_k > 1) t += kLaunchPs + 4 * (u128)(L.split_k + 1) * (u128)m * (u128)n / 8;
+    if (L.split_k > 1) t += kLaunchPs + 4 * (u128)(L.split_k + 1) * structural_entries(m, n, st.pc) / 8;
     return t;
 }
 
@@ -352,7 +352,7 @@ mom_status_t lay_out_launches(mom_plan *plan)
                     ReduceParams &r = pl.reduce.prob[pl.reduce.count];
                     pl.reduce_of[pl.reduce.count++] = slot;
                     r.slice_stride = p.slice_stride;
-                    r.slices = L.split_k; r.M = p.M; r.N = p.N;
+                    r.slices = L.split_k; r.M = p.M; r.N = p.N; r.pc = st.pc;
                     reduce_quads = std::max<int64_t>(reduce_quads, (st.m * st.n + 3) / 4);
                 }
                 const int64_t blocks = (int64_t)(slot ? pl.batch.block_end[slot - 1] : 0) + (int64_t)L.grid * L.split_k;

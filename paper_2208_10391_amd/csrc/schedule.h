@@ -122,14 +122,14 @@ inline Launch choose_launch(const ProductStep &st)
     // Split-K: a product with few output tiles and a long k leaves most compute units idle; cut
     // every tile's k-range into slices (one workgroup per tile and slice, partial sums to scratch,
     // summed by a second small kernel) until about three workgroups per compute unit
-    // exist, keeping at least kMinChunksPerSlice chunks per slice of a full k-range.  The result
-    // must be general (the summing kernel writes whole matrices); the operands may be triangular,
-    // their tiles then have shorter k-ranges and shorter slices.
+    // exist, keeping at least kMinChunksPerSlice chunks per slice of a full k-range.  Operands and
+    // result may be triangular: a tile's clipped k-range is what is dealt out, the slices are
+    // dense m x n buffers of which only the result's structure is written and summed.
     L.split_k = 1;
     L.scratch_bytes = 0;
     const int bk = small ? kChunk64 : kChunk128;
     const int chunks = (int)((st.k + bk - 1) / bk);
-    if (st.pc == kGeneral && L.num_tiles < kComputeUnits && chunks >= kMinChunksToSplit) {
+    if (L.num_tiles < kComputeUnits && chunks >= kMinChunksToSplit) {
         const int want = (kSplitTargetWorkgroups + L.num_tiles - 1) / L.num_tiles;
         const int split = std::min(want, chunks / kMinChunksPerSlice);
         if (split > 1) {

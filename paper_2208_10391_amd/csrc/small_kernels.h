@@ -10,7 +10,8 @@
 namespace mom {
 
 // Sum of split-K slices (ReduceBatch; blockIdx.y selects the product).  The order of summation
-// is fixed, so results repeat bit for bit from run to run.
+// is fixed, so results repeat bit for bit from run to run.  Only the structure of the result
+// is summed and written: outside it the slices were never written.
 // 256 threads = 32 groups of 4 consecutive floats x 8 lanes over the slices: lane g of a group
 // sums slices g, g+8, ... with all its loads in flight, the 8 partial sums meet in LDS.
 __global__ __launch_bounds__(256) void reduce_slices_kernel(const ReduceBatch batch)
@@ -23,27 +24,41 @@ __global__ __launch_bounds__(256) void reduce_slices_kernel(const ReduceBatch ba
     const int q_in_block = threadIdx.x % 32, g = threadIdx.x / 32;
     for (int64_t q0 = (int64_t)blockIdx.x * 32; q0 < quads; q0 += (int64_t)gridDim.x * 32) {
         const int64_t q = q0 + q_in_block, e = q * 4;
-        f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f};
+        // where the quad sits in the result's structure: 2 wholly inside, 1 partly, 0 outside
+        // (with N % 4 == 0 a quad lies in one row; otherwise every element is checked)
+        int inside = 0;
         if (q < quads) {
-            if (vec) {
-#pragma unroll 8
-                for (int k = g; k < r.slices; k += 8) s += *reinterpret_cast<const f32x4 *>(r.P + k * r.slice_stride + e);
+            if (r.pc == kGeneral) {
+                inside = 2;
+            } else if (vec) {
+                const int i = (int)(e / r.N), j = (int)(e % r.N);
+                const bool first = in_structure(r.pc, i, j), last = in_structure(r.pc, i, j + 3);
+                inside = (first && last) ? 2 : (first || last) ? 1 : 0;
             } else {
-                for (int k = g; k < r.slices; k += 8)
-                    for (int c = 0; c < 4; ++c)
-                        if (e + c < total) s[c] += r.P[k * r.slice_stride + e + c];
+                inside = 1;
             }
+        }
+        f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (inside == 2 && vec) {
+#pragma unroll 8
+            for (int k = g; k < r.slices; k += 8) s += *reinterpret_cast<const f32x4 *>(r.P + k * r.slice_stride + e);
+        } else if (inside) {
+            for (int k = g; k < r.slices; k += 8)
+                for (int c = 0; c < 4; ++c)
+                    if (e + c < total && in_structure(r.pc, (int)((e + c) / r.N), (int)((e + c) % r.N)))
+                        s[c] += r.P[k * r.slice_stride + e + c];
         }
         part[g][q_in_block] = s;
         __syncthreads();
-        if (g == 0 && q < quads) {
+        if (g == 0 && inside) {
 #pragma unroll
             for (int k = 1; k < 8; ++k) s += part[k][q_in_block];
-            if (vec) {
+            if (inside == 2 && vec) {
                 *reinterpret_cast<f32x4 *>(r.C + (e / r.N) * r.ldc + (e % r.N)) = s;
             } else {
                 for (int c = 0; c < 4; ++c)
-                    if (e + c < total) r.C[((e + c) / r.N) * r.ldc + ((e + c) % r.N)] = s[c];
+                    if (e + c < total && in_structure(r.pc, (int)((e + c) / r.N), (int)((e + c) % r.N)))
+                        r.C[((e + c) / r.N) * r.ldc + ((e + c) % r.N)] = s[c];
             }
         }
         __syncthreads();

@@ -40,10 +40,11 @@ CONFIGS = {
     # L1 * I * L2 * U * G
     "mixed5": ChainConfig("mixed5", 4, (8192, 8192, 8192, 8192, 8192, 1024),
                           (LOWER_TRI, IDENTITY, LOWER_TRI, UPPER_TRI, GENERAL)),
-    # upperTri * upperTri * general: a chain on which the multiplication count and the time model
-    # choose different trees (the count forms U*U first: few tiles, and a triangular result
-    # cannot be cut along k)
-    "uug2048": ChainConfig("uug2048", 6, (2048, 2048, 2048, 1024), (UPPER_TRI, UPPER_TRI, GENERAL)),
+    # general * general * general * lowerTri: a chain on which the multiplication count and the
+    # time model choose different trees (the count forms the 1024 x 512 product with k = 4096
+    # first, then two more dependent products; the time model pairs the factors up, two
+    # independent products that share a launch, at one and a half times the multiplications)
+    "gggl512": ChainConfig("gggl512", 6, (512, 1024, 4096, 512, 512), (GENERAL, GENERAL, GENERAL, LOWER_TRI)),
     # 4096 independent chains L * G * U of 32x32 factors
     "batched32": ChainConfig("batched32", 5, (32, 32, 32, 32), (LOWER_TRI, GENERAL, UPPER_TRI),
                              batch=4096),

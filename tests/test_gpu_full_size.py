@@ -79,6 +79,15 @@ def test_paired_tiles_rectangular_right_hand_side_whole_result(pa):
     run_whole(dims, props, sc.make_chain(dims, props, 75), reference="dense")
 
 
+@pytest.mark.parametrize("pa,pb,n", [(L, L, 2048), (U, U, 2048), (L, L, 2100), (U, U, 2688)])
+def test_split_k_with_triangular_operands_and_results_whole_result(pa, pb, n):
+    # fewer than 256 tiles and k >= 2048: every tile's clipped k-range is cut into slices, also when
+    # the result is a triangle (136 to 231 tiles); the summing kernel touches the triangle only
+    dims, props = [n, n, n], [pa, pb]
+    plan = run_whole(dims, props, sc.make_chain(dims, props, 76), reference="dense")
+    assert mom.mom_plan_num_launches(plan) == 2
+
+
 def test_persistent_grid_whole_result():
     # 24 x 24 = 576 equal tiles > 512 resident workgroups, k = 288 >= 256: every workgroup
     # strides over the tiles, some take two

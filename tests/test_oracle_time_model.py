@@ -101,11 +101,11 @@ def test_large_matrix_bound_general_chains_get_the_multiplication_optimal_tree()
 
 
 def test_a_chain_where_the_two_objectives_part():
-    # upperTri * upperTri * general: the fewest multiplications are in (U U) G, whose first product
-    # has 136 tiles for 256 compute units and a triangular result that cannot be cut along k; the
-    # time model prefers U (U G)
-    dims, props = [2048, 2048, 2048, 1024], [U, U, G]
+    # general * general * general * lowerTri, 512 x 1024 x 4096 x 512 x 512: the fewest multiplications
+    # are in ((0 (1 2)) 3), three dependent products of which the first has 32 tiles and a long k;
+    # the time model prefers ((0 1) (2 3)): half as many again, in two independent products and a root
+    dims, props = [512, 1024, 4096, 512, 512], [G, G, G, L]
     a, b = oracle.plan_bruteforce(dims, props), oracle.plan_bruteforce_time(dims, props)
-    assert a["splits"] == [1, 0] and b["splits"] == [0, 1]
-    assert b["mults"] > 1.15 * a["cost"]
-    assert oracle.tree_time_ps(dims, props, a["splits"]) > 1.4 * b["time_ps"]
+    assert a["splits"] == [2, 0, 1] and b["splits"] == [1, 0, 2]
+    assert b["mults"] > 1.4 * a["cost"]
+    assert oracle.tree_time_ps(dims, props, a["splits"]) > 1.1 * b["time_ps"]

@@ -236,9 +236,9 @@ def test_time_objective_equals_the_oracle_enumeration():
         b = mom.mom_chain_plan_ex(c.dims, c.props, None, objective=mom.MOM_PLAN_MIN_TIME)
         assert a.splits == b.splits
     # and one chain where the objectives part (see tests/test_oracle_time_model.py)
-    a = mom.mom_chain_plan([2048, 2048, 2048, 1024], [U, U, G])
-    b = mom.mom_chain_plan_ex([2048, 2048, 2048, 1024], [U, U, G], None, objective=mom.MOM_PLAN_MIN_TIME)
-    assert (a.string, b.string) == ("((0 1) 2)", "(0 (1 2))")
+    a = mom.mom_chain_plan([512, 1024, 4096, 512, 512], [G, G, G, L])
+    b = mom.mom_chain_plan_ex([512, 1024, 4096, 512, 512], [G, G, G, L], None, objective=mom.MOM_PLAN_MIN_TIME)
+    assert (a.string, b.string) == ("((0 (1 2)) 3)", "((0 1) (2 3))")
 
 
 def test_plans_with_diagonal_factors_equal_bruteforce_under_both_objectives():
