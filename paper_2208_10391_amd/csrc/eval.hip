@@ -135,9 +135,10 @@ mom_status_t eval_chain(const mom_plan_t *plan, const float *const *d_factors, c
         const int32_t f = plan->survivors[0];
         const Resolved a = factor(f);
         if (plan->trans[f]) {
-            const int64_t blocks = (int64_t)((M + 31) / 32) * ((N + 31) / 32);
+            const int64_t blocks = (int64_t)((M + kTransposeTile - 1) / kTransposeTile) * ((N + kTransposeTile - 1) / kTransposeTile);
             hipLaunchKernelGGL(copy_transposed_kernel, dim3((unsigned)std::min<int64_t>(blocks, 1 << 20)), dim3(256), 0, stream,
-                               a.ptr, a.ld, d_out, ld_out, M, N, plan->chain_props[f]);
+                               a.ptr, a.ld, d_out, ld_out, M, N, plan->chain_props[f],
+                               (int)(aligned16(a.ptr, a.ld) && aligned16(d_out, ld_out)));
         } else {
             hipLaunchKernelGGL(copy_structure_kernel, rowwise_grid(M, N, kRowUnroll), dim3(256), 0, stream, a.ptr, a.ld,
                                d_out, ld_out, M, N, plan->props[f], (int)(aligned16(a.ptr, a.ld) && aligned16(d_out, ld_out)));

@@ -121,23 +121,50 @@ __global__ __launch_bounds__(256) void copy_structure_kernel(const float *A, int
 }
 
 // out = S^T restricted to the structure `prop` of the result (single surviving factor that
-// enters the chain transposed): 32x32 blocks through LDS, reads and writes both along rows.
+// enters the chain transposed): 64 x 64 blocks through LDS, reads and writes both along rows.
+// A block that lies wholly inside the matrix and the structure moves with 16-byte non-temporal
+// accesses on both sides (`vec`: bases and row strides allow them); edge and diagonal blocks go
+// element by element.
+constexpr int kTransposeTile = 64;
 __global__ __launch_bounds__(256) void copy_transposed_kernel(const float *S, int64_t lds_, float *C, int64_t ldc, int M, int N,
-                                                              int prop)
+                                                              int prop, int vec)
 {
-    __shared__ float tile[32][33];
-    const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;      // 32 x 8 threads
-    const int bj = (N + 31) / 32, blocks = ((M + 31) / 32) * bj;
+    constexpr int T = kTransposeTile;
+    __shared__ float tile[T][T + 1];                             // tile[j][i] = S[j0 + j][i0 + i]
+    const int tid = threadIdx.x, c4 = 4 * (tid % 16), r4 = tid / 16;
+    const int bj = (N + T - 1) / T, blocks = ((M + T - 1) / T) * bj;
     for (int b = blockIdx.x; b < blocks; b += gridDim.x) {
-        const int i0 = (b / bj) * 32, j0 = (b % bj) * 32;        // block of the result
-        for (int r = ty; r < 32; r += 8) {                       // S is N x M: rows j0.., columns i0..
-            const int j = j0 + r, i = i0 + tx;
-            tile[r][tx] = (j < N && i < M && in_structure(prop, i, j)) ? S[(int64_t)j * lds_ + i] : 0.0f;
-        }
-        __syncthreads();
-        for (int r = ty; r < 32; r += 8) {
-            const int i = i0 + r, j = j0 + tx;
-            if (i < M && j < N && in_structure(prop, i, j)) C[(int64_t)i * ldc + j] = tile[tx][r];
+        const int i0 = (b / bj) * T, j0 = (b % bj) * T;          // block of the result
+        bool whole = vec && i0 + T <= M && j0 + T <= N;
+        if (prop == kLower) whole = whole && j0 + T - 1 <= i0;
+        if (prop == kUpper) whole = whole && i0 + T - 1 <= j0;
+        if (prop == kDiagonal) whole = false;
+        if (whole) {
+            f32x4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)                          // S is N x M: rows j0.., columns i0..
+                v[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(S + (int64_t)(j0 + r4 + 16 * u) * lds_ + i0 + c4));
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) tile[r4 + 16 * u][c4 + e] = v[u][e];
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = r4 + 16 * u;
+                const f32x4 w = {tile[c4][i], tile[c4 + 1][i], tile[c4 + 2][i], tile[c4 + 3][i]};
+                __builtin_nontemporal_store(w, reinterpret_cast<f32x4 *>(C + (int64_t)(i0 + i) * ldc + j0 + c4));
+            }
+        } else {
+            for (int idx = tid; idx < T * T; idx += 256) {
+                const int r = idx / T, x = idx % T, j = j0 + r, i = i0 + x;
+                tile[r][x] = (j < N && i < M && in_structure(prop, i, j)) ? S[(int64_t)j * lds_ + i] : 0.0f;
+            }
+            __syncthreads();
+            for (int idx = tid; idx < T * T; idx += 256) {
+                const int r = idx / T, x = idx % T, i = i0 + r, j = j0 + x;
+                if (i < M && j < N && in_structure(prop, i, j)) C[(int64_t)i * ldc + j] = tile[x][r];
+            }
         }
         __syncthreads();
     }

@@ -83,6 +83,23 @@ def test_single_transposed_factor_is_a_transposing_copy():
     assert np.array_equal(got[up], lo.numpy().T[up]) and np.all(np.isnan(got[~up]))
 
 
+@pytest.mark.parametrize("rows,cols", [(256, 192), (300, 452), (64, 64)])
+def test_transposing_copy_whole_blocks_and_edges(rows, cols):
+    # blocks of 64 x 64 that lie wholly inside move 16 bytes at a time, the rest element by element;
+    # a strided output keeps its padding
+    a = sc.make_factor(rows, cols, G, 12)
+    for pad in (0, 4, 5):
+        plan, got = eval_chain([cols, rows], [G], [a], trans=[1], pad_cols=pad, out_pad=pad)
+        assert plan.result == (cols, rows, G) and np.array_equal(got, a.numpy().T)
+    if rows == cols or rows == 256:
+        n = rows
+        for prop, keep in ((L, np.triu), (U, np.tril)):
+            t = sc.make_factor(n, n, prop, 13)
+            plan, got = eval_chain([n, n], [prop], [t], trans=[1])
+            mask = keep(np.ones((n, n), dtype=bool))
+            assert np.array_equal(got[mask], t.numpy().T[mask]) and np.all(np.isnan(got[~mask]))
+
+
 def test_gram_matrix_is_symmetric_bit_for_bit_or_close():
     x = sc.make_factor(300, 200, G, 11)
     _, got = eval_chain([300, 200, 300], [G, G], [x, x], trans=[0, 1])       # X * X^T
