@@ -37,6 +37,9 @@
 namespace mom {
 
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+constexpr int kRawBufferFlags = 0x00020000;     // fourth word of an untyped buffer descriptor (32-bit data format)
 
 constexpr int kPairRows = 32;            // rows of the result per workgroup
 constexpr int kPairMaxWidth = 64;        // widest intermediate (two interleaved 32-column blocks)
@@ -67,12 +70,22 @@ struct SkinnyPairParams {
 template <bool FAST>
 __device__ __forceinline__ void skinny_pair_body(const SkinnyPairParams &p, float *lds)
 {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);          // (tells the compiler that it is uniform)
     const int row0 = blockIdx.x * kPairRows;
     // Y and Z are read at (uniform row and column) + (this lane's rows below and 2*l32 columns):
     // the lane's part sits in one pointer, everything else is scalar arithmetic
     const float *yl = p.Y + (int64_t)(4 * half) * p.ldy + 2 * l32;      // phase 1: k = 8g + 4*half + e
     const float *zl = p.Z + (int64_t)(8 * half) * p.ldz + 2 * l32;      // phase 2: k = 16q + 2r + b + 8*half
+    // (FAST: all of Y, of Z and of this workgroup's rows of C lie within 2 GiB of their first byte)
+    const int y_lane_bytes = (int)((4 * half) * p.ldy + 2 * l32) * 4;
+    const __amdgpu_buffer_rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(p.Y), 0, FAST ? (int)(((int64_t)(p.K1 - 1) * p.ldy + p.W) * 4) : 0, kRawBufferFlags);
+    const __amdgpu_buffer_rsrc_t c_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        p.C + (int64_t)row0 * p.ldc, 0, FAST ? (int)(((int64_t)(kPairRows - 1) * p.ldc + p.N) * 4) : 0, kRawBufferFlags);
+    const int z_lane_bytes = (int)((8 * half) * p.ldz + 2 * l32) * 4;
+    const __amdgpu_buffer_rsrc_t z_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(p.Z), 0, FAST ? (int)(((int64_t)(p.W - 1) * p.ldz + p.N) * 4) : 0, kRawBufferFlags);
 
     // ---- Z as phase 2 reads it: this wavefront's 64-column strips, half of the k-values (one of the two
     // interleaved blocks of T) at a time: z[v] = Z[k][strip's columns 2*l32, 2*l32 + 1] for
@@ -84,7 +97,10 @@ __device__ __forceinline__ void skinny_pair_body(const SkinnyPairParams &p, floa
             const int kc = 16 * (v / 4) + 2 * (v % 4) + b, k = kc + 8 * half;
             const float *src = zl + (int64_t)kc * p.ldz + strip * 64;         // (uniform part is scalar)
             if (FAST) {
-                z[v] = *reinterpret_cast<const f32x2 *>(src);
+                // buffer load: descriptor and the uniform byte offset in scalar registers, this lane's
+                // offset in one vector register: no vector arithmetic per load
+                const u32x2 raw = __builtin_amdgcn_raw_buffer_load_b64(z_rsrc, z_lane_bytes, (kc * (int)p.ldz + strip * 64) * 4, 0);
+                z[v] = __builtin_bit_cast(f32x2, raw);
             } else if (p.yz_vec && k < p.W && strip * 64 + 2 * l32 + 2 <= p.N) {
                 z[v] = *reinterpret_cast<const f32x2 *>(src);
             } else {
@@ -146,7 +162,8 @@ __device__ __forceinline__ void skinny_pair_body(const SkinnyPairParams &p, floa
                 for (int e = 0; e < 4; ++e) {
                     const float *src = yl + (int64_t)(kb + 8 * g + e) * p.ldy;
                     if (FAST) {
-                        bt.y[u][e] = *reinterpret_cast<const f32x2 *>(src);
+                        const u32x2 raw = __builtin_amdgcn_raw_buffer_load_b64(y_rsrc, y_lane_bytes, (kb + 8 * g + e) * (int)p.ldy * 4, 0);
+                        bt.y[u][e] = __builtin_bit_cast(f32x2, raw);
                     } else {
                         const bool k_ok = kb + 8 * g + 4 * half + e < p.K1;
                         bt.y[u][e][0] = (k_ok && 2 * l32 < p.W) ? src[0] : 0.0f;
@@ -240,7 +257,9 @@ __device__ __forceinline__ void skinny_pair_body(const SkinnyPairParams &p, floa
             const int r = 4 * i + (lane >> 4), c = 4 * (lane & 15), col = strip * 64 + c;
             const f32x4 v = *reinterpret_cast<const f32x4 *>(patch + r * kPatchLd + c);
             float *dst = p.C + (int64_t)(row0 + r) * p.ldc + col;
-            if (FAST || (row0 + r < p.M && p.c_vec && col + 4 <= p.N)) {
+            if (FAST) {
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), c_rsrc, (r * (int)p.ldc + c) * 4, strip * 256, 0);
+            } else if (row0 + r < p.M && p.c_vec && col + 4 <= p.N) {
                 *reinterpret_cast<f32x4 *>(dst) = v;
             } else if (row0 + r < p.M) {
 #pragma unroll
@@ -290,11 +309,13 @@ __global__ __launch_bounds__(kPairThreads, 1) void skinny_pair_kernel(const Skin
     skinny_pair_body<FAST>(p, pair_lds);
 }
 
-// FAST needs: aligned rows of X, Y, Z and C, M a multiple of 32, K1 of 8, N of 64, W = 64.
+// FAST needs: aligned rows of X, Y, Z and C, M a multiple of 32, K1 of 8, N of 64, W = 64; Y, Z and 32 rows of C within 2 GiB each.
 inline bool skinny_pair_is_fast(const SkinnyPairParams &p)
 {
     return p.x_vec && p.c_vec && p.yz_vec && p.M % kPairRows == 0 && p.K1 % 8 == 0 && p.W == kPairMaxWidth &&
-           p.N % 64 == 0;
+           p.N % 64 == 0 && ((int64_t)(p.W - 1) * p.ldz + p.N) * 4 < (int64_t)1 << 31 &&
+           ((int64_t)(p.K1 - 1) * p.ldy + p.W) * 4 < (int64_t)1 << 31 &&
+           ((int64_t)(kPairRows - 1) * p.ldc + p.N) * 4 < (int64_t)1 << 31;
 }
 
 }  // namespace mom
