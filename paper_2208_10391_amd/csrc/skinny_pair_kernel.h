@@ -24,13 +24,21 @@
 //            a starting point that differs between workgroups); per strip 64 MFMAs from
 //            registers, Z straight from memory, the next strip requested a whole strip ahead; a
 //            finished strip leaves through LDS as whole 256-byte row segments.
-// In both phases loads are issued a whole batch ahead from two register sets in turn, never
-// behind a branch (past the end the last valid batch is fetched again and dropped), and with at
-// most 32 loads per batch: the hardware counts at most 63 outstanding memory operations, so a
-// larger batch could not be told apart from the one before it.
+// Both phases are one even stream of MFMA pairs with at most one load, one LDS access and one
+// store between two pairs: a wavefront is alone on its SIMD, so whatever it issues in a burst
+// (sixteen loads, a strip's stores, the read-out of the accumulators) is time the matrix pipe
+// idles.  Loads go two batches (a whole strip) ahead into the registers that have just been
+// consumed, never behind a branch (past the end the last valid batch is fetched again and
+// dropped), with fewer than 63 memory operations outstanding (the hardware counter has six
+// bits).  Y, Z and the result are addressed through buffer descriptors: descriptor and uniform
+// offset in scalar registers, the lane's own offset in one vector register, so that no vector
+// arithmetic is spent on addresses (64-bit vector adds per access cost this kernel a tenth of
+// its time).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 #include "product_kernel.h"
 
@@ -91,9 +99,8 @@ __device__ __forceinline__ void skinny_pair_body(const SkinnyPairParams &p, floa
     // interleaved blocks of T) at a time: z[v] = Z[k][strip's columns 2*l32, 2*l32 + 1] for
     // k = 2*i(v) + b = (16*(v/4) + 2*(v%4) + b) + 8*half
     const int strips = (p.N + 63) / 64;
-    auto load_half = [&](int strip, int b, f32x2 (&z)[16]) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
+    auto load_one = [&](int strip, int b, int v, f32x2 (&z)[16]) {
+        {
             const int kc = 16 * (v / 4) + 2 * (v % 4) + b, k = kc + 8 * half;
             const float *src = zl + (int64_t)kc * p.ldz + strip * 64;         // (uniform part is scalar)
             if (FAST) {
@@ -108,6 +115,10 @@ __device__ __forceinline__ void skinny_pair_body(const SkinnyPairParams &p, floa
                 z[v][1] = (k < p.W && strip * 64 + 2 * l32 + 1 < p.N) ? src[1] : 0.0f;
             }
         }
+    };
+    auto load_half = [&](int strip, int b, f32x2 (&z)[16]) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) load_one(strip, b, v, z);
     };
     const int my_strips = strips > wave ? (strips - wave + kPairWaves - 1) / kPairWaves : 0;
     const int last_strip = wave + kPairWaves * (my_strips - 1);
@@ -154,53 +165,62 @@ __device__ __forceinline__ void skinny_pair_body(const SkinnyPairParams &p, floa
         // this wavefront's k-groups of the block are wave, wave + 4, ...
         const int kgroups = (kc + 7) / 8;
         const int mine_count = kgroups > wave ? (kgroups - wave + kPairWaves - 1) / kPairWaves : 0;
-        auto load_batch = [&](int i0, Batch &bt) {         // Y: 8-byte loads, row kb + 8g + 4*half + e
-#pragma unroll
-            for (int u = 0; u < kPairBatch; ++u) {
-                const int g = wave + kPairWaves * min(i0 + u, mine_count - 1);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float *src = yl + (int64_t)(kb + 8 * g + e) * p.ldy;
-                    if (FAST) {
-                        const u32x2 raw = __builtin_amdgcn_raw_buffer_load_b64(y_rsrc, y_lane_bytes, (kb + 8 * g + e) * (int)p.ldy * 4, 0);
-                        bt.y[u][e] = __builtin_bit_cast(f32x2, raw);
-                    } else {
-                        const bool k_ok = kb + 8 * g + 4 * half + e < p.K1;
-                        bt.y[u][e][0] = (k_ok && 2 * l32 < p.W) ? src[0] : 0.0f;
-                        bt.y[u][e][1] = (k_ok && 2 * l32 + 1 < p.W) ? src[1] : 0.0f;
-                    }
-                }
+        auto group_of = [&](int i) { return wave + kPairWaves * min(i, mine_count - 1); };
+        auto load_y = [&](int i, int e, f32x2 &y) {        // Y: 8-byte loads, row kb + 8g + 4*half + e
+            const int g = group_of(i);                     // (past the end: the last valid group again)
+            if (FAST) {
+                const u32x2 raw = __builtin_amdgcn_raw_buffer_load_b64(y_rsrc, y_lane_bytes, (kb + 8 * g + e) * (int)p.ldy * 4, 0);
+                y = __builtin_bit_cast(f32x2, raw);
+            } else {
+                const float *src = yl + (int64_t)(kb + 8 * g + e) * p.ldy;
+                const bool k_ok = kb + 8 * g + 4 * half + e < p.K1;
+                y[0] = (k_ok && 2 * l32 < p.W) ? src[0] : 0.0f;
+                y[1] = (k_ok && 2 * l32 + 1 < p.W) ? src[1] : 0.0f;
             }
         };
-        // (a k-group past the end was fetched from the last valid one: it multiplies as zero)
-        auto multiply_batch = [&](int i0, const Batch &bt) {
+        auto load_batch = [&](int i0, Batch &bt) {
+#pragma unroll
+            for (int u = 0; u < kPairBatch; ++u)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) load_y(i0 + u, e, bt.y[u][e]);
+        };
+        auto read_x = [&](int i) {
+            return *reinterpret_cast<const f32x4 *>(lds + l32 * kPairXLd + 8 * group_of(i) + 4 * half);
+        };
+        // One batch (four k-groups): the MFMAs of `cur`, every MFMA pair followed by one load of the
+        // batch after next into the registers it has just consumed; the X values of the following
+        // group are read one group ahead.
+        // A k-group past the end is skipped (its loads fetched the last valid group again).
+        auto multiply_batch = [&](int i0, Batch &cur, int n0) {
+            f32x4 x = read_x(i0);
 #pragma unroll
             for (int u = 0; u < kPairBatch; ++u) {
-                const bool valid = i0 + u < mine_count;
-                const int g = wave + kPairWaves * min(i0 + u, mine_count - 1);
-                const f32x4 x = *reinterpret_cast<const f32x4 *>(lds + l32 * kPairXLd + 8 * g + 4 * half);
+                const f32x4 x_next = read_x(u + 1 < kPairBatch ? i0 + u + 1 : n0 - kPairBatch);
+                if (i0 + u < mine_count) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float a = valid ? x[e] : 0.0f;
-                    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(bt.y[u][e][0], a, acc0, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(bt.y[u][e][1], a, acc1, 0, 0, 0);
+                    for (int e = 0; e < 4; ++e) {
+                        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(cur.y[u][e][0], x[e], acc0, 0, 0, 0);
+                        acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(cur.y[u][e][1], x[e], acc1, 0, 0, 0);
+                        load_y(n0 + u, e, cur.y[u][e]);    // (the registers just consumed take the next values)
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) load_y(n0 + u, e, cur.y[u][e]);
                 }
+                x = x_next;
             }
         };
         Batch b0, b1;
-        if (mine_count > 0) load_batch(0, b0);             // in flight while the X block lands
+        if (mine_count > 0) {                              // in flight while the X block lands
+            load_batch(0, b0);
+            load_batch(kPairBatch, b1);
+        }
         __syncthreads();
         if (mine_count > 0) {
-            // (the scheduling barriers keep the compiler from sinking a batch's loads down to their uses)
             for (int i = 0; i < mine_count; i += 2 * kPairBatch) {
-                load_batch(i + kPairBatch, b1);
-                __builtin_amdgcn_sched_barrier(0);
-                multiply_batch(i, b0);
-                __builtin_amdgcn_sched_barrier(0);
-                load_batch(i + 2 * kPairBatch, b0);
-                __builtin_amdgcn_sched_barrier(0);
-                multiply_batch(i + kPairBatch, b1);
-                __builtin_amdgcn_sched_barrier(0);
+                multiply_batch(i, b0, i + 2 * kPairBatch);
+                multiply_batch(i + kPairBatch, b1, i + 3 * kPairBatch);
             }
         }
     }
@@ -228,44 +248,35 @@ __device__ __forceinline__ void skinny_pair_body(const SkinnyPairParams &p, floa
     }
 
     // ---- phase 2
-    auto multiply_half = [&](int b, const f32x2 (&z)[16]) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(z[v][0], t[16 * b + v], acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(z[v][1], t[16 * b + v], acc1, 0, 0, 0);
-        }
-    };
-    // acc0[v] / acc1[v]: row l32, strip columns 2*i(v) / 2*i(v) + 1; registers 4q .. 4q+3 of both
-    // together are the eight consecutive columns 16q + 8*half .. + 7.  Stored from there, one
-    // instruction would write 16-byte pieces of 32 different rows; the strip goes through this
-    // wavefront's 32 x 64 patch of LDS instead and leaves it as whole 256-byte row segments, four
-    // rows per store instruction.
+    // acc[v] of block 0 / block 1: row l32, strip columns 2*i(v) / 2*i(v) + 1; registers 4q .. 4q+3
+    // of both together are the eight consecutive columns 16q + 8*half .. + 7.  Stored from there,
+    // one instruction would write 16-byte pieces of 32 different rows; a finished strip goes
+    // through this wavefront's 32 x 64 patch of LDS instead and leaves it as whole 256-byte row
+    // segments, four rows per store instruction.  That trip rides on the NEXT strip's MFMAs: two
+    // accumulator sets take turns, and between two MFMA pairs there is at most one load of Z, one
+    // LDS access and one store of the finished strip, so that the matrix pipe never waits for a
+    // burst of other instructions, for LDS, or for the accumulators to be read out.
     __syncthreads();                                       // every wavefront has read the partial sums
     float *patch = lds + wave * (kPairRows * kPatchLd);
-    auto stash_strip = [&]() {
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-            for (int h2 = 0; h2 < 2; ++h2) {
-                const f32x4 v = {acc0[4 * q + 2 * h2], acc1[4 * q + 2 * h2], acc0[4 * q + 2 * h2 + 1], acc1[4 * q + 2 * h2 + 1]};
-                *reinterpret_cast<f32x4 *>(patch + l32 * kPatchLd + 16 * q + 8 * half + 4 * h2) = v;
-            }
+    auto stash_piece = [&](int piece, const f32x16 &d0, const f32x16 &d1) {
+        const int q = piece / 2, h2 = piece % 2;
+        const f32x4 v = {d0[4 * q + 2 * h2], d1[4 * q + 2 * h2], d0[4 * q + 2 * h2 + 1], d1[4 * q + 2 * h2 + 1]};
+        *reinterpret_cast<f32x4 *>(patch + l32 * kPatchLd + 16 * q + 8 * half + 4 * h2) = v;
     };
-    auto flush_strip = [&](int strip) {
+    auto read_piece = [&](int piece) {
+        return *reinterpret_cast<const f32x4 *>(patch + (4 * piece + (lane >> 4)) * kPatchLd + 4 * (lane & 15));
+    };
+    auto store_piece = [&](int piece, int strip, const f32x4 &v) {
+        const int r = 4 * piece + (lane >> 4), c = 4 * (lane & 15), col = strip * 64 + c;
+        float *dst = p.C + (int64_t)(row0 + r) * p.ldc + col;
+        if (FAST) {
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), c_rsrc, (r * (int)p.ldc + c) * 4, strip * 256, 0);
+        } else if (row0 + r < p.M && p.c_vec && col + 4 <= p.N) {
+            *reinterpret_cast<f32x4 *>(dst) = v;
+        } else if (row0 + r < p.M) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int r = 4 * i + (lane >> 4), c = 4 * (lane & 15), col = strip * 64 + c;
-            const f32x4 v = *reinterpret_cast<const f32x4 *>(patch + r * kPatchLd + c);
-            float *dst = p.C + (int64_t)(row0 + r) * p.ldc + col;
-            if (FAST) {
-                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), c_rsrc, (r * (int)p.ldc + c) * 4, strip * 256, 0);
-            } else if (row0 + r < p.M && p.c_vec && col + 4 <= p.N) {
-                *reinterpret_cast<f32x4 *>(dst) = v;
-            } else if (row0 + r < p.M) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (col + e < p.N) dst[e] = v[e];
-            }
+            for (int e = 0; e < 4; ++e)
+                if (col + e < p.N) dst[e] = v[e];
         }
     };
     if (my_strips > 0) {
@@ -273,30 +284,55 @@ __device__ __forceinline__ void skinny_pair_body(const SkinnyPairParams &p, floa
         // requested while this strip is multiplied, a whole strip (4096 MFMA cycles) ahead of their
         // use; after the last strip it is fetched once more and dropped.
         f32x2 a1[16], b1[16];
-        auto strip_step = [&](int j, const f32x2 (&ca)[16], const f32x2 (&cb)[16], f32x2 (&na)[16], f32x2 (&nb)[16]) {
+        f32x16 alt0, alt1;                                 // the second accumulator set
+        const f32x16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+        // Strip j into (c0, c1) while the finished strip j-1 leaves (d0, d1); have_done is false
+        // for the first strip only.
+        auto strip_step = [&](auto have_done, int j, const f32x2 (&ca)[16], const f32x2 (&cb)[16], f32x2 (&na)[16],
+                              f32x2 (&nb)[16], f32x16 &c0, f32x16 &c1, const f32x16 &d0, const f32x16 &d1) {
+            constexpr bool HAVE_DONE = decltype(have_done)::value;
             const int next = rotated(min(wave + kPairWaves * (j + 1), last_strip));
-            load_half(next, 0, na);
-            __builtin_amdgcn_sched_barrier(0);
+            const int done = rotated(wave + kPairWaves * (j - 1));
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc0[v] = acc1[v] = 0.0f;
-            multiply_half(0, ca);
-            __builtin_amdgcn_sched_barrier(0);
-            load_half(next, 1, nb);
-            __builtin_amdgcn_sched_barrier(0);
-            // (the previous strip leaves its patch while this one's second half multiplies)
-            if (j > 0) flush_strip(rotated(wave + kPairWaves * (j - 1)));
-            multiply_half(1, cb);
-            stash_strip();
-            __builtin_amdgcn_sched_barrier(0);
+            for (int v = 0; v < 16; ++v) {                 // first half of k; the finished strip goes to LDS
+                load_one(next, 0, v, na);
+                c0 = __builtin_amdgcn_mfma_f32_32x32x2f32(ca[v][0], t[v], v == 0 ? zero : c0, 0, 0, 0);
+                c1 = __builtin_amdgcn_mfma_f32_32x32x2f32(ca[v][1], t[v], v == 0 ? zero : c1, 0, 0, 0);
+                if (HAVE_DONE && v >= 1 && v < 9) stash_piece(v - 1, d0, d1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            f32x4 piece[8];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {                 // second half; the finished strip goes LDS -> memory
+                load_one(next, 1, v, nb);
+                c0 = __builtin_amdgcn_mfma_f32_32x32x2f32(cb[v][0], t[16 + v], c0, 0, 0, 0);
+                c1 = __builtin_amdgcn_mfma_f32_32x32x2f32(cb[v][1], t[16 + v], c1, 0, 0, 0);
+                if (HAVE_DONE && v < 8) piece[v] = read_piece(v);
+                if (HAVE_DONE && v >= 4 && v < 12) store_piece(v - 4, done, piece[v - 4]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         };
-        strip_step(0, a0, b0, a1, b1);
+        using yes = std::integral_constant<bool, true>;
+        using no = std::integral_constant<bool, false>;
+        strip_step(no{}, 0, a0, b0, a1, b1, acc0, acc1, alt0, alt1);
         int j = 1;
         for (; j + 1 < my_strips; j += 2) {
-            strip_step(j, a1, b1, a0, b0);
-            strip_step(j + 1, a0, b0, a1, b1);
+            strip_step(yes{}, j, a1, b1, a0, b0, alt0, alt1, acc0, acc1);
+            strip_step(yes{}, j + 1, a0, b0, a1, b1, acc0, acc1, alt0, alt1);
         }
-        if (j < my_strips) strip_step(j, a1, b1, a0, b0);
-        flush_strip(rotated(last_strip));
+        if (j < my_strips) {
+            strip_step(yes{}, j, a1, b1, a0, b0, alt0, alt1, acc0, acc1);
+            ++j;
+        }
+        // the last strip: strip j-1 sits in the first set when j is odd
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (j & 1) stash_piece(i, acc0, acc1);
+            else stash_piece(i, alt0, alt1);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) store_piece(i, rotated(last_strip), read_piece(i));
     }
 }
 
