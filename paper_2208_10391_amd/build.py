@@ -9,6 +9,13 @@ SOURCES = [os.path.join(CSRC, f) for f in ("eval.hip", "plan.cpp", "product_nn.h
                                             "product_nt.hip", "product_tt.hip")]
 
 
+# Per-source additions to the compile line.  eval.hip holds the kernels whose accumulators are read
+# out by other instructions than MFMAs (LDS writes of the skinny-pair kernel, the batched kernels'
+# stores): there the accumulators stay in the vector registers proper, which those instructions can
+# take as they are; from the accumulation registers every value would cost a vector move first.
+EXTRA_FLAGS = {"eval.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
+
 def _newest_source_mtime() -> float:
     paths = [os.path.join(CSRC, f) for f in os.listdir(CSRC)]
     paths.append(os.path.join(os.path.dirname(HERE), "include", "mom.h"))
@@ -35,7 +42,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
     try:
         def compile_one(src):
             obj = os.path.join(work, os.path.basename(src) + ".o")
-            cmd = [hipcc] + flags + ["-c", src, "-o", obj]
+            cmd = [hipcc] + flags + EXTRA_FLAGS.get(os.path.basename(src), []) + ["-c", src, "-o", obj]
             if verbose:
                 print(" ".join(cmd), flush=True)
             subprocess.run(cmd, check=True)

@@ -258,10 +258,16 @@ __device__ __forceinline__ void skinny_pair_body(const SkinnyPairParams &p, floa
     // burst of other instructions, for LDS, or for the accumulators to be read out.
     __syncthreads();                                       // every wavefront has read the partial sums
     float *patch = lds + wave * (kPairRows * kPatchLd);
+    // (a piece is one accumulator's four consecutive registers: every other column of eight, written
+    // as two two-address LDS writes straight from the accumulator registers)
     auto stash_piece = [&](int piece, const f32x16 &d0, const f32x16 &d1) {
-        const int q = piece / 2, h2 = piece % 2;
-        const f32x4 v = {d0[4 * q + 2 * h2], d1[4 * q + 2 * h2], d0[4 * q + 2 * h2 + 1], d1[4 * q + 2 * h2 + 1]};
-        *reinterpret_cast<f32x4 *>(patch + l32 * kPatchLd + 16 * q + 8 * half + 4 * h2) = v;
+        const int blk = piece / 4, q = piece % 4;
+        const f32x16 &d = blk ? d1 : d0;
+        float *dst = patch + l32 * kPatchLd + 16 * q + 8 * half + blk;
+        dst[0] = d[4 * q];
+        dst[2] = d[4 * q + 1];
+        dst[4] = d[4 * q + 2];
+        dst[6] = d[4 * q + 3];
     };
     auto read_piece = [&](int piece) {
         return *reinterpret_cast<const f32x4 *>(patch + (4 * piece + (lane >> 4)) * kPatchLd + 4 * (lane & 15));
@@ -284,7 +290,7 @@ __device__ __forceinline__ void skinny_pair_body(const SkinnyPairParams &p, floa
         // requested while this strip is multiplied, a whole strip (4096 MFMA cycles) ahead of their
         // use; after the last strip it is fetched once more and dropped.
         f32x2 a1[16], b1[16];
-        f32x16 alt0, alt1;                                 // the second accumulator set
+        f32x16 set0, set1, alt0, alt1;                     // two accumulator sets of two blocks each
         const f32x16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
         // Strip j into (c0, c1) while the finished strip j-1 leaves (d0, d1); have_done is false
         // for the first strip only.
@@ -314,21 +320,21 @@ __device__ __forceinline__ void skinny_pair_body(const SkinnyPairParams &p, floa
         };
         using yes = std::integral_constant<bool, true>;
         using no = std::integral_constant<bool, false>;
-        strip_step(no{}, 0, a0, b0, a1, b1, acc0, acc1, alt0, alt1);
+        strip_step(no{}, 0, a0, b0, a1, b1, set0, set1, alt0, alt1);
         int j = 1;
         for (; j + 1 < my_strips; j += 2) {
-            strip_step(yes{}, j, a1, b1, a0, b0, alt0, alt1, acc0, acc1);
-            strip_step(yes{}, j + 1, a0, b0, a1, b1, acc0, acc1, alt0, alt1);
+            strip_step(yes{}, j, a1, b1, a0, b0, alt0, alt1, set0, set1);
+            strip_step(yes{}, j + 1, a0, b0, a1, b1, set0, set1, alt0, alt1);
         }
         if (j < my_strips) {
-            strip_step(yes{}, j, a1, b1, a0, b0, alt0, alt1, acc0, acc1);
+            strip_step(yes{}, j, a1, b1, a0, b0, alt0, alt1, set0, set1);
             ++j;
         }
         // the last strip: strip j-1 sits in the first set when j is odd
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            if (j & 1) stash_piece(i, acc0, acc1);
+            if (j & 1) stash_piece(i, set0, set1);
             else stash_piece(i, alt0, alt1);
         }
 #pragma unroll
