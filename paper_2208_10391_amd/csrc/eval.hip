@@ -199,7 +199,9 @@ mom_status_t eval_chain(const mom_plan_t *plan, const float *const *d_factors, c
             const Resolved a = resolve(st.a, st.k), b = resolve(st.b, st.n), c = resolve(st.c, st.n);
             p.A = a.ptr; p.B = b.ptr; p.C = const_cast<float *>(c.ptr);
             p.lda = a.ld; p.ldb = b.ld; p.ldc = c.ld;
-            p.a_vec = aligned16(a.ptr, a.ld); p.b_vec = aligned16(b.ptr, b.ld);
+            // (a row stride of 2^22 elements or more leaves the reach of the kernel's 32-bit offsets)
+            p.a_vec = aligned16(a.ptr, a.ld) && a.ld < (1 << 22);
+            p.b_vec = aligned16(b.ptr, b.ld) && b.ld < (1 << 22);
             if (p.split_k > 1) {                           // partial sums go to the scratch region
                 p.C = reinterpret_cast<float *>(ws + plan->scratch_offset + st.scratch_offset);
                 p.ldc = st.n;

@@ -18,7 +18,8 @@ struct ProductParams {
     int pa, pb, pc;
     int tiles_m, tiles_n, num_tiles, order, paired, mirrored;
     int grid;              // workgroups per k-slice
-    int a_vec, b_vec;      // 16-byte loads are legal for A / B (base and row stride aligned)
+    int a_vec, b_vec;      // 16-byte loads at 32-bit offsets are legal for A / B (base and row stride aligned,
+                           // row stride below 2^22 elements)
     int c_vec;             // 16-byte stores are legal for C
     int split_k;
 };

@@ -26,6 +26,11 @@ namespace mom {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+// Fourth word of an untyped buffer descriptor (32-bit data format).  A load through such a
+// descriptor takes its address as descriptor base + scalar byte offset + one 32-bit vector byte
+// offset: everything that is the same for the whole workgroup stays in scalar registers.
+constexpr int kRawBufferFlags = 0x00020000;
 
 // Is (i, j) inside the structure of property p?  (p is never Identity here; diagonal, the last
 // case, reaches the batched and the element-wise kernels only.)
@@ -112,43 +117,42 @@ struct TileConfig {
     static __device__ __forceinline__ int b_k(int idx) { return TB ? (idx % (BK / 4)) * 4 : idx / (BN / 4); }
 };
 
-// Element-wise loads of one k-chunk for the edges of a matrix and for rows that are not
-// 16-byte aligned: bounds-checked and predicated on the structure, so nothing outside the
-// matrix or the triangle is touched.  src[q] is this thread's address of the q-th group of
-// four elements in the chunk that starts at k = kc.
+// Element-wise loads of one k-chunk for the edges of a matrix, for rows that are not 16-byte
+// aligned and for row strides too long for 32-bit offsets: bounds-checked and predicated on the
+// structure, so nothing outside the matrix or the triangle is touched; 64-bit addresses.
 template <class T>
-__device__ __forceinline__ void load_a_checked(const ProductParams &p, int r0, int kc, int tid,
-                                               const float *const (&src)[T::A_F4], f32x4 (&ra)[T::A_F4])
+__device__ __forceinline__ void load_a_checked(const ProductParams &p, int r0, int kc, int tid, f32x4 (&ra)[T::A_F4])
 {
 #pragma unroll
     for (int q = 0; q < T::A_F4; ++q) {
         const int idx = tid + q * T::NT;
         const int gi = r0 + T::a_row(idx), gk = kc + T::a_k(idx);
+        const float *src = T::TA ? p.A + (int64_t)gk * p.lda + gi : p.A + (int64_t)gi * p.lda + gk;
         f32x4 v;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int i = T::TA ? gi + e : gi, k = T::TA ? gk : gk + e;
             const bool ok = i < p.M && k < p.K && in_structure(p.pa, i, k);
-            v[e] = ok ? src[q][e] : 0.0f;
+            v[e] = ok ? src[e] : 0.0f;
         }
         ra[q] = v;
     }
 }
 
 template <class T>
-__device__ __forceinline__ void load_b_checked(const ProductParams &p, int c0, int kc, int tid,
-                                               const float *const (&src)[T::B_F4], f32x4 (&rb)[T::B_F4])
+__device__ __forceinline__ void load_b_checked(const ProductParams &p, int c0, int kc, int tid, f32x4 (&rb)[T::B_F4])
 {
 #pragma unroll
     for (int q = 0; q < T::B_F4; ++q) {
         const int idx = tid + q * T::NT;
         const int gk = kc + T::b_k(idx), gj = c0 + T::b_col(idx);
+        const float *src = T::TB ? p.B + (int64_t)gj * p.ldb + gk : p.B + (int64_t)gk * p.ldb + gj;
         f32x4 v;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int k = T::TB ? gk + e : gk, j = T::TB ? gj : gj + e;
             const bool ok = k < p.K && j < p.N && in_structure(p.pb, k, j);
-            v[e] = ok ? src[q][e] : 0.0f;
+            v[e] = ok ? src[e] : 0.0f;
         }
         rb[q] = v;
     }
@@ -329,8 +333,10 @@ constexpr int kSchedMfma = 0x008, kSchedVmemRead = 0x020, kSchedLdsRead = 0x100,
 template <class T>
 struct Pipeline {
     f32x4 ra[T::A_F4], rb[T::B_F4];     // the chunk on its way from HBM to LDS
-    const float *a_src[T::A_F4];        // this thread's addresses in the next chunk to load
-    const float *b_src[T::B_F4];        // (they advance with every chunk fetched)
+    // Where the next chunk to load starts (its first element: the same for the whole workgroup,
+    // scalar registers) and this thread's byte offsets from there (the same for every chunk).
+    const float *a_chunk, *b_chunk;
+    int a_off[T::A_F4], b_off[T::B_F4];
     Fragments<T> f0, f1;                // MFMA operands: current group, next group
     // fetch cursor: the next chunk to load is chunk fj of tile fw (the f_seq-th of the workgroup)
     TileWork fw;
@@ -380,18 +386,28 @@ __device__ __forceinline__ void next_fetch_tile(const ProductParams &p, int bloc
         if (pl.fw.nchunks > 0) break;
     }
     pl.fj = 0;
+    pl.a_chunk = T::TA ? p.A + (int64_t)pl.fw.klo * p.lda + pl.fw.r0 : p.A + (int64_t)pl.fw.r0 * p.lda + pl.fw.klo;
+    pl.b_chunk = T::TB ? p.B + (int64_t)pl.fw.c0 * p.ldb + pl.fw.klo : p.B + (int64_t)pl.fw.klo * p.ldb + pl.fw.c0;
+}
+
+// The 16-byte loads of one plain (or diagonal) chunk: through descriptors whose base is the
+// chunk's first element, then on to the next chunk with scalar arithmetic only.
+template <class T>
+__device__ __forceinline__ void load_chunk_vectors(const ProductParams &p, Pipeline<T> &pl)
+{
+    const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(pl.a_chunk), 0, 0x7fffffff, kRawBufferFlags);
+    const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(pl.b_chunk), 0, 0x7fffffff, kRawBufferFlags);
 #pragma unroll
-    for (int q = 0; q < T::A_F4; ++q) {
-        const int idx = tid + q * T::NT;
-        const int i = pl.fw.r0 + T::a_row(idx), k = pl.fw.klo + T::a_k(idx);
-        pl.a_src[q] = T::TA ? p.A + (int64_t)k * p.lda + i : p.A + (int64_t)i * p.lda + k;
-    }
+    for (int q = 0; q < T::A_F4; ++q) pl.ra[q] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(ra, pl.a_off[q], 0, 0));
 #pragma unroll
-    for (int q = 0; q < T::B_F4; ++q) {
-        const int idx = tid + q * T::NT;
-        const int k = pl.fw.klo + T::b_k(idx), j = pl.fw.c0 + T::b_col(idx);
-        pl.b_src[q] = T::TB ? p.B + (int64_t)j * p.ldb + k : p.B + (int64_t)k * p.ldb + j;
-    }
+    for (int q = 0; q < T::B_F4; ++q) pl.rb[q] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rb, pl.b_off[q], 0, 0));
+}
+
+template <class T>
+__device__ __forceinline__ void advance_chunk(const ProductParams &p, Pipeline<T> &pl)
+{
+    pl.a_chunk += T::TA ? (int64_t)T::BK * p.lda : T::BK;      // one chunk further along k
+    pl.b_chunk += T::TB ? T::BK : (int64_t)T::BK * p.ldb;
 }
 
 // Next chunk of the flat sequence: HBM -> registers.
@@ -402,20 +418,12 @@ __device__ __forceinline__ void fetch_chunk(const ProductParams &p, int block, i
     if (!pl.f_live) return;
     const int kind = chunk_kind<T>(p, pl.fw, pl.fj), kc = pl.fw.klo + pl.fj * T::BK;
     if (kind == kEdge) {
-        load_a_checked<T>(p, pl.fw.r0, kc, tid, pl.a_src, pl.ra);
-        load_b_checked<T>(p, pl.fw.c0, kc, tid, pl.b_src, pl.rb);
+        load_a_checked<T>(p, pl.fw.r0, kc, tid, pl.ra);
+        load_b_checked<T>(p, pl.fw.c0, kc, tid, pl.rb);
     } else {
-#pragma unroll
-        for (int q = 0; q < T::A_F4; ++q) pl.ra[q] = *reinterpret_cast<const f32x4 *>(pl.a_src[q]);
-#pragma unroll
-        for (int q = 0; q < T::B_F4; ++q) pl.rb[q] = *reinterpret_cast<const f32x4 *>(pl.b_src[q]);
+        load_chunk_vectors<T>(p, pl);
     }
-    const int64_t a_step = T::TA ? (int64_t)T::BK * p.lda : T::BK;     // one chunk further along k
-    const int64_t b_step = T::TB ? T::BK : (int64_t)T::BK * p.ldb;
-#pragma unroll
-    for (int q = 0; q < T::A_F4; ++q) pl.a_src[q] += a_step;
-#pragma unroll
-    for (int q = 0; q < T::B_F4; ++q) pl.b_src[q] += b_step;
+    advance_chunk<T>(p, pl);
     pl.reg_kind = kind; pl.reg_r0 = pl.fw.r0; pl.reg_c0 = pl.fw.c0; pl.reg_kc = kc;
     if (++pl.fj == pl.fw.nchunks) next_fetch_tile<T>(p, block, slice, tid, pl);
 }
@@ -464,12 +472,8 @@ __device__ __forceinline__ void chunk_step(float *smem, const ProductParams &p, 
         if (kg == MOVE) {
             if (HOT) {
                 stage_to_lds<T>(An, Bn, tid, pl.ra, pl.rb);
-                const int64_t a_step = T::TA ? (int64_t)T::BK * p.lda : T::BK;
-                const int64_t b_step = T::TB ? T::BK : (int64_t)T::BK * p.ldb;
-#pragma unroll
-                for (int q = 0; q < T::A_F4; ++q) { pl.ra[q] = *reinterpret_cast<const f32x4 *>(pl.a_src[q]); pl.a_src[q] += a_step; }
-#pragma unroll
-                for (int q = 0; q < T::B_F4; ++q) { pl.rb[q] = *reinterpret_cast<const f32x4 *>(pl.b_src[q]); pl.b_src[q] += b_step; }
+                load_chunk_vectors<T>(p, pl);
+                advance_chunk<T>(p, pl);
             } else {
                 staged = pl.in_regs;
                 if (pl.in_regs) {
@@ -525,6 +529,16 @@ __global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const Pro
 
     // prologue of the whole workgroup: flat chunk 0 into stage 0, flat chunk 1 into the registers
     Pipeline<T> pl;
+#pragma unroll
+    for (int q = 0; q < T::A_F4; ++q) {
+        const int idx = tid + q * T::NT;
+        pl.a_off[q] = (T::TA ? T::a_k(idx) * (int)p.lda + T::a_row(idx) : T::a_row(idx) * (int)p.lda + T::a_k(idx)) * 4;
+    }
+#pragma unroll
+    for (int q = 0; q < T::B_F4; ++q) {
+        const int idx = tid + q * T::NT;
+        pl.b_off[q] = (T::TB ? T::b_col(idx) * (int)p.ldb + T::b_k(idx) : T::b_k(idx) * (int)p.ldb + T::b_col(idx)) * 4;
+    }
     pl.f_seq = -1;
     pl.f_live = true;
     next_fetch_tile<T>(p, block, slice, tid, pl);

@@ -46,8 +46,6 @@ namespace mom {
 
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-constexpr int kRawBufferFlags = 0x00020000;     // fourth word of an untyped buffer descriptor (32-bit data format)
 
 constexpr int kPairRows = 32;            // rows of the result per workgroup
 constexpr int kPairMaxWidth = 64;        // widest intermediate (two interleaved 32-column blocks)

@@ -340,3 +340,27 @@ def test_few_tiles_with_triangular_operands_are_split_along_k(pa, pb):
     plan, _ = check_against_dense(dims, props, chain(dims, props, 970))
     # 72 chunks in the full k for n = 2304: product launch + slice sum; 35 chunks for n = 1100: one launch
     assert mom.mom_plan_num_launches(plan) == (2 if n == 2304 else 1)
+
+
+def test_row_stride_beyond_the_reach_of_32_bit_offsets():
+    """A factor whose rows lie 2^22 elements (16 MiB) apart: the 16-byte loads of the product kernel
+    address a chunk with 32-bit byte offsets from its first element, which 128 such rows exceed, so
+    these operands take the element-wise path with 64-bit addresses."""
+    m, k, n, ld = 200, 160, 136, 1 << 22
+    a = sc.make_factor(m, k, G, 31)
+    b = sc.make_factor(k, n, G, 32)
+    wide = torch.empty((m - 1) * ld + k, device="cuda", dtype=torch.float32)          # 3.3 GB, only m x k of it used
+    a_dev = torch.as_strided(wide, (m, k), (ld, 1))
+    a_dev.copy_(a.cuda())
+    plan = mom.mom_chain_plan([m, k, n], [G, G])
+    out = mom.mom_chain_eval(plan, [a_dev, b.cuda()])
+    torch.cuda.synchronize()
+    want = a.numpy().astype(np.float64) @ b.numpy().astype(np.float64)
+    assert rel_fro(out.cpu().numpy(), want) <= TOL
+    # and as the right-hand operand, transposed
+    plan = mom.mom_chain_plan_ex([n, k, m], [G, G], [1, 1])
+    out = mom.mom_chain_eval(plan, [b.cuda(), a_dev])
+    torch.cuda.synchronize()
+    assert rel_fro(out.cpu().numpy(), want.T) <= TOL
+    del wide, a_dev
+    torch.cuda.empty_cache()
