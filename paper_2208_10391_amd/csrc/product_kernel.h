@@ -571,7 +571,7 @@ __global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const Pro
             // Pairs of chunks (stage 0, stage 1) run the decision-free body for as long as the
             // chunk in the registers and the ones to load are plain chunks of the fetch tile.
             if (!(g & 1) && pl.in_regs && pl.reg_kind == kPlain && pl.f_live && pl.fj >= pl.fw.f_lo) {
-                const int pairs = min(n - c, pl.fw.f_hi - pl.fj) / 2;
+                const int pairs = __builtin_amdgcn_readfirstlane(min(n - c, pl.fw.f_hi - pl.fj) / 2);     // (uniform: a scalar loop counter)
                 if (pairs > 0) {
                     for (int i = 0; i < pairs; ++i) {
                         chunk_step<T, true, 0>(smem, p, block, slice, 0, tid, a_lane, b_lane, pl, acc);
