@@ -296,14 +296,35 @@ __device__ __forceinline__ int chunk_kind(const ProductParams &p, const TileWork
     return (w.a_edge || w.b_edge || w.klo + (j + 1) * T::BK > p.K) ? kEdge : kDiag;
 }
 
+// How the rectangle rows [r_lo, r_hi] x columns [c_lo, c_hi] of a triangular matrix lies to its
+// structure: 1 wholly inside, 0 wholly outside, 2 across the diagonal.
+__device__ __forceinline__ int structure_class(int prop, int r_lo, int r_hi, int c_lo, int c_hi)
+{
+    if (prop == kLower) return c_hi <= r_lo ? 1 : (c_lo > r_hi ? 0 : 2);       // kept: column <= row
+    if (prop == kUpper) return c_lo >= r_hi ? 1 : (c_hi < r_lo ? 0 : 2);       // kept: column >= row
+    return 1;
+}
+
 // Zero what lies outside the structures in the registers of the chunk that starts at k = kc.
+// The q-th 16-byte group of all threads together covers a rectangle of the operand (32 rows of
+// an A tile by the chunk's k-range when A is stored as it is read, a few k-values by all rows
+// when it is stored transposed; B likewise): where that rectangle lies wholly inside or outside
+// the structure, which the whole workgroup knows at once, no element is compared.
 template <class T>
 __device__ __forceinline__ void mask_registers(const ProductParams &p, int r0, int c0, int kc, int tid,
                                                f32x4 (&ra)[T::A_F4], f32x4 (&rb)[T::B_F4])
 {
+    const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
     if (p.pa != kGeneral) {
+        constexpr int ROWS = T::TA ? T::BM : T::NT / (T::BK / 4);      // rows and k-values one group index spans
+        constexpr int KS = T::TA ? T::NT / (T::BM / 4) : T::BK;
 #pragma unroll
         for (int q = 0; q < T::A_F4; ++q) {
+            const int i_lo = r0 + (T::TA ? 0 : q * ROWS), k_lo = kc + (T::TA ? q * KS : 0);
+            // (stored transposed, a group spans all rows of the tile: next to a diagonal always across)
+            const int cls = T::TA ? 2 : structure_class(p.pa, i_lo, i_lo + ROWS - 1, k_lo, k_lo + KS - 1);
+            if (cls == 0) ra[q] = zero;
+            if (cls != 2) continue;
             const int idx = tid + q * T::NT;
             const int gi = r0 + T::a_row(idx), gk = kc + T::a_k(idx);
 #pragma unroll
@@ -312,8 +333,14 @@ __device__ __forceinline__ void mask_registers(const ProductParams &p, int r0, i
         }
     }
     if (p.pb != kGeneral) {
+        constexpr int COLS = T::TB ? T::NT / (T::BK / 4) : T::BN;
+        constexpr int KS = T::TB ? T::BK : T::NT / (T::BN / 4);
 #pragma unroll
         for (int q = 0; q < T::B_F4; ++q) {
+            const int j_lo = c0 + (T::TB ? q * COLS : 0), k_lo = kc + (T::TB ? 0 : q * KS);
+            const int cls = T::TB ? structure_class(p.pb, k_lo, k_lo + KS - 1, j_lo, j_lo + COLS - 1) : 2;
+            if (cls == 0) rb[q] = zero;
+            if (cls != 2) continue;
             const int idx = tid + q * T::NT;
             const int gk = kc + T::b_k(idx), gj = c0 + T::b_col(idx);
 #pragma unroll
