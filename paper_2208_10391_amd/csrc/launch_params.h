@@ -17,6 +17,7 @@ struct ProductParams {
     int M, N, K;
     int pa, pb, pc;
     int tiles_m, tiles_n, num_tiles, order, paired, mirrored;
+    int k_walk;            // bit 0: the first tile of a workgroup walks its k-range downwards, bit 1: its later tiles do
     int grid;              // workgroups per k-slice
     int a_vec, b_vec;      // 16-byte loads at 32-bit offsets are legal for A / B (base and row stride aligned,
                            // row stride below 2^22 elements)

@@ -231,14 +231,14 @@ __device__ __forceinline__ void mfma_group(const Fragments<T> &f, f32x16 (&acc)[
 // interior for both operands.
 struct TileWork {
     int r0, c0;            // first row / column of the tile
-    int klo;               // first k (a multiple of BK)
+    int k0, kstep;         // chunk j starts at k = k0 + j * kstep (kstep = BK, or -BK for a range walked downwards)
     int nchunks;           // chunks of BK to multiply (0: the tile is all zeros)
     int f_lo, f_hi;        // chunks [f_lo, f_hi) need neither masking nor bounds checks
     bool a_edge, b_edge;   // the tile pokes over the matrix edge, or rows are not 16-byte aligned
 };
 
 template <class T>
-__device__ __forceinline__ TileWork tile_work(const ProductParams &p, int t, int slice)
+__device__ __forceinline__ TileWork tile_work(const ProductParams &p, int t, int slice, bool down)
 {
     int I, J;
     tile_coords(p.order, t, p.tiles_m, p.tiles_n, I, J);
@@ -261,7 +261,6 @@ __device__ __forceinline__ TileWork tile_work(const ProductParams &p, int t, int
         nchunks = min(per, nchunks - first);
         klo += first * T::BK;
     }
-    w.klo = klo;
     w.nchunks = nchunks;
     w.a_edge = !p.a_vec || w.r0 + T::BM > p.M;
     w.b_edge = !p.b_vec || w.c0 + T::BN > p.N;
@@ -276,6 +275,14 @@ __device__ __forceinline__ TileWork tile_work(const ProductParams &p, int t, int
         if (p.pb == kUpper) k_to = min(k_to, w.c0);
         w.f_lo = min((k_from - klo) / T::BK, nchunks);
         w.f_hi = max(min((k_to - klo) / T::BK, nchunks), w.f_lo);
+    }
+    w.k0 = klo;
+    w.kstep = T::BK;
+    if (down) {                                      // the same chunks, last one first
+        const int lo = nchunks - w.f_hi, hi = nchunks - w.f_lo;
+        w.f_lo = lo; w.f_hi = hi;
+        w.k0 = klo + (nchunks - 1) * T::BK;
+        w.kstep = -T::BK;
     }
     return w;
 }
@@ -293,7 +300,7 @@ template <class T>
 __device__ __forceinline__ int chunk_kind(const ProductParams &p, const TileWork &w, int j)
 {
     if (j >= w.f_lo && j < w.f_hi) return kPlain;
-    return (w.a_edge || w.b_edge || w.klo + (j + 1) * T::BK > p.K) ? kEdge : kDiag;
+    return (w.a_edge || w.b_edge || w.k0 + j * w.kstep + T::BK > p.K) ? kEdge : kDiag;
 }
 
 // How the rectangle rows [r_lo, r_hi] x columns [c_lo, c_hi] of a triangular matrix lies to its
@@ -363,6 +370,7 @@ struct Pipeline {
     // Where the next chunk to load starts (its first element: the same for the whole workgroup,
     // scalar registers) and this thread's byte offsets from there (the same for every chunk).
     const float *a_chunk, *b_chunk;
+    int64_t a_step, b_step;             // elements from one chunk of the fetch tile to the next
     int a_off[T::A_F4], b_off[T::B_F4];
     Fragments<T> f0, f1;                // MFMA operands: current group, next group
     // fetch cursor: the next chunk to load is chunk fj of tile fw (the f_seq-th of the workgroup)
@@ -373,6 +381,13 @@ struct Pipeline {
     bool in_regs;
     int reg_kind, reg_r0, reg_c0, reg_kc;
 };
+
+// Whether the i-th tile of a workgroup walks its k-range downwards.
+__device__ __forceinline__ bool walks_down(const ProductParams &p, int block, int i)
+{
+    const bool second = p.mirrored ? block >= (p.num_tiles + 1) / 2 : i > 0;
+    return (p.k_walk >> (second ? 1 : 0)) & 1;
+}
 
 // The i-th tile of a workgroup (-1: none): tile `block` and its partner from the other end of
 // the longest-first order when tiles are paired, else every grid-th tile.
@@ -409,12 +424,14 @@ __device__ __forceinline__ void next_fetch_tile(const ProductParams &p, int bloc
     for (;;) {
         const int t = tile_at(p, block, ++pl.f_seq);
         if (t < 0) { pl.f_live = false; return; }
-        pl.fw = tile_work<T>(p, t, slice);
+        pl.fw = tile_work<T>(p, t, slice, walks_down(p, block, pl.f_seq));
         if (pl.fw.nchunks > 0) break;
     }
     pl.fj = 0;
-    pl.a_chunk = T::TA ? p.A + (int64_t)pl.fw.klo * p.lda + pl.fw.r0 : p.A + (int64_t)pl.fw.r0 * p.lda + pl.fw.klo;
-    pl.b_chunk = T::TB ? p.B + (int64_t)pl.fw.c0 * p.ldb + pl.fw.klo : p.B + (int64_t)pl.fw.klo * p.ldb + pl.fw.c0;
+    pl.a_chunk = T::TA ? p.A + (int64_t)pl.fw.k0 * p.lda + pl.fw.r0 : p.A + (int64_t)pl.fw.r0 * p.lda + pl.fw.k0;
+    pl.b_chunk = T::TB ? p.B + (int64_t)pl.fw.c0 * p.ldb + pl.fw.k0 : p.B + (int64_t)pl.fw.k0 * p.ldb + pl.fw.c0;
+    pl.a_step = T::TA ? (int64_t)pl.fw.kstep * p.lda : pl.fw.kstep;
+    pl.b_step = T::TB ? pl.fw.kstep : (int64_t)pl.fw.kstep * p.ldb;
 }
 
 // The 16-byte loads of one plain (or diagonal) chunk: through descriptors whose base is the
@@ -433,8 +450,8 @@ __device__ __forceinline__ void load_chunk_vectors(const ProductParams &p, Pipel
 template <class T>
 __device__ __forceinline__ void advance_chunk(const ProductParams &p, Pipeline<T> &pl)
 {
-    pl.a_chunk += T::TA ? (int64_t)T::BK * p.lda : T::BK;      // one chunk further along k
-    pl.b_chunk += T::TB ? T::BK : (int64_t)T::BK * p.ldb;
+    pl.a_chunk += pl.a_step;      // one chunk further along k
+    pl.b_chunk += pl.b_step;
 }
 
 // Next chunk of the flat sequence: HBM -> registers.
@@ -443,7 +460,7 @@ __device__ __forceinline__ void fetch_chunk(const ProductParams &p, int block, i
 {
     pl.in_regs = pl.f_live;
     if (!pl.f_live) return;
-    const int kind = chunk_kind<T>(p, pl.fw, pl.fj), kc = pl.fw.klo + pl.fj * T::BK;
+    const int kind = chunk_kind<T>(p, pl.fw, pl.fj), kc = pl.fw.k0 + pl.fj * pl.fw.kstep;
     if (kind == kEdge) {
         load_a_checked<T>(p, pl.fw.r0, kc, tid, pl.ra);
         load_b_checked<T>(p, pl.fw.c0, kc, tid, pl.rb);
@@ -582,7 +599,7 @@ __global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const Pro
     for (int seq = 0;; ++seq) {
         const int t = tile_at(p, block, seq);
         if (t < 0) break;
-        const TileWork w = tile_work<T>(p, t, slice);
+        const TileWork w = tile_work<T>(p, t, slice, walks_down(p, block, seq));
         const int n = w.nchunks;
 
         f32x16 acc[T::FM][T::FN];
@@ -607,7 +624,7 @@ __global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const Pro
                     c += 2 * pairs;
                     g += 2 * pairs;
                     pl.fj += 2 * pairs;                          // the registers hold chunk fj-1 of the fetch tile
-                    pl.reg_r0 = pl.fw.r0; pl.reg_c0 = pl.fw.c0; pl.reg_kc = pl.fw.klo + (pl.fj - 1) * T::BK;
+                    pl.reg_r0 = pl.fw.r0; pl.reg_c0 = pl.fw.c0; pl.reg_kc = pl.fw.k0 + (pl.fj - 1) * pl.fw.kstep;
                     if (pl.fj == pl.fw.nchunks) next_fetch_tile<T>(p, block, slice, tid, pl);
                     continue;
                 }

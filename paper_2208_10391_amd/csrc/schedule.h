@@ -45,6 +45,8 @@ struct Launch {
     int mirrored;          // pairs few enough to leave compute units with one workgroup: the two tiles of
                            // a pair go to two workgroups, b (long tile) and b + pairs (short tile), which
                            // the dispatcher places on the same compute unit; they then overlap each other
+    int k_walk;            // direction in which tiles walk their k-range (bit 0: a workgroup's first tile
+                           // downwards, bit 1: its later tiles downwards)
     int grid;              // workgroups
     int split_k;           // >1: the k-range is cut into this many slices, summed by a second kernel
     size_t scratch_bytes;  // split_k * m * n floats of partial sums
@@ -111,6 +113,17 @@ inline Launch choose_launch(const ProductStep &st)
     if (L.paired && (L.order == kRowsDesc || L.order == kRowsAsc) && L.tiles_m % (2 * kXcds) == 0 &&
         L.tiles_m > 2 * L.tiles_n && L.num_tiles % (2 * kXcds) == 0)
         L.paired = 2;
+    // Tiles that share an operand panel hit in a die's L2 only while they are at the same k at about
+    // the same time (the L2 merges misses in flight, but holds only some ten chunks of what a die's
+    // workgroups stream).  The clipped k-ranges of a triangular operand all share one end (k = 0 for
+    // L*G and G*U, k = K for U*G and G*L): tiles that start together walk away from that end; the
+    // second, short tile of a pair starts when its long partner ends, that is the later the shorter
+    // it is, and walks towards the shared end, which puts all second tiles at the same k again.  The
+    // same holds when the pair is two workgroups on one compute unit: the older one takes most of
+    // the matrix pipe, so the short tile runs mostly after the long one.
+    const bool high_end = L.order == kRowsAsc || L.order == kColsAsc;
+    L.k_walk = (high_end ? 1 : 0) | ((L.paired ? !high_end : high_end) ? 2 : 0);
+    if (L.order != kRowsDesc && L.order != kRowsAsc && L.order != kColsAsc && L.order != kColsDesc) L.k_walk = 0;
     L.grid = L.paired ? (L.num_tiles + 1) / 2 : L.num_tiles;
     L.mirrored = (L.paired && L.grid <= kComputeUnits) ? 1 : 0;
     if (L.mirrored) L.grid *= 2;

@@ -72,6 +72,15 @@ def test_paired_tiles_whole_result(pa, pb):
     run_whole(dims, props, sc.make_chain(dims, props, 71), reference="dense")
 
 
+@pytest.mark.parametrize("pa,pb,n", [(L, G, 2900), (U, G, 2899), (G, L, 2899), (G, U, 2900)])
+def test_paired_tiles_ragged_whole_result(pa, pb, n):
+    # 23 x 23 tiles again, the last row and column of tiles ragged (n = 2899: rows not 16-byte aligned
+    # either): the second tile of a pair walks its k-range from the far end, so its first chunk is the
+    # ragged or the diagonal one
+    dims, props = [n, n, n], [pa, pb]
+    run_whole(dims, props, sc.make_chain(dims, props, 77), reference="dense")
+
+
 @pytest.mark.parametrize("pa", [L, U])
 def test_paired_tiles_rectangular_right_hand_side_whole_result(pa):
     # 24 x 28 = 672 tiles, paired, more tile columns than tile rows
