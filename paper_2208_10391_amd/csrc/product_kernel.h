@@ -357,6 +357,44 @@ __device__ __forceinline__ void mask_registers(const ProductParams &p, int r0, i
     }
 }
 
+// The MFMAs of one group of 8 k-values for a chunk next to a diagonal: 32x32 blocks of a triangular operand that lie wholly
+// outside its structure are not multiplied at all.  Bit bi of `skip` drops row block bi of the
+// wavefront, bit 8 + bj column block bj (the same for the whole wavefront: scalar branches).
+template <class T>
+__device__ __forceinline__ void mfma_group_some(const Fragments<T> &f, f32x16 (&acc)[T::FM][T::FN], int skip)
+{
+    // (one plain condition per block, none nested and none with an else: each block's accumulator is
+    // updated in place; with anything richer the compiler copies accumulators at the joins)
+#pragma unroll
+    for (int bi = 0; bi < T::FM; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < T::FN; ++bj) {
+            if (skip & ((1 << bi) | (256 << bj))) continue;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.b[bj][e], f.a[bi][e], acc[bi][bj], 0, 0, 0);
+        }
+}
+
+// Which of a wavefront's blocks chunk [kc, kc + BK) of a tile cannot touch: the skip mask of
+// mfma_group_some.  wr0 / wc0: first row / column of the wavefront inside the tile.
+template <class T>
+__device__ __forceinline__ int blocks_outside(const ProductParams &p, int r0, int c0, int kc, int wr0, int wc0)
+{
+    int skip = 0;
+#pragma unroll
+    for (int bi = 0; bi < T::FM; ++bi) {
+        const int r_lo = r0 + wr0 + bi * T::RSTEP;
+        if (structure_class(p.pa, r_lo, r_lo + 31, kc, kc + T::BK - 1) == 0) skip |= 1 << bi;
+    }
+#pragma unroll
+    for (int bj = 0; bj < T::FN; ++bj) {
+        const int c_lo = c0 + wc0 + bj * T::CSTEP;
+        if (structure_class(p.pb, kc, kc + T::BK - 1, c_lo, c_lo + 31) == 0) skip |= 256 << bj;
+    }
+    return skip;
+}
+
 // Scheduling groups (masks of __builtin_amdgcn_sched_group_barrier).
 constexpr int kSchedMfma = 0x008, kSchedVmemRead = 0x020, kSchedLdsRead = 0x100, kSchedLdsWrite = 0x200;
 
@@ -485,7 +523,7 @@ __device__ __forceinline__ void fetch_chunk(const ProductParams &p, int block, i
 // (kDiag), element-wise loads (kEdge), a new fetch tile, the end of the workgroup's chunks.
 template <class T, bool HOT, int S>
 __device__ __forceinline__ void chunk_step(float *smem, const ProductParams &p, int block, int slice, int s_, int tid,
-                                           int a_lane, int b_lane, Pipeline<T> &pl, f32x16 (&acc)[T::FM][T::FN])
+                                           int a_lane, int b_lane, Pipeline<T> &pl, f32x16 (&acc)[T::FM][T::FN], int skip = 0)
 {
     constexpr int NKG = T::BK / 8;
     static_assert(NKG % 2 == 0, "the operand double buffer returns to f0 after an even number of groups");
@@ -527,7 +565,7 @@ __device__ __forceinline__ void chunk_step(float *smem, const ProductParams &p, 
                 fetch_chunk<T>(p, block, slice, tid, pl);
             }
         }
-        mfma_group<T>(now, acc);
+        if (HOT) mfma_group<T>(now, acc); else mfma_group_some<T>(now, acc, skip);
         if (!HOT) {
             // the general body is left to the compiler's own scheduling
         } else if (kg == MOVE) {
@@ -629,7 +667,9 @@ __global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const Pro
                     continue;
                 }
             }
-            chunk_step<T, false, 0>(smem, p, block, slice, g & 1, tid, a_lane, b_lane, pl, acc);
+            const int swave = __builtin_amdgcn_readfirstlane(wave);       // (the wavefront's place in the tile, in scalar registers)
+            const int skip = blocks_outside<T>(p, w.r0, w.c0, w.k0 + c * w.kstep, (swave / T::WN) * 32, (swave % T::WN) * 32);
+            chunk_step<T, false, 0>(smem, p, block, slice, g & 1, tid, a_lane, b_lane, pl, acc, skip);
             ++c;
             ++g;
         }
