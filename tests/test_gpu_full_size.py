@@ -97,6 +97,15 @@ def test_split_k_with_triangular_operands_and_results_whole_result(pa, pb, n):
     assert mom.mom_plan_num_launches(plan) == 2
 
 
+@pytest.mark.parametrize("dims,props", [([4000, 4000, 200], [U, G]), ([200, 4000, 4000], [G, L]),
+                                        ([4000, 4000, 200], [L, G]), ([200, 4000, 4000], [G, U])])
+def test_split_k_with_one_triangular_operand_whole_result(dims, props):
+    # 64 tiles and 125 chunks: split-K; with U * G and G * L every slice of a tile's clipped k-range is
+    # walked from its far end, and the last chunk of the range is ragged
+    plan = run_whole(dims, props, sc.make_chain(dims, props, 78), reference="dense")
+    assert mom.mom_plan_num_launches(plan) == 2
+
+
 def test_persistent_grid_whole_result():
     # 24 x 24 = 576 equal tiles > 512 resident workgroups, k = 288 >= 256: every workgroup
     # strides over the tiles, some take two
