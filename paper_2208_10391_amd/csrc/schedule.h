@@ -101,10 +101,14 @@ inline Launch choose_launch(const ProductStep &st)
         L.num_tiles = L.tiles_m * L.tiles_n;
     // Pair the longest tile with the shortest, the second longest with the second shortest,
     // ...: for the linear length profile of a triangular operand every workgroup then does
-    // the same amount of work.  Worth it while the pairs still cover the chip and the tiles are
-    // few: from about four rounds of resident workgroups on, handing out single tiles longest
-    // first balances by itself and keeps more workgroups in flight.
-    L.paired = (L.order != kRowMajor && L.num_tiles >= 2 * kComputeUnits && L.num_tiles < 8 * kComputeUnits) ? 1 : 0;
+    // the same amount of work, and a pair's second tile rides the pipeline of the first instead of
+    // starting a workgroup of its own.  Measured: for one triangular operand (the linear profiles)
+    // a gain up to the 4096 tiles of an 8192^3 product, the largest tried (+1.3 to +1.6 %);
+    // for two triangular operands, whose many short tiles do not pair up to equal sums, a loss
+    // from about four rounds of resident workgroups on (there single tiles, longest first).
+    const bool linear = L.order == kRowsDesc || L.order == kRowsAsc || L.order == kColsAsc || L.order == kColsDesc;
+    L.paired = (L.order != kRowMajor && L.num_tiles >= 2 * kComputeUnits &&
+                L.num_tiles < (linear ? 17 : 8) * kComputeUnits) ? 1 : 0;
     // A tall triangular operand against a narrow right-hand side (more than twice as many tile
     // rows as tile columns): the triangle is the bulk of the traffic, and with the plain order
     // every die streams all of it, once per tile column it holds.  Give each die 1/8 of the tile

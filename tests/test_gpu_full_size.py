@@ -66,7 +66,7 @@ def run_whole(dims, props, host, splits=None, flags=0, reference="plan", expect_
 
 @pytest.mark.parametrize("pa,pb", [(L, G), (U, G), (G, L), (G, U)])
 def test_paired_tiles_whole_result(pa, pb):
-    # 23 x 23 = 529 tiles of 128: between 512 and 2047, so workgroup b takes tiles b and 528-b
+    # 23 x 23 = 529 tiles of 128: at least 512, so workgroup b takes tiles b and 528-b
     n = 2944
     dims, props = [n, n, n], [pa, pb]
     run_whole(dims, props, sc.make_chain(dims, props, 71), reference="dense")
@@ -79,6 +79,13 @@ def test_paired_tiles_ragged_whole_result(pa, pb, n):
     # ragged or the diagonal one
     dims, props = [n, n, n], [pa, pb]
     run_whole(dims, props, sc.make_chain(dims, props, 77), reference="dense")
+
+
+@pytest.mark.parametrize("dims,props", [([8192, 8192, 4352], [L, G]), ([4352, 8192, 8192], [G, U])])
+def test_paired_tiles_beyond_four_rounds_whole_result(dims, props):
+    # 64 x 34 = 2176 tiles: more than four rounds of resident workgroups, still paired when only one
+    # operand is triangular
+    run_whole(dims, props, sc.make_chain(dims, props, 79))
 
 
 @pytest.mark.parametrize("pa", [L, U])
