@@ -17,7 +17,8 @@ struct ProductParams {
     int M, N, K;
     int pa, pb, pc;
     int tiles_m, tiles_n, num_tiles, order, paired, mirrored;
-    int k_walk;            // bit 0: the first tile of a workgroup walks its k-range downwards, bit 1: its later tiles do
+    int folded;            // single tiles; workgroups 256..511 take tiles min(T, 512) - 1 - (b - 256)
+    int k_walk;            // bit 0: the first tile of a workgroup walks its k-range downwards, bit 1: its later tiles (the short tiles of mirrored and folded launches) do
     int grid;              // workgroups per k-slice
     int a_vec, b_vec;      // 16-byte loads at 32-bit offsets are legal for A / B (base and row stride aligned,
                            // row stride below 2^22 elements)

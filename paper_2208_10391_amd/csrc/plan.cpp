@@ -345,7 +345,7 @@ mom_status_t lay_out_launches(mom_plan *plan)
                 p.M = (int)st.m; p.N = (int)st.n; p.K = (int)st.k;
                 p.pa = st.pa; p.pb = st.pb; p.pc = st.pc;
                 p.tiles_m = L.tiles_m; p.tiles_n = L.tiles_n; p.num_tiles = L.num_tiles;
-                p.order = L.order; p.paired = L.paired; p.mirrored = L.mirrored; p.k_walk = L.k_walk; p.grid = L.grid;
+                p.order = L.order; p.paired = L.paired; p.mirrored = L.mirrored; p.k_walk = L.k_walk; p.folded = L.folded; p.grid = L.grid;
                 p.split_k = L.split_k;
                 p.slice_stride = L.split_k > 1 ? st.m * st.n : 0;
                 if (L.split_k > 1) {

@@ -423,7 +423,8 @@ struct Pipeline {
 // Whether the i-th tile of a workgroup walks its k-range downwards.
 __device__ __forceinline__ bool walks_down(const ProductParams &p, int block, int i)
 {
-    const bool second = p.mirrored ? block >= (p.num_tiles + 1) / 2 : i > 0;
+    const bool second = p.mirrored ? block >= (p.num_tiles + 1) / 2
+                                   : (p.folded ? block >= kComputeUnits && block < 2 * kComputeUnits : i > 0);
     return (p.k_walk >> (second ? 1 : 0)) & 1;
 }
 
@@ -451,6 +452,11 @@ __device__ __forceinline__ int tile_at(const ProductParams &p, int block, int i)
     if (p.paired) {
         const int partner = p.num_tiles - 1 - block;
         return i == 0 ? block : (i == 1 && partner > block ? partner : -1);
+    }
+    if (p.folded) {              // one tile each; the second 256 workgroups in reverse
+        if (i > 0) return -1;
+        const int hi = min(p.num_tiles, 2 * kComputeUnits);
+        return block >= kComputeUnits && block < hi ? hi - 1 - (block - kComputeUnits) : block;
     }
     const int64_t t = block + (int64_t)i * p.grid;
     return t < p.num_tiles ? (int)t : -1;

@@ -45,6 +45,7 @@ struct Launch {
     int mirrored;          // pairs few enough to leave compute units with one workgroup: the two tiles of
                            // a pair go to two workgroups, b (long tile) and b + pairs (short tile), which
                            // the dispatcher places on the same compute unit; they then overlap each other
+    int folded;            // single tiles, the second 256 workgroups in reverse order (see choose_launch)
     int k_walk;            // direction in which tiles walk their k-range (bit 0: a workgroup's first tile
                            // downwards, bit 1: its later tiles downwards)
     int grid;              // workgroups
@@ -100,15 +101,22 @@ inline Launch choose_launch(const ProductStep &st)
     else
         L.num_tiles = L.tiles_m * L.tiles_n;
     // Pair the longest tile with the shortest, the second longest with the second shortest,
-    // ...: for the linear length profile of a triangular operand every workgroup then does
+    // ...: for the linear length profile of one triangular operand every workgroup then does
     // the same amount of work, and a pair's second tile rides the pipeline of the first instead of
-    // starting a workgroup of its own.  Measured: for one triangular operand (the linear profiles)
-    // a gain up to the 4096 tiles of an 8192^3 product, the largest tried (+1.3 to +1.6 %);
-    // for two triangular operands, whose many short tiles do not pair up to equal sums, a loss
-    // from about four rounds of resident workgroups on (there single tiles, longest first).
+    // starting a workgroup of its own.  Equal workgroups only pay when they fill the chip evenly:
+    // with 265 pairs on 256 compute units nine units do twice the work of the others (45 % of the
+    // peak measured, 69 % with single tiles), so tiles are paired only when the pairs are a
+    // multiple of the compute units (up to the 4096 tiles of an 8192^3 product, the largest
+    // tried: +1.3 to +1.6 % against single tiles).  Two triangular operands have many short
+    // tiles that do not pair up to equal sums: never paired.
     const bool linear = L.order == kRowsDesc || L.order == kRowsAsc || L.order == kColsAsc || L.order == kColsDesc;
-    L.paired = (L.order != kRowMajor && L.num_tiles >= 2 * kComputeUnits &&
-                L.num_tiles < (linear ? 17 : 8) * kComputeUnits) ? 1 : 0;
+    L.paired = (linear && L.num_tiles >= 2 * kComputeUnits && L.num_tiles < 17 * kComputeUnits &&
+                ((L.num_tiles + 1) / 2) % kComputeUnits == 0) ? 1 : 0;
+    // Otherwise single tiles, longest first, which the dispatcher hands to whichever compute unit
+    // has a free slot; only the start is fixed: workgroups b and b + 256 share a compute unit, so
+    // the second 256 take their tiles in reverse (compute unit c starts with the c-th longest and
+    // the c-th shortest of the first 512 tiles: equal sums for a linear profile).
+    L.folded = (!L.paired && L.order != kRowMajor && L.num_tiles > kComputeUnits) ? 1 : 0;
     // A tall triangular operand against a narrow right-hand side (more than twice as many tile
     // rows as tile columns): the triangle is the bulk of the traffic, and with the plain order
     // every die streams all of it, once per tile column it holds.  Give each die 1/8 of the tile
@@ -126,7 +134,7 @@ inline Launch choose_launch(const ProductStep &st)
     // same holds when the pair is two workgroups on one compute unit: the older one takes most of
     // the matrix pipe, so the short tile runs mostly after the long one.
     const bool high_end = L.order == kRowsAsc || L.order == kColsAsc;
-    L.k_walk = (high_end ? 1 : 0) | ((L.paired ? !high_end : high_end) ? 2 : 0);
+    L.k_walk = (high_end ? 1 : 0) | (((L.paired || L.folded) ? !high_end : high_end) ? 2 : 0);
     if (L.order != kRowsDesc && L.order != kRowsAsc && L.order != kColsAsc && L.order != kColsDesc) L.k_walk = 0;
     L.grid = L.paired ? (L.num_tiles + 1) / 2 : L.num_tiles;
     L.mirrored = (L.paired && L.grid <= kComputeUnits) ? 1 : 0;

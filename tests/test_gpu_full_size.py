@@ -65,32 +65,41 @@ def run_whole(dims, props, host, splits=None, flags=0, reference="plan", expect_
 # ---- one dense-checked product per large-launch path ---------------------------------------
 
 @pytest.mark.parametrize("pa,pb", [(L, G), (U, G), (G, L), (G, U)])
-def test_paired_tiles_whole_result(pa, pb):
-    # 23 x 23 = 529 tiles of 128: at least 512, so workgroup b takes tiles b and 528-b
+def test_single_tiles_second_256_reversed_whole_result(pa, pb):
+    # 23 x 23 = 529 tiles of 128, 265 pairs would not fill 256 compute units evenly: single tiles,
+    # workgroups 256..511 take tiles 511..256
     n = 2944
     dims, props = [n, n, n], [pa, pb]
     run_whole(dims, props, sc.make_chain(dims, props, 71), reference="dense")
 
 
 @pytest.mark.parametrize("pa,pb,n", [(L, G, 2900), (U, G, 2899), (G, L, 2899), (G, U, 2900)])
-def test_paired_tiles_ragged_whole_result(pa, pb, n):
+def test_single_tiles_ragged_whole_result(pa, pb, n):
     # 23 x 23 tiles again, the last row and column of tiles ragged (n = 2899: rows not 16-byte aligned
-    # either): the second tile of a pair walks its k-range from the far end, so its first chunk is the
-    # ragged or the diagonal one
+    # either): the tiles of workgroups 256..511 walk their k-range from the far end, so their first
+    # chunk is the ragged or the diagonal one
     dims, props = [n, n, n], [pa, pb]
     run_whole(dims, props, sc.make_chain(dims, props, 77), reference="dense")
 
 
 @pytest.mark.parametrize("dims,props", [([8192, 8192, 4352], [L, G]), ([4352, 8192, 8192], [G, U])])
-def test_paired_tiles_beyond_four_rounds_whole_result(dims, props):
-    # 64 x 34 = 2176 tiles: more than four rounds of resident workgroups, still paired when only one
-    # operand is triangular
+def test_single_tiles_beyond_four_rounds_whole_result(dims, props):
+    # 64 x 34 = 2176 tiles: more than four rounds of resident workgroups
     run_whole(dims, props, sc.make_chain(dims, props, 79))
 
 
+@pytest.mark.parametrize("pa,pb,n", [(L, G, 4000), (U, G, 3999), (G, L, 3999), (G, U, 4000)])
+def test_paired_tiles_ragged_whole_result(pa, pb, n):
+    # 32 x 32 = 1024 tiles, 512 pairs (two per compute unit): workgroup b takes tiles b and 1023-b, the
+    # second one walked from the far end of its k-range; the last row and column of tiles ragged
+    # (n = 3999: rows not 16-byte aligned either)
+    dims, props = [n, n, n], [pa, pb]
+    run_whole(dims, props, sc.make_chain(dims, props, 80), rows_seed=81)
+
+
 @pytest.mark.parametrize("pa", [L, U])
-def test_paired_tiles_rectangular_right_hand_side_whole_result(pa):
-    # 24 x 28 = 672 tiles, paired, more tile columns than tile rows
+def test_single_tiles_rectangular_right_hand_side_whole_result(pa):
+    # 24 x 28 = 672 tiles, more tile columns than tile rows
     dims, props = [3072, 3072, 3584], [pa, G]
     run_whole(dims, props, sc.make_chain(dims, props, 75), reference="dense")
 
