@@ -234,7 +234,9 @@ struct TileWork {
     int k0, kstep;         // chunk j starts at k = k0 + j * kstep (kstep = BK, or -BK for a range walked downwards)
     int nchunks;           // chunks of BK to multiply (0: the tile is all zeros)
     int f_lo, f_hi;        // chunks [f_lo, f_hi) need neither masking nor bounds checks
-    bool a_edge, b_edge;   // the tile pokes over the matrix edge, or rows are not 16-byte aligned
+    bool a_edge, b_edge;   // the operand's part of the tile cannot be loaded 16 bytes at a time: rows not
+                           // 16-byte aligned, or the tile pokes over the matrix edge and a 16-byte group
+                           // could straddle the end of a row
 };
 
 template <class T>
@@ -262,8 +264,8 @@ __device__ __forceinline__ TileWork tile_work(const ProductParams &p, int t, int
         klo += first * T::BK;
     }
     w.nchunks = nchunks;
-    w.a_edge = !p.a_vec || w.r0 + T::BM > p.M;
-    w.b_edge = !p.b_vec || w.c0 + T::BN > p.N;
+    w.a_edge = !p.a_vec || (w.r0 + T::BM > p.M && !p.a_tail);
+    w.b_edge = !p.b_vec || (w.c0 + T::BN > p.N && !p.b_tail);
     // What a property or an edge makes special is always a run of chunks at the head and a
     // run at the tail of the k-range; the chunks in between are interior.
     w.f_lo = w.f_hi = 0;
@@ -289,18 +291,25 @@ __device__ __forceinline__ TileWork tile_work(const ProductParams &p, int t, int
 
 // How the operands of chunk j of a tile get from HBM to LDS (uniform over the workgroup):
 //   kPlain  16-byte loads, staged as they are
-//   kDiag   16-byte loads; the chunk straddles a diagonal, so the elements outside the
-//           structure are zeroed when the registers are staged (one chunk after the load, when
-//           the data has long arrived)
-//   kEdge   edge of a matrix or unaligned rows: element-wise loads, bounds-checked and
-//           predicated on the structure; staged as they are
+//   kDiag   16-byte loads; the chunk straddles a diagonal or the end of k, so the elements outside
+//           the structure or beyond k are zeroed when the registers are staged (one chunk after
+//           the load, when the data has long arrived)
+//   kEdge   unaligned rows, or an edge of the matrix that a 16-byte group could straddle:
+//           element-wise loads, bounds-checked and predicated on the structure; staged as they are
+// 16-byte loads go through buffer descriptors that end with the matrix: what lies past its last
+// element (rows below the last one, the tail of the last row) reads as zero and is never
+// touched.  What a tile reads beyond an edge INSIDE the buffer (the next row's head in place of
+// columns past the edge) only reaches rows or columns of the tile that are not stored, except
+// along k, which the mask covers.
 enum ChunkKind : int { kPlain = 0, kDiag = 1, kEdge = 2 };
 
 template <class T>
 __device__ __forceinline__ int chunk_kind(const ProductParams &p, const TileWork &w, int j)
 {
     if (j >= w.f_lo && j < w.f_hi) return kPlain;
-    return (w.a_edge || w.b_edge || w.k0 + j * w.kstep + T::BK > p.K) ? kEdge : kDiag;
+    if (w.a_edge || w.b_edge) return kEdge;
+    // the ragged last chunk of k: 16-byte loads and a mask when nothing can straddle the end of k
+    return (w.k0 + j * w.kstep + T::BK > p.K && !(p.a_tail && p.b_tail)) ? kEdge : kDiag;
 }
 
 // How the rectangle rows [r_lo, r_hi] x columns [c_lo, c_hi] of a triangular matrix lies to its
@@ -322,6 +331,18 @@ __device__ __forceinline__ void mask_registers(const ProductParams &p, int r0, i
                                                f32x4 (&ra)[T::A_F4], f32x4 (&rb)[T::B_F4])
 {
     const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (kc + T::BK > p.K) {      // ragged end of k: whole groups (the extent along k is a multiple of four)
+        if (!T::TA) {
+#pragma unroll
+            for (int q = 0; q < T::A_F4; ++q)
+                if (kc + T::a_k(tid + q * T::NT) >= p.K) ra[q] = zero;
+        }
+        if (T::TB) {
+#pragma unroll
+            for (int q = 0; q < T::B_F4; ++q)
+                if (kc + T::b_k(tid + q * T::NT) >= p.K) rb[q] = zero;
+        }
+    }
     if (p.pa != kGeneral) {
         constexpr int ROWS = T::TA ? T::BM : T::NT / (T::BK / 4);      // rows and k-values one group index spans
         constexpr int KS = T::TA ? T::NT / (T::BM / 4) : T::BK;
@@ -408,7 +429,8 @@ struct Pipeline {
     // Where the next chunk to load starts (its first element: the same for the whole workgroup,
     // scalar registers) and this thread's byte offsets from there (the same for every chunk).
     const float *a_chunk, *b_chunk;
-    int64_t a_step, b_step;             // elements from one chunk of the fetch tile to the next
+    const float *a_end, *b_end;         // one past the last element of A / B: where their descriptors end
+    int a_step, b_step;                 // elements from one chunk of the fetch tile to the next
     int a_off[T::A_F4], b_off[T::B_F4];
     Fragments<T> f0, f1;                // MFMA operands: current group, next group
     // fetch cursor: the next chunk to load is chunk fj of tile fw (the f_seq-th of the workgroup)
@@ -474,8 +496,8 @@ __device__ __forceinline__ void next_fetch_tile(const ProductParams &p, int bloc
     pl.fj = 0;
     pl.a_chunk = T::TA ? p.A + (int64_t)pl.fw.k0 * p.lda + pl.fw.r0 : p.A + (int64_t)pl.fw.r0 * p.lda + pl.fw.k0;
     pl.b_chunk = T::TB ? p.B + (int64_t)pl.fw.c0 * p.ldb + pl.fw.k0 : p.B + (int64_t)pl.fw.k0 * p.ldb + pl.fw.c0;
-    pl.a_step = T::TA ? (int64_t)pl.fw.kstep * p.lda : pl.fw.kstep;
-    pl.b_step = T::TB ? pl.fw.kstep : (int64_t)pl.fw.kstep * p.ldb;
+    pl.a_step = T::TA ? pl.fw.kstep * (int)p.lda : pl.fw.kstep;      // (row strides of 16-byte-loadable operands are below 2^22)
+    pl.b_step = T::TB ? pl.fw.kstep : pl.fw.kstep * (int)p.ldb;
 }
 
 // The 16-byte loads of one plain (or diagonal) chunk: through descriptors whose base is the
@@ -483,8 +505,14 @@ __device__ __forceinline__ void next_fetch_tile(const ProductParams &p, int bloc
 template <class T>
 __device__ __forceinline__ void load_chunk_vectors(const ProductParams &p, Pipeline<T> &pl)
 {
-    const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(pl.a_chunk), 0, 0x7fffffff, kRawBufferFlags);
-    const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(pl.b_chunk), 0, 0x7fffffff, kRawBufferFlags);
+    // (bytes from the chunk's first element to the end of the matrix; a thread's offsets stay below 2^31)
+    const uint64_t a_left = (uint64_t)(pl.a_end - pl.a_chunk) * 4, b_left = (uint64_t)(pl.b_end - pl.b_chunk) * 4;
+    // (clamped to 2^31 - 1 in 32-bit pieces: there is no scalar 64-bit ordering compare)
+    const uint32_t a_lo = (uint32_t)a_left, b_lo = (uint32_t)b_left;
+    const uint32_t a_over = (uint32_t)(a_left >> 32) | (a_lo >> 31), b_over = (uint32_t)(b_left >> 32) | (b_lo >> 31);
+    const int a_bytes = a_over != 0 ? 0x7fffffff : (int)a_lo, b_bytes = b_over != 0 ? 0x7fffffff : (int)b_lo;
+    const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(pl.a_chunk), 0, a_bytes, kRawBufferFlags);
+    const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(pl.b_chunk), 0, b_bytes, kRawBufferFlags);
 #pragma unroll
     for (int q = 0; q < T::A_F4; ++q) pl.ra[q] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(ra, pl.a_off[q], 0, 0));
 #pragma unroll
@@ -627,6 +655,8 @@ __global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const Pro
         const int idx = tid + q * T::NT;
         pl.b_off[q] = (T::TB ? T::b_col(idx) * (int)p.ldb + T::b_k(idx) : T::b_k(idx) * (int)p.ldb + T::b_col(idx)) * 4;
     }
+    pl.a_end = T::TA ? p.A + (int64_t)(p.K - 1) * p.lda + p.M : p.A + (int64_t)(p.M - 1) * p.lda + p.K;
+    pl.b_end = T::TB ? p.B + (int64_t)(p.N - 1) * p.ldb + p.K : p.B + (int64_t)(p.K - 1) * p.ldb + p.N;
     pl.f_seq = -1;
     pl.f_live = true;
     next_fetch_tile<T>(p, block, slice, tid, pl);
