@@ -41,8 +41,8 @@ WORKLOADS = {
     "batched32": ("batched32", None),
     # a chain on which the two planning objectives part: the multiplication-optimal tree, and the
     # tree of the time objective (timed with its own, larger, multiplication count as tree_flop)
-    "gggl512_min_mults": ("gggl512", None),
-    "gggl512_min_time": ("gggl512", "min_time"),
+    "gggl256_min_mults": ("gggl256", None),
+    "gggl256_min_time": ("gggl256", "min_time"),
     # element-wise passes, bound by HBM: a diagonal times a general matrix (one scaling launch)
     # and the sum of three general matrices (an equation whose addends are plain matrices)
     "dscale8192": ("dscale8192", None),
@@ -53,7 +53,7 @@ WORKLOADS = {
 }
 ELEMENTWISE_KERNEL = {"copy8192": "copy_structure_kernel", "dscale8192": "diag_scale_kernel", "add3_8192": "add_terms_kernel"}
 SIDE_WORKLOADS = ["trmm4096", "trmm4096_transposed", "general5", "general5_left_to_right", "mixed5_tri_intermediate",
-                  "mixed5_left_to_right", "batched32", "gggl512_min_mults", "gggl512_min_time", "dscale8192", "add3_8192"]
+                  "mixed5_left_to_right", "batched32", "gggl256_min_mults", "gggl256_min_time", "dscale8192", "add3_8192"]
 
 sc.CONFIGS["copy8192"] = sc.ChainConfig("copy8192", 9, (8192, 8192), (sc.GENERAL,))
 sc.CONFIGS["dscale8192"] = sc.ChainConfig("dscale8192", 10, (8192, 8192, 8192), (sc.DIAGONAL, sc.GENERAL))

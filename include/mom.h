@@ -121,7 +121,9 @@ mom_status_t mom_plan_from_splits(const int64_t *dims, const int32_t *props, int
  * count is not the run time.  This opt-in objective minimises, by the same dynamic program, the
  * sum over the tree's products of an integer estimate in picoseconds of the tiled kernel's
  * time for X (m x k) * Y (k x n):
- *   T = 64 if m <= 64 or n <= 64, else 128 (square output tiles); k-chunks of 32;
+ *   T = 64 if m <= 64 or n <= 64 or ceil(m/128) * ceil(n/128) <= limit, else 128 (square output
+ *   tiles), with limit = 192 when neither operand is triangular, 448 for one triangular operand,
+ *   900 for lowerTri * upperTri and upperTri * lowerTri, 1400 for two equal triangles; k-chunks of 32;
  *   a tile (I, J) exists unless it lies wholly in the zero half of a triangular result;
  *   its k-range is [0, k) clipped by the operands' structures (X lowerTri: k < min((I+1)T, m);
  *   X upperTri: k >= I*T; Y lowerTri: k >= J*T; Y upperTri: k < min((J+1)T, n)), start rounded

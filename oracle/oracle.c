@@ -301,7 +301,10 @@ done:
 /* estimate, in integer picoseconds, of what the tiled product kernel        */
 /* spends on X (m x k, pX) * Y (k x n, pY).  Stated so that both sides can   */
 /* compute it exactly:                                                       */
-/*   T  = 64 if m <= 64 or n <= 64, else 128        (square output tiles)    */
+/*   T  = 64 if m <= 64 or n <= 64 or ceil(m/128) * ceil(n/128) <= limit,    */
+/*        else 128 (square output tiles); limit = 192 when neither operand   */
+/*        is triangular, 448 for one triangular operand, 900 for lowerTri *  */
+/*        upperTri and upperTri * lowerTri, 1400 for two equal triangles     */
 /*   a tile (I, J) of the result exists unless the result is triangular and  */
 /*   the tile lies wholly in its zero half                                   */
 /*   k-range of a tile: [0, k) clipped by the operands' structures           */
@@ -341,7 +344,9 @@ static u128 product_time(int64_t m, int64_t k, int64_t n, int pX, int pY)
         return TIME_LAUNCH_PS + 4 * (structural_entries(m, k, pX) + structural_entries(k, n, pY) +
                                      structural_entries(m, n, pD)) / 8;
     }
-    int64_t T = (m <= 64 || n <= 64) ? 64 : 128;
+    int triX = pX == P_LOWER || pX == P_UPPER, triY = pY == P_LOWER || pY == P_UPPER;
+    int64_t limit = (triX && triY) ? (pX == pY ? 1400 : 900) : ((triX || triY) ? 448 : 192);
+    int64_t T = (m <= 64 || n <= 64 || ((m + 127) / 128) * ((n + 127) / 128) <= limit) ? 64 : 128;
     u128 chunk_ps = T == 128 ? TIME_CHUNK128_PS : TIME_CHUNK64_PS;
     int pR = product_property(pX, pY);
     int64_t tm = (m + T - 1) / T, tn = (n + T - 1) / T;

@@ -712,12 +712,14 @@ __global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const Pro
 
         // store: register v of lane (l32, half) is C[row l32][column 8*(v/4) + 4*half + v%4] of its
         // 32x32 block.  Full tiles of a general result (or tiles strictly inside the triangle) go out
-        // unchecked, 16 bytes at a time when the result allows; edge and diagonal tiles element by
-        // element, the triangle only
+        // unchecked, 16 bytes at a time when the result allows; so do the groups of four of an edge
+        // tile that lie inside the matrix; the rest and diagonal tiles element by element, the
+        // triangle only
         float *const C = p.C + (int64_t)slice * p.slice_stride;
-        bool plain = w.r0 + T::BM <= p.M && w.c0 + T::BN <= p.N;
-        if (p.pc == kLower) plain = plain && w.c0 + T::BN - 1 <= w.r0;
-        if (p.pc == kUpper) plain = plain && w.r0 + T::BM - 1 <= w.c0;
+        bool inside = true;                                // no element of the tile lies outside the result's structure
+        if (p.pc == kLower) inside = w.c0 + T::BN - 1 <= w.r0;
+        if (p.pc == kUpper) inside = w.r0 + T::BM - 1 <= w.c0;
+        const bool plain = inside && w.r0 + T::BM <= p.M && w.c0 + T::BN <= p.N;
 #pragma unroll
         for (int bi = 0; bi < T::FM; ++bi)
 #pragma unroll
@@ -727,7 +729,7 @@ __global__ __launch_bounds__(T::NT, T::MIN_BLOCKS) void product_kernel(const Pro
                     const int gi = w.r0 + wr0 + bi * T::RSTEP + l32;
                     const int gj = w.c0 + wc0 + bj * T::CSTEP + 8 * q + 4 * half;
                     float *dst = C + (int64_t)gi * p.ldc + gj;
-                    if (plain && p.c_vec) {
+                    if (p.c_vec && (plain || (inside && gi < p.M && gj + 4 <= p.N))) {
                         const f32x4 v = {acc[bi][bj][4 * q], acc[bi][bj][4 * q + 1], acc[bi][bj][4 * q + 2], acc[bi][bj][4 * q + 3]};
                         *reinterpret_cast<f32x4 *>(dst) = v;
                     } else {

@@ -83,6 +83,14 @@ inline bool fits_skinny_pair(const ProductStep &inner, const ProductStep &outer)
            outer.n >= kPairMinCols;
 }
 
+// Up to how many 128x128 tiles of the result a product runs on 64x64 tiles instead.
+inline int small_tile_limit(int pa, int pb)
+{
+    const bool ta = pa == kLower || pa == kUpper, tb = pb == kLower || pb == kUpper;
+    if (ta && tb) return pa == pb ? 1400 : 900;
+    return ta || tb ? 448 : 192;
+}
+
 inline Launch choose_launch(const ProductStep &st)
 {
     Launch L{};
@@ -90,7 +98,14 @@ inline Launch choose_launch(const ProductStep &st)
         L.shape = kTile128; L.bm = L.bn = 128; L.split_k = 1;
         return L;
     }
-    const bool small = st.m <= 64 || st.n <= 64;
+    // 64x64 tiles when a side is at most 64, and when 128x128 tiles would be too few to keep the
+    // 256 compute units busy.  Triangular operands make a tile count worth less (the tiles' k-ranges
+    // run from one chunk to all of k) and a triangular result leaves only half of the tiles.
+    // Limits measured on square products (64x64 tiles run at about 80 % of the peak when they
+    // fill the chip): general n <= 1664, one triangular operand n <= 2688, L*U and U*L
+    // n <= 3840, L*L and U*U n <= 4736.
+    const int64_t t128 = ((st.m + 127) / 128) * ((st.n + 127) / 128);
+    const bool small = st.m <= 64 || st.n <= 64 || t128 <= small_tile_limit(st.pa, st.pb);
     L.shape = small ? kTile64 : kTile128;
     L.bm = L.bn = small ? 64 : 128;
     L.tiles_m = (int)((st.m + L.bm - 1) / L.bm);

@@ -41,10 +41,10 @@ CONFIGS = {
     "mixed5": ChainConfig("mixed5", 4, (8192, 8192, 8192, 8192, 8192, 1024),
                           (LOWER_TRI, IDENTITY, LOWER_TRI, UPPER_TRI, GENERAL)),
     # general * general * general * lowerTri: a chain on which the multiplication count and the
-    # time model choose different trees (the count forms the 1024 x 512 product with k = 4096
+    # time model choose different trees (the count forms the 1024 x 256 product with k = 4096
     # first, then two more dependent products; the time model pairs the factors up, two
-    # independent products that share a launch, at one and a half times the multiplications)
-    "gggl512": ChainConfig("gggl512", 6, (512, 1024, 4096, 512, 512), (GENERAL, GENERAL, GENERAL, LOWER_TRI)),
+    # independent products that share a launch, at 1.29 times the multiplications)
+    "gggl256": ChainConfig("gggl256", 6, (256, 1024, 4096, 256, 256), (GENERAL, GENERAL, GENERAL, LOWER_TRI)),
     # 4096 independent chains L * G * U of 32x32 factors
     "batched32": ChainConfig("batched32", 5, (32, 32, 32, 32), (LOWER_TRI, GENERAL, UPPER_TRI),
                              batch=4096),

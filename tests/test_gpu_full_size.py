@@ -104,13 +104,13 @@ def test_single_tiles_rectangular_right_hand_side_whole_result(pa):
     run_whole(dims, props, sc.make_chain(dims, props, 75), reference="dense")
 
 
-@pytest.mark.parametrize("pa,pb,n", [(L, L, 2048), (U, U, 2048), (L, L, 2100), (U, U, 2688)])
-def test_split_k_with_triangular_operands_and_results_whole_result(pa, pb, n):
-    # fewer than 256 tiles and k >= 2048: every tile's clipped k-range is cut into slices, also when
-    # the result is a triangle (136 to 231 tiles); the summing kernel touches the triangle only
+@pytest.mark.parametrize("pa,pb,n", [(L, L, 2560), (U, U, 2560), (L, L, 2600), (U, U, 2688)])
+def test_two_triangular_operands_on_small_tiles_whole_result(pa, pb, n):
+    # 820 to 903 tiles of 64 x 64 (a triangular result of this size runs on the small tiles), single
+    # tiles with the second 256 workgroups in reverse; one size ragged
     dims, props = [n, n, n], [pa, pb]
     plan = run_whole(dims, props, sc.make_chain(dims, props, 76), reference="dense")
-    assert mom.mom_plan_num_launches(plan) == 2
+    assert mom.mom_plan_num_launches(plan) == 1
 
 
 @pytest.mark.parametrize("dims,props", [([4000, 4000, 200], [U, G]), ([200, 4000, 4000], [G, L]),

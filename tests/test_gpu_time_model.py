@@ -29,8 +29,8 @@ def timed(call, reps=30):
 
 
 def test_time_objective_tree_is_correct_and_faster_where_the_objectives_part():
-    c = sc.CONFIGS["gggl512"]
-    host = sc.make_config("gggl512")
+    c = sc.CONFIGS["gggl256"]
+    host = sc.make_config("gggl256")
     np_f = [f.numpy() for f in host]
     by_mults = mom.mom_chain_plan(c.dims, c.props)
     by_time = mom.mom_chain_plan_ex(c.dims, c.props, None, objective=mom.MOM_PLAN_MIN_TIME)

@@ -101,11 +101,11 @@ def test_large_matrix_bound_general_chains_get_the_multiplication_optimal_tree()
 
 
 def test_a_chain_where_the_two_objectives_part():
-    # general * general * general * lowerTri, 512 x 1024 x 4096 x 512 x 512: the fewest multiplications
-    # are in ((0 (1 2)) 3), three dependent products of which the first has 32 tiles and a long k;
-    # the time model prefers ((0 1) (2 3)): half as many again, in two independent products and a root
-    dims, props = [512, 1024, 4096, 512, 512], [G, G, G, L]
+    # general * general * general * lowerTri, 256 x 1024 x 4096 x 256 x 256: the fewest multiplications
+    # are in ((0 (1 2)) 3), three dependent products of which the first has few tiles and a long k;
+    # the time model prefers ((0 1) (2 3)): 1.29 times as many, in two independent products and a root
+    dims, props = [256, 1024, 4096, 256, 256], [G, G, G, L]
     a, b = oracle.plan_bruteforce(dims, props), oracle.plan_bruteforce_time(dims, props)
     assert a["splits"] == [2, 0, 1] and b["splits"] == [1, 0, 2]
-    assert b["mults"] > 1.4 * a["cost"]
+    assert b["mults"] > 1.25 * a["cost"]
     assert oracle.tree_time_ps(dims, props, a["splits"]) > 1.1 * b["time_ps"]

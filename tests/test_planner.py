@@ -236,8 +236,8 @@ def test_time_objective_equals_the_oracle_enumeration():
         b = mom.mom_chain_plan_ex(c.dims, c.props, None, objective=mom.MOM_PLAN_MIN_TIME)
         assert a.splits == b.splits
     # and one chain where the objectives part (see tests/test_oracle_time_model.py)
-    a = mom.mom_chain_plan([512, 1024, 4096, 512, 512], [G, G, G, L])
-    b = mom.mom_chain_plan_ex([512, 1024, 4096, 512, 512], [G, G, G, L], None, objective=mom.MOM_PLAN_MIN_TIME)
+    a = mom.mom_chain_plan([256, 1024, 4096, 256, 256], [G, G, G, L])
+    b = mom.mom_chain_plan_ex([256, 1024, 4096, 256, 256], [G, G, G, L], None, objective=mom.MOM_PLAN_MIN_TIME)
     assert (a.string, b.string) == ("((0 (1 2)) 3)", "((0 1) (2 3))")
 
 
