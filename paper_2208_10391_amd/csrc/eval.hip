@@ -202,6 +202,7 @@ mom_status_t eval_chain(const mom_plan_t *plan, const float *const *d_factors, c
             // (a row stride of 2^22 elements or more leaves the reach of the kernel's 32-bit offsets)
             p.a_vec = aligned16(a.ptr, a.ld) && a.ld < (1 << 22);
             p.b_vec = aligned16(b.ptr, b.ld) && b.ld < (1 << 22);
+            p.a_word = a.ld < (1 << 22); p.b_word = b.ld < (1 << 22);
             p.a_tail = p.a_vec && ((pl.variant & 1) ? p.M : p.K) % 4 == 0;      // (bit 0 of the variant: A is stored transposed)
             p.b_tail = p.b_vec && ((pl.variant & 2) ? p.K : p.N) % 4 == 0;
             if (p.split_k > 1) {                           // partial sums go to the scratch region
@@ -210,7 +211,9 @@ mom_status_t eval_chain(const mom_plan_t *plan, const float *const *d_factors, c
             }
             p.c_vec = aligned16(p.C, p.ldc);
         }
-        if (kLaunchers[pl.variant](pl.shape, batch, stream) != hipSuccess) return MOM_ERR_HIP;
+        bool words = false;
+        for (int i = 0; i < batch.count; ++i) words = words || needs_words(batch.prob[i]);
+        if (kLaunchers[pl.variant](pl.shape, words, batch, stream) != hipSuccess) return MOM_ERR_HIP;
         if (pl.reduce.count > 0) {
             ReduceBatch reduce = pl.reduce;
             for (int i = 0; i < reduce.count; ++i) {

@@ -22,6 +22,7 @@ struct ProductParams {
     int grid;              // workgroups per k-slice
     int a_vec, b_vec;      // 16-byte loads at 32-bit offsets are legal for A / B (base and row stride aligned,
                            // row stride below 2^22 elements)
+    int a_word, b_word;    // the row stride is below 2^22 elements: 32-bit byte offsets reach every element of a tile
     int a_tail, b_tail;    // ... and the extent along which the buffer is contiguous is a multiple of four, so no
                            // 16-byte group straddles the end of a row: tiles that poke over the matrix edge can
                            // then be loaded 16 bytes at a time through a descriptor that ends with the matrix

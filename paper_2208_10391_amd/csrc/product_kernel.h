@@ -82,11 +82,14 @@ __device__ __forceinline__ void tile_coords(int order, int t, int tm, int tn, in
 // fetched and staged the way a plain B tile is ([k][i], contiguous along i, read from LDS
 // with one 4-byte read per k), a transposed B tile the way a plain A tile is ([j][k + pad],
 // read with one 16-byte read per lane).
-template <int BM_, int BN_, int BK_, int WM_, int WN_, int MIN_BLOCKS_, bool TA_ = false, bool TB_ = false>
+// WORDS: the instance also knows how to load an operand 4 bytes at a time (rows that are not
+// 16-byte aligned, edges that a 16-byte group could straddle); the instance without it keeps
+// that code out of the way of the products whose operands never need it.
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int MIN_BLOCKS_, bool TA_ = false, bool TB_ = false, bool WORDS_ = false>
 struct TileConfig {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
     static constexpr int MIN_BLOCKS = MIN_BLOCKS_;
-    static constexpr bool TA = TA_, TB = TB_;
+    static constexpr bool TA = TA_, TB = TB_, WORDS = WORDS_;
     static constexpr int NT = WM * WN * 64;           // threads per workgroup
     static constexpr int WTM = BM / WM, WTN = BN / WN;   // tile of one wavefront
     static constexpr int FM = WTM / 32, FN = WTN / 32;   // 32x32 MFMA blocks per wavefront
@@ -234,9 +237,10 @@ struct TileWork {
     int k0, kstep;         // chunk j starts at k = k0 + j * kstep (kstep = BK, or -BK for a range walked downwards)
     int nchunks;           // chunks of BK to multiply (0: the tile is all zeros)
     int f_lo, f_hi;        // chunks [f_lo, f_hi) need neither masking nor bounds checks
-    bool a_edge, b_edge;   // the operand's part of the tile cannot be loaded 16 bytes at a time: rows not
-                           // 16-byte aligned, or the tile pokes over the matrix edge and a 16-byte group
-                           // could straddle the end of a row
+    int a_load, b_load;    // how the operand's part of the tile is loaded: 16 bytes at a time; 4 bytes at a time
+                           // (rows not 16-byte aligned, or the tile pokes over the matrix edge and a 16-byte
+                           // group could straddle the end of a row); or 0: element-wise with 64-bit
+                           // addresses (a row stride out of reach of 32-bit offsets)
 };
 
 template <class T>
@@ -264,12 +268,12 @@ __device__ __forceinline__ TileWork tile_work(const ProductParams &p, int t, int
         klo += first * T::BK;
     }
     w.nchunks = nchunks;
-    w.a_edge = !p.a_vec || (w.r0 + T::BM > p.M && !p.a_tail);
-    w.b_edge = !p.b_vec || (w.c0 + T::BN > p.N && !p.b_tail);
+    w.a_load = p.a_vec && (w.r0 + T::BM <= p.M || p.a_tail) ? 16 : (T::WORDS && p.a_word ? 4 : 0);
+    w.b_load = p.b_vec && (w.c0 + T::BN <= p.N || p.b_tail) ? 16 : (T::WORDS && p.b_word ? 4 : 0);
     // What a property or an edge makes special is always a run of chunks at the head and a
     // run at the tail of the k-range; the chunks in between are interior.
     w.f_lo = w.f_hi = 0;
-    if (!w.a_edge && !w.b_edge) {
+    if (w.a_load == 16 && w.b_load == 16) {
         int k_from = klo, k_to = (p.K / T::BK) * T::BK;
         if (p.pa == kUpper) k_from = max(k_from, w.r0 + T::BM);
         if (p.pb == kLower) k_from = max(k_from, w.c0 + T::BN);
@@ -291,12 +295,13 @@ __device__ __forceinline__ TileWork tile_work(const ProductParams &p, int t, int
 
 // How the operands of chunk j of a tile get from HBM to LDS (uniform over the workgroup):
 //   kPlain  16-byte loads, staged as they are
-//   kDiag   16-byte loads; the chunk straddles a diagonal or the end of k, so the elements outside
-//           the structure or beyond k are zeroed when the registers are staged (one chunk after
-//           the load, when the data has long arrived)
-//   kEdge   unaligned rows, or an edge of the matrix that a 16-byte group could straddle:
-//           element-wise loads, bounds-checked and predicated on the structure; staged as they are
-// 16-byte loads go through buffer descriptors that end with the matrix: what lies past its last
+//   kDiag   loads through descriptors, 16 bytes at a time or, where rows are not 16-byte aligned or
+//           a group could straddle a matrix edge, 4 bytes at a time; the elements outside the
+//           structure or beyond a ragged end of k are zeroed when the registers are staged (one
+//           chunk after the load, when the data has long arrived)
+//   kEdge   a row stride beyond the reach of 32-bit offsets: element-wise loads with 64-bit
+//           addresses, bounds-checked and predicated on the structure; staged as they are
+// Descriptor loads go through buffer descriptors that end with the matrix: what lies past its last
 // element (rows below the last one, the tail of the last row) reads as zero and is never
 // touched.  What a tile reads beyond an edge INSIDE the buffer (the next row's head in place of
 // columns past the edge) only reaches rows or columns of the tile that are not stored, except
@@ -307,9 +312,9 @@ template <class T>
 __device__ __forceinline__ int chunk_kind(const ProductParams &p, const TileWork &w, int j)
 {
     if (j >= w.f_lo && j < w.f_hi) return kPlain;
-    if (w.a_edge || w.b_edge) return kEdge;
-    // the ragged last chunk of k: 16-byte loads and a mask when nothing can straddle the end of k
-    return (w.k0 + j * w.kstep + T::BK > p.K && !(p.a_tail && p.b_tail)) ? kEdge : kDiag;
+    // through descriptors (16 or 4 bytes at a time), masked at staging where a mask is due: next to a
+    // diagonal and at a ragged end of k
+    return (w.a_load == 0 || w.b_load == 0) ? kEdge : kDiag;
 }
 
 // How the rectangle rows [r_lo, r_hi] x columns [c_lo, c_hi] of a triangular matrix lies to its
@@ -331,16 +336,20 @@ __device__ __forceinline__ void mask_registers(const ProductParams &p, int r0, i
                                                f32x4 (&ra)[T::A_F4], f32x4 (&rb)[T::B_F4])
 {
     const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
-    if (kc + T::BK > p.K) {      // ragged end of k: whole groups (the extent along k is a multiple of four)
+    if (kc + T::BK > p.K) {      // ragged end of k, where k runs along the rows of the buffer
         if (!T::TA) {
 #pragma unroll
             for (int q = 0; q < T::A_F4; ++q)
-                if (kc + T::a_k(tid + q * T::NT) >= p.K) ra[q] = zero;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (kc + T::a_k(tid + q * T::NT) + e >= p.K) ra[q][e] = 0.0f;
         }
         if (T::TB) {
 #pragma unroll
             for (int q = 0; q < T::B_F4; ++q)
-                if (kc + T::b_k(tid + q * T::NT) >= p.K) rb[q] = zero;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (kc + T::b_k(tid + q * T::NT) + e >= p.K) rb[q][e] = 0.0f;
         }
     }
     if (p.pa != kGeneral) {
@@ -519,6 +528,38 @@ __device__ __forceinline__ void load_chunk_vectors(const ProductParams &p, Pipel
     for (int q = 0; q < T::B_F4; ++q) pl.rb[q] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rb, pl.b_off[q], 0, 0));
 }
 
+// The same through descriptors for a chunk of which an operand has to be loaded 4 bytes at a time.
+template <class T>
+__device__ __forceinline__ void load_chunk_words(const ProductParams &p, Pipeline<T> &pl, bool a_wide, bool b_wide)
+{
+    const uint64_t a_left = (uint64_t)(pl.a_end - pl.a_chunk) * 4, b_left = (uint64_t)(pl.b_end - pl.b_chunk) * 4;
+    const uint32_t a_lo = (uint32_t)a_left, b_lo = (uint32_t)b_left;
+    const uint32_t a_over = (uint32_t)(a_left >> 32) | (a_lo >> 31), b_over = (uint32_t)(b_left >> 32) | (b_lo >> 31);
+    const int a_bytes = a_over != 0 ? 0x7fffffff : (int)a_lo, b_bytes = b_over != 0 ? 0x7fffffff : (int)b_lo;
+    const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(pl.a_chunk), 0, a_bytes, kRawBufferFlags);
+    const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(pl.b_chunk), 0, b_bytes, kRawBufferFlags);
+#pragma unroll
+    for (int q = 0; q < T::A_F4; ++q) {
+        if (a_wide) {
+            pl.ra[q] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(ra, pl.a_off[q], 0, 0));
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)      // (the next element along the rows of the buffer, or the next row of it)
+                pl.ra[q][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ra, pl.a_off[q] + 4 * e, 0, 0));
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < T::B_F4; ++q) {
+        if (b_wide) {
+            pl.rb[q] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rb, pl.b_off[q], 0, 0));
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                pl.rb[q][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, pl.b_off[q] + 4 * e, 0, 0));
+        }
+    }
+}
+
 template <class T>
 __device__ __forceinline__ void advance_chunk(const ProductParams &p, Pipeline<T> &pl)
 {
@@ -536,8 +577,10 @@ __device__ __forceinline__ void fetch_chunk(const ProductParams &p, int block, i
     if (kind == kEdge) {
         load_a_checked<T>(p, pl.fw.r0, kc, tid, pl.ra);
         load_b_checked<T>(p, pl.fw.c0, kc, tid, pl.rb);
-    } else {
+    } else if (!T::WORDS || (pl.fw.a_load == 16 && pl.fw.b_load == 16)) {
         load_chunk_vectors<T>(p, pl);
+    } else {
+        load_chunk_words<T>(p, pl, pl.fw.a_load == 16, pl.fw.b_load == 16);
     }
     advance_chunk<T>(p, pl);
     pl.reg_kind = kind; pl.reg_r0 = pl.fw.r0; pl.reg_c0 = pl.fw.c0; pl.reg_kc = kc;

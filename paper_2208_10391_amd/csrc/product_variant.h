@@ -11,17 +11,27 @@ namespace mom {
 enum ProductVariant : int { kVariantNN = 0, kVariantTN = 1, kVariantNT = 2, kVariantTT = 3, kNumVariants };
 inline int product_variant(bool ta, bool tb) { return (ta ? 1 : 0) + (tb ? 2 : 0); }
 
-typedef hipError_t (*ProductLauncher)(int shape, const ProductBatch &batch, hipStream_t stream);
+// words: some operand of the batch has to be loaded 4 bytes at a time somewhere (see needs_words)
+typedef hipError_t (*ProductLauncher)(int shape, bool words, const ProductBatch &batch, hipStream_t stream);
 typedef hipError_t (*ProductConfigurer)();
 
-hipError_t launch_product_nn(int shape, const ProductBatch &batch, hipStream_t stream);
-hipError_t launch_product_tn(int shape, const ProductBatch &batch, hipStream_t stream);
-hipError_t launch_product_nt(int shape, const ProductBatch &batch, hipStream_t stream);
-hipError_t launch_product_tt(int shape, const ProductBatch &batch, hipStream_t stream);
+hipError_t launch_product_nn(int shape, bool words, const ProductBatch &batch, hipStream_t stream);
+hipError_t launch_product_tn(int shape, bool words, const ProductBatch &batch, hipStream_t stream);
+hipError_t launch_product_nt(int shape, bool words, const ProductBatch &batch, hipStream_t stream);
+hipError_t launch_product_tt(int shape, bool words, const ProductBatch &batch, hipStream_t stream);
 hipError_t configure_product_nn();
 hipError_t configure_product_tn();
 hipError_t configure_product_nt();
 hipError_t configure_product_tt();
+
+// Does the product need the kernel instance that can load 4 bytes at a time?  (An operand whose
+// rows are not 16-byte aligned, or whose contiguous extent is not a multiple of four while some
+// tile pokes over an edge; a row stride out of reach of 32-bit offsets takes the element-wise
+// path, which every instance has.)
+inline bool needs_words(const ProductParams &p)
+{
+    return (p.a_word && !(p.a_vec && p.a_tail)) || (p.b_word && !(p.b_vec && p.b_tail));
+}
 
 }  // namespace mom
 
@@ -30,8 +40,10 @@ hipError_t configure_product_tt();
 #define MOM_DEFINE_PRODUCT_VARIANT(NAME, TA, TB)                                                                     \
     namespace mom {                                                                                                  \
     namespace {                                                                                                      \
-    typedef TileConfig<128, 128, kChunk128, 2, 2, 2, TA, TB> Tile128;                                                \
-    typedef TileConfig<64, 64, kChunk64, 2, 2, 4, TA, TB> Tile64;                                                    \
+    typedef TileConfig<128, 128, kChunk128, 2, 2, 2, TA, TB, false> Tile128;                                         \
+    typedef TileConfig<64, 64, kChunk64, 2, 2, 4, TA, TB, false> Tile64;                                             \
+    typedef TileConfig<128, 128, kChunk128, 2, 2, 2, TA, TB, true> Tile128W;                                         \
+    typedef TileConfig<64, 64, kChunk64, 2, 2, 4, TA, TB, true> Tile64W;                                             \
     template <class T>                                                                                               \
     hipError_t launch_one(const ProductBatch &batch, hipStream_t stream)                                             \
     {                                                                                                                \
@@ -46,13 +58,17 @@ hipError_t configure_product_tt();
                                    hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);                        \
     }                                                                                                                \
     }                                                                                                                \
-    hipError_t launch_product_##NAME(int shape, const ProductBatch &batch, hipStream_t stream)                       \
+    hipError_t launch_product_##NAME(int shape, bool words, const ProductBatch &batch, hipStream_t stream)           \
     {                                                                                                                \
+        if (words)                                                                                                   \
+            return shape == kTile128 ? launch_one<Tile128W>(batch, stream) : launch_one<Tile64W>(batch, stream);     \
         return shape == kTile128 ? launch_one<Tile128>(batch, stream) : launch_one<Tile64>(batch, stream);           \
     }                                                                                                                \
     hipError_t configure_product_##NAME()                                                                            \
     {                                                                                                                \
-        const hipError_t e = raise_lds_limit<Tile128>();                                                             \
-        return e != hipSuccess ? e : raise_lds_limit<Tile64>();                                                      \
+        hipError_t e = raise_lds_limit<Tile128>();                                                                   \
+        if (e == hipSuccess) e = raise_lds_limit<Tile64>();                                                          \
+        if (e == hipSuccess) e = raise_lds_limit<Tile128W>();                                                        \
+        return e != hipSuccess ? e : raise_lds_limit<Tile64W>();                                                     \
     }                                                                                                                \
     }
