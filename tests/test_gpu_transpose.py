@@ -21,7 +21,7 @@ COMBOS = [(0, 0), (1, 0), (0, 1), (1, 1)]
 @pytest.mark.parametrize("ta,tb", COMBOS)
 @pytest.mark.parametrize("n", [33, 130, 300])
 def test_every_property_pair_transposed_ragged(ta, tb, n):
-    # several tiles plus a ragged tail, unaligned rows: the element-wise loaders
+    # several tiles plus a ragged tail, unaligned rows: loads 4 bytes wide through the bounded descriptors
     for pa, pb in PAIRS:
         m = n if pa != G else n + 7
         c = n if pb != G else max(n - 5, 1)
@@ -136,3 +136,29 @@ def test_transposed_trmm4096_whole_result(trans):
     torch.cuda.synchronize()
     want, _ = oracle.eval_plan(dims, props, [f.numpy() for f in host], plan.splits, trans=trans)
     assert_close_by_tiles(out.cpu().numpy(), want, G)
+
+
+LARGE_TILE_CASES = [
+    ([1801, 1803, 1799], [G, G]),     # 15 x 15 tiles of 128, nothing aligned: every load 4 bytes wide
+    ([2899, 2899, 2899], [L, G]),     # one triangle, 23 x 23 tiles, unaligned
+    ([2900, 2900, 2900], [G, U]),     # the same from the right, rows 16-byte aligned, ragged last tiles
+    ([4868, 4868, 4868], [L, L]),     # two triangles, 39 tile rows: a triangular or a general result
+]
+
+
+@pytest.mark.parametrize("ta,tb", COMBOS)
+@pytest.mark.parametrize("dims,props", LARGE_TILE_CASES)
+def test_large_tiles_in_every_orientation_ragged_and_unaligned(dims, props, ta, tb):
+    # sizes at which the 128 x 128 tile shape is chosen (the small cases above all run on 64 x 64 tiles):
+    # edges, diagonals and 4-byte loads of all four kernel orientations, whole results
+    trans = [ta, tb]
+    host = sc.make_chain(dims, props, 1950, trans=trans)
+    plan = mom.mom_chain_plan(dims, props, trans=trans)
+    rows, cols, prop = plan.result
+    dev = upload(host, props, poison=True)
+    out = torch.full((rows, cols), float("nan"), device="cuda")
+    mom.mom_chain_eval(plan, dev, out=out)
+    torch.cuda.synchronize()
+    want, want_prop = oracle.eval_plan(dims, props, [f.numpy() for f in host], plan.splits, trans=trans)
+    assert want_prop == prop
+    assert_close_by_tiles(out.cpu().numpy(), want, prop)
