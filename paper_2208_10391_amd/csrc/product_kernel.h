@@ -273,7 +273,7 @@ __device__ __forceinline__ TileWork tile_work(const ProductParams &p, int t, int
     // What a property or an edge makes special is always a run of chunks at the head and a
     // run at the tail of the k-range; the chunks in between are interior.
     w.f_lo = w.f_hi = 0;
-    if (w.a_load == 16 && w.b_load == 16) {
+    if (w.a_load != 0 && w.b_load != 0) {
         int k_from = klo, k_to = (p.K / T::BK) * T::BK;
         if (p.pa == kUpper) k_from = max(k_from, w.r0 + T::BM);
         if (p.pb == kLower) k_from = max(k_from, w.c0 + T::BN);
@@ -560,6 +560,17 @@ __device__ __forceinline__ void load_chunk_words(const ProductParams &p, Pipelin
     }
 }
 
+// Loads of a chunk that needs no element-wise path: 16 bytes at a time, or, in the instance that
+// knows how, 4 bytes at a time for the operands that need it.
+template <class T>
+__device__ __forceinline__ void load_chunk(const ProductParams &p, Pipeline<T> &pl)
+{
+    if (!T::WORDS || (pl.fw.a_load == 16 && pl.fw.b_load == 16))
+        load_chunk_vectors<T>(p, pl);
+    else
+        load_chunk_words<T>(p, pl, pl.fw.a_load == 16, pl.fw.b_load == 16);
+}
+
 template <class T>
 __device__ __forceinline__ void advance_chunk(const ProductParams &p, Pipeline<T> &pl)
 {
@@ -577,10 +588,8 @@ __device__ __forceinline__ void fetch_chunk(const ProductParams &p, int block, i
     if (kind == kEdge) {
         load_a_checked<T>(p, pl.fw.r0, kc, tid, pl.ra);
         load_b_checked<T>(p, pl.fw.c0, kc, tid, pl.rb);
-    } else if (!T::WORDS || (pl.fw.a_load == 16 && pl.fw.b_load == 16)) {
-        load_chunk_vectors<T>(p, pl);
     } else {
-        load_chunk_words<T>(p, pl, pl.fw.a_load == 16, pl.fw.b_load == 16);
+        load_chunk<T>(p, pl);
     }
     advance_chunk<T>(p, pl);
     pl.reg_kind = kind; pl.reg_r0 = pl.fw.r0; pl.reg_c0 = pl.fw.c0; pl.reg_kc = kc;
@@ -631,7 +640,7 @@ __device__ __forceinline__ void chunk_step(float *smem, const ProductParams &p, 
         if (kg == MOVE) {
             if (HOT) {
                 stage_to_lds<T>(An, Bn, tid, pl.ra, pl.rb);
-                load_chunk_vectors<T>(p, pl);
+                load_chunk<T>(p, pl);
                 advance_chunk<T>(p, pl);
             } else {
                 staged = pl.in_regs;
@@ -643,8 +652,9 @@ __device__ __forceinline__ void chunk_step(float *smem, const ProductParams &p, 
             }
         }
         if (HOT) mfma_group<T>(now, acc); else mfma_group_some<T>(now, acc, skip);
-        if (!HOT) {
-            // the general body is left to the compiler's own scheduling
+        if (!HOT || T::WORDS) {
+            // the general body, and the steady state of the instance with 4-byte loads (whose load count
+            // is only known at run time), are left to the compiler's own scheduling
         } else if (kg == MOVE) {
             __builtin_amdgcn_sched_group_barrier(kSchedLdsRead, NREAD, 0);
 #pragma unroll
