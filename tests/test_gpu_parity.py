@@ -364,3 +364,13 @@ def test_row_stride_beyond_the_reach_of_32_bit_offsets():
     assert rel_fro(out.cpu().numpy(), want.T) <= TOL
     del wide, a_dev
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("dims", [[128, 130, 62], [128, 130, 192], [256, 258, 254], [2944, 130, 2814]])
+def test_aligned_row_stride_with_extents_that_are_not_multiples_of_four(dims):
+    # two NaN-filled columns of padding make every row stride a multiple of four while the extents are
+    # not: interior tiles load 16 bytes at a time and the group that straddles the end of k is cut by
+    # the descriptor in the matrix's last row (its tail lies past the last element) and by the staging
+    # mask elsewhere; tiles that poke over the right edge load 4 bytes at a time.  The last case takes
+    # the 128 x 128 tiles.
+    check_against_dense(dims, [G, G], sc.make_chain(dims, [G, G], 4100 + dims[0]), pad_cols=2)
