@@ -8,8 +8,9 @@
 //     of its diagonal tiles (only the triangle is written).
 // This is the non-rectangular iteration space that Sec. 5 of the paper names as future work.
 //
-// Data path: global -> registers (16-byte loads, two chunks ahead) -> LDS (two stages, one
-// barrier per chunk) -> MFMA operands (read one group of 8 k-values ahead).
+// Data path: global -> registers (16-byte loads through buffer descriptors that end with the
+// matrix, two chunks ahead) -> LDS (two stages, one barrier per chunk) -> MFMA operands (read one
+// group of 8 k-values ahead).
 // v_mfma_f32_32x32x2_f32 computes D = X * Y + D with lane l supplying X[i = l%32][k = l/32] and
 // Y[k = l/32][j = l%32]; register v of lane l holds D[8*(v/4) + 4*(l/32) + v%4][l%32].  The kernel
 // feeds it the transposed problem, X = B^T and Y = A^T, so that D = C^T: a lane then owns one row
@@ -120,9 +121,10 @@ struct TileConfig {
     static __device__ __forceinline__ int b_k(int idx) { return TB ? (idx % (BK / 4)) * 4 : idx / (BN / 4); }
 };
 
-// Element-wise loads of one k-chunk for the edges of a matrix, for rows that are not 16-byte
-// aligned and for row strides too long for 32-bit offsets: bounds-checked and predicated on the
-// structure, so nothing outside the matrix or the triangle is touched; 64-bit addresses.
+// Element-wise loads of one k-chunk for row strides too long for 32-bit offsets (and, in the
+// instance without the 4-byte descriptor loads, for whatever else cannot be loaded 16 bytes at a
+// time): bounds-checked and predicated on the structure, so nothing outside the matrix or the
+// triangle is touched; 64-bit addresses.
 template <class T>
 __device__ __forceinline__ void load_a_checked(const ProductParams &p, int r0, int kc, int tid, f32x4 (&ra)[T::A_F4])
 {
