@@ -114,10 +114,12 @@ def test_two_triangular_operands_on_small_tiles_whole_result(pa, pb, n):
 
 
 @pytest.mark.parametrize("dims,props", [([4000, 4000, 200], [U, G]), ([200, 4000, 4000], [G, L]),
-                                        ([4000, 4000, 200], [L, G]), ([200, 4000, 4000], [G, U])])
+                                        ([4000, 4000, 200], [L, G]), ([200, 4000, 4000], [G, U]),
+                                        ([3999, 3999, 199], [U, G]), ([199, 3999, 3999], [G, L])])
 def test_split_k_with_one_triangular_operand_whole_result(dims, props):
-    # 64 tiles and 125 chunks: split-K; with U * G and G * L every slice of a tile's clipped k-range is
-    # walked from its far end, and the last chunk of the range is ragged
+    # fewer than 256 tiles and 125 chunks: split-K; with U * G and G * L every slice of a tile's clipped
+    # k-range is walked from its far end, and the last chunk of the range is ragged; the last two cases
+    # have nothing 16-byte aligned (4-byte loads)
     plan = run_whole(dims, props, sc.make_chain(dims, props, 78), reference="dense")
     assert mom.mom_plan_num_launches(plan) == 2
 
