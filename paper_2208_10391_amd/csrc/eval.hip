@@ -197,7 +197,11 @@ mom_status_t eval_chain(const mom_plan_t *plan, const float *const *d_factors, c
             ProductParams &p = batch.prob[i];
             // (the column count only matters for temporaries, which are never stored transposed)
             const Resolved a = resolve(st.a, st.k), b = resolve(st.b, st.n), c = resolve(st.c, st.n);
-            p.A = a.ptr; p.B = b.ptr; p.C = const_cast<float *>(c.ptr);
+            // (a sub-product of the result's rows from row0 on: the same rows of A, which are columns of
+            // its buffer when that holds the transpose)
+            const int64_t row0 = pl.row0[i];
+            p.A = a.ptr + ((pl.variant & 1) ? row0 : row0 * a.ld); p.B = b.ptr;
+            p.C = const_cast<float *>(c.ptr) + row0 * c.ld;
             p.lda = a.ld; p.ldb = b.ld; p.ldc = c.ld;
             // (a row stride of 2^22 elements or more leaves the reach of the kernel's 32-bit offsets)
             p.a_vec = aligned16(a.ptr, a.ld) && a.ld < (1 << 22);
@@ -220,7 +224,7 @@ mom_status_t eval_chain(const mom_plan_t *plan, const float *const *d_factors, c
                 const int slot = pl.reduce_of[i];
                 const Resolved c = resolve(plan->steps[pl.step[slot]].c, plan->steps[pl.step[slot]].n);
                 reduce.prob[i].P = batch.prob[slot].C;
-                reduce.prob[i].C = const_cast<float *>(c.ptr);
+                reduce.prob[i].C = const_cast<float *>(c.ptr) + pl.row0[slot] * c.ld;
                 reduce.prob[i].ldc = c.ld;
             }
             hipLaunchKernelGGL(reduce_slices_kernel, dim3(pl.reduce_grid_x, reduce.count), dim3(256), 0, stream, reduce);

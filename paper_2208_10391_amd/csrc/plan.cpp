@@ -328,6 +328,38 @@ mom_status_t lay_out_launches(mom_plan *plan)
             pl.kind = kLaunchProduct;
             pl.shape = choose_launch(plan->steps[order[first]]).shape;
             pl.variant = (plan->steps[order[first]].ta ? 1 : 0) + (plan->steps[order[first]].tb ? 2 : 0);
+            {   // a product whose last round of tiles is cut along k: two sub-products, one launch
+                const ProductStep &st = plan->steps[order[first]];
+                const Launch L = choose_launch(st);
+                const Tail tail = choose_tail(st, L);
+                if (tail.tile_rows_main > 0) {
+                    done[first - next] = 1;
+                    const int64_t rows_main = (int64_t)tail.tile_rows_main * L.bm;
+                    for (int slot = 0; slot < 2; ++slot) {
+                        pl.step[slot] = order[first];
+                        pl.row0[slot] = slot ? rows_main : 0;
+                        ProductParams &p = pl.batch.prob[slot];
+                        p.M = (int)(slot ? st.m - rows_main : rows_main); p.N = (int)st.n; p.K = (int)st.k;
+                        p.pa = st.pa; p.pb = st.pb; p.pc = st.pc;
+                        p.tiles_m = slot ? L.tiles_m - tail.tile_rows_main : tail.tile_rows_main;
+                        p.tiles_n = L.tiles_n; p.num_tiles = p.tiles_m * p.tiles_n;
+                        p.order = L.order; p.paired = 0; p.mirrored = 0; p.k_walk = 0; p.folded = 0;
+                        p.grid = slot ? p.num_tiles : std::min(p.num_tiles, 2 * kComputeUnits);
+                        p.split_k = slot ? tail.split : 1;
+                        p.slice_stride = slot ? (int64_t)p.M * p.N : 0;
+                        const int64_t blocks = (int64_t)(slot ? pl.batch.block_end[0] : 0) + (int64_t)p.grid * p.split_k;
+                        pl.batch.block_end[pl.batch.count++] = (int)blocks;
+                    }
+                    ReduceParams &r = pl.reduce.prob[0];
+                    pl.reduce_of[0] = 1;
+                    pl.reduce.count = 1;
+                    r.slice_stride = pl.batch.prob[1].slice_stride;
+                    r.slices = tail.split; r.M = pl.batch.prob[1].M; r.N = pl.batch.prob[1].N; r.pc = st.pc;
+                    pl.reduce_grid_x = (unsigned)std::min<int64_t>((((int64_t)r.M * r.N + 3) / 4 + 31) / 32, 8192);
+                    plan->launches.push_back(pl);
+                    continue;
+                }
+            }
             int64_t reduce_quads = 0;
             bool batch_small = true;
             for (size_t i = first; i < level_end && pl.batch.count < kMaxFused; ++i) {
@@ -435,7 +467,8 @@ mom_status_t finish(mom_plan *plan, const std::vector<int64_t> &d, const std::ve
             plan->order.push_back((int32_t)i);
             if (st.c.where == mom::Where::Temp) plan->temps[st.c.index].offset = arena.alloc(plan->temps[st.c.index].bytes);
             st.scratch_offset = level_scratch;
-            level_scratch += (mom::choose_launch(st).scratch_bytes + 255) & ~(size_t)255;
+            const mom::Launch L = mom::choose_launch(st);
+            level_scratch += (L.scratch_bytes + mom::choose_tail(st, L).scratch_bytes + 255) & ~(size_t)255;
         }
         scratch = std::max(scratch, level_scratch);
         for (const mom::ProductStep &st : plan->steps) {

@@ -49,6 +49,7 @@ struct PlannedLaunch {
     int shape;                       // TileShape of the product kernel
     int variant;                     // which operands are stored transposed (ProductVariant)
     int step[kMaxFused];             // index into mom_plan::steps of batch.prob[i]
+    int64_t row0[kMaxFused];         // batch.prob[i] is the sub-product of the result's rows from row0 on (see choose_tail)
     ProductBatch batch;              // geometry complete; A, B, C, ld*, *_vec patched per call
     ReduceBatch reduce;              // count == 0: no product of this launch is split
     int reduce_of[kMaxFused];        // reduce.prob[i] sums the slices of batch.prob[reduce_of[i]]

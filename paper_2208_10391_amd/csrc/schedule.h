@@ -180,4 +180,42 @@ inline Launch choose_launch(const ProductStep &st)
     return L;
 }
 
+// The last round of a general * general product on 128x128 tiles.  Its tiles are all equally long,
+// and a compute unit multiplies as fast with one workgroup as with two, so the product takes
+// ceil(tiles / 256) tile times: when the tile count is a little above a multiple of 256, the last few
+// tiles run on a few compute units while the rest of the chip waits (576 tiles: 2.25 per unit,
+// 72 % of the peak; 2304 tiles: 9 per unit, 96 %).  Such a product is cut into two sub-products
+// along the rows of the result: the first tile rows, a whole number of tiles per unit, and the
+// remaining tile rows, whose tiles are cut along k into as many slices as fill the chip once
+// (their partial sums are added by the slice-sum kernel).  Both run in one launch.  Only when the
+// idle part of the last round is worth at least 24 chunk times per compute unit (some 40 us) and
+// the tail is small: the slices cost a second launch and traffic.
+struct Tail {
+    int tile_rows_main;    // 0: the product is not cut
+    int split;             // k-slices of the tail's tiles
+    size_t scratch_bytes;  // split * (rows of the tail) * n floats
+};
+
+inline Tail choose_tail(const ProductStep &st, const Launch &L)
+{
+    Tail t{0, 1, 0};
+    const int resident = 2 * kComputeUnits;
+    const int chunks = (int)((st.k + kChunk128 - 1) / kChunk128);
+    if (L.shape != kTile128 || L.order != kRowMajor || L.split_k != 1 || L.num_tiles <= kComputeUnits || chunks < 32)
+        return t;
+    const int per_unit = L.num_tiles / kComputeUnits, rounds_up = (L.num_tiles + kComputeUnits - 1) / kComputeUnits;
+    const int64_t idle_tiles = (int64_t)rounds_up * kComputeUnits - L.num_tiles;
+    if (idle_tiles * chunks < (int64_t)24 * kComputeUnits) return t;      // the last round is full enough, or k short
+    const int main_rows = (int)(((int64_t)per_unit * kComputeUnits) / L.tiles_n);
+    if (main_rows < 1 || main_rows >= L.tiles_m) return t;
+    const int tail_tiles = (L.tiles_m - main_rows) * L.tiles_n;
+    if (tail_tiles > kComputeUnits * 5 / 8) return t;      // (measured: a tail of 182 tiles loses, one of 160 gains)
+    const int split = std::min((resident + tail_tiles - 1) / tail_tiles, chunks / kMinChunksPerSlice);
+    if (split < 2) return t;
+    t.tile_rows_main = main_rows;
+    t.split = split;
+    t.scratch_bytes = (size_t)split * (size_t)(st.m - (int64_t)main_rows * 128) * (size_t)st.n * sizeof(float);
+    return t;
+}
+
 }  // namespace mom

@@ -124,6 +124,16 @@ def test_split_k_with_one_triangular_operand_whole_result(dims, props):
     assert mom.mom_plan_num_launches(plan) == 2
 
 
+@pytest.mark.parametrize("dims", [[3072, 1024, 3072], [3000, 1100, 2900], [3001, 1027, 2999]])
+def test_last_round_of_equal_tiles_is_cut_along_k_whole_result(dims):
+    # 24 x 24 = 576 (or 24 x 23 = 552) equal tiles of 128: one round of 512 and a few left over; the
+    # last tile rows form a sub-product of their own whose tiles are cut into k-slices, in the same
+    # launch, and a slice-sum launch follows; ragged and unaligned variants
+    props = [G, G]
+    plan = run_whole(dims, props, sc.make_chain(dims, props, 82), reference="dense")
+    assert mom.mom_plan_num_launches(plan) == 2
+
+
 def test_persistent_grid_whole_result():
     # 24 x 24 = 576 equal tiles > 512 resident workgroups, k = 288 >= 256: every workgroup
     # strides over the tiles, some take two
