@@ -312,3 +312,26 @@ def test_operands_of_a_shared_launch_stay_alive_until_it_runs():
     assert plan.workspace_bytes >= (256 + 2 + 128) * mib
     levels = [mom.mom_plan_product(plan, i)["level"] for i in range(4)]
     assert levels == [1, 3, 3, 4]                 # the absorbed product stands at its consumer's level (3)
+
+
+def test_launch_layout_of_the_chooser():
+    """How many launches the planner lays out (host logic only): one per product or fused level,
+    plus one slice-sum launch wherever tiles are cut along k."""
+    cases = [
+        ([4096, 4096, 4096], [L, G], 1),           # 1024 tiles in 512 pairs
+        ([3072, 288, 3072], [G, G], 1),            # 576 equal tiles, k too short to cut the last round
+        ([3072, 1024, 3072], [G, G], 2),           # 576 = 2.25 tiles per compute unit: last three tile rows cut along k
+        ([6144, 1024, 6144], [G, G], 1),           # 2304 = 9 per compute unit: nothing to gain
+        ([3328, 3328, 3328], [G, G], 1),           # a tail of 182 tiles is too large to be worth cutting
+        ([64, 4096, 64], [G, G], 2),               # one small tile, long k: k-slices
+        ([1024, 1024, 1024], [G, G], 1),           # 256 tiles of 64 x 64
+        ([2048, 2048, 256], [L, G], 2),            # 128 small tiles, 64 chunks: k-slices
+        ([2048, 2048, 2048], [L, L], 1),           # 528 small tiles
+        ([8192, 512, 8192, 64, 4096, 2048], [G] * 5, 3),      # two products and their slice sum, then (X Y) Z in one
+        ([256, 1024, 4096, 256, 256], [G, G, G, L], 4),
+    ]
+    for dims, props, want in cases:
+        plan = mom.mom_chain_plan(dims, props)
+        assert mom.mom_plan_num_launches(plan) == want, (dims, props, mom.mom_plan_num_launches(plan))
+        # the workspace covers the slices: never smaller than the temporaries alone
+        assert plan.workspace_bytes >= 0
